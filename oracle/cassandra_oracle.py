@@ -1,0 +1,505 @@
+"""Plain CPU oracle for the Cassandra self-speculative decode path.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of
+what the path computes, written from the paper; the HIP library shares no code
+with it and never calls it.  Only tests/, the smoke check and the bench's
+cpu_baseline leg may import it.
+
+Every function cites the passage of the paper it follows (section / equation /
+figure).  Floating point is float64 unless stated; bf16 tensors are uint16 bit
+patterns.  Nothing here is blocked, fused or reordered beyond the definition.
+
+Parity pins (tests/test_oracle_*.py): exhaustive bit-exact round trip over all
+65536 bf16 patterns, bit-prefix property of truncation, kept count, brute-force
+subset search for the selection, closed-form stream sizes, library matmul /
+attention special cases, brute-force acceptance, and speculative == plain token
+streams.  Parity unpinned: acceptance *rates* and speedups (the paper's tables
+for them are images that did not survive, and need trained weights).
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+
+import numpy as np
+
+BF16_BITS = 16  # 1 sign + 8 exponent + 7 mantissa (Sec. 4.2, "Exponent Compression")
+
+
+# ----------------------------------------------------------------------------
+# bf16 <-> float helpers
+# ----------------------------------------------------------------------------
+def bf16_to_f64(u16):
+    """Exact widening of bf16 bit patterns to float64."""
+    u = np.asarray(u16, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16(x):
+    """Round a real value to bf16, nearest-even (via float32; both roundings RNE)."""
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    b = np.ascontiguousarray(f).view(np.uint32).astype(np.uint64)
+    nan = np.isnan(f)
+    r = ((b + np.uint64(0x7FFF) + ((b >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16))
+    r = np.where(nan, (b >> np.uint64(16)) | np.uint64(0x40), r)
+    return r.astype(np.uint16)
+
+
+def round_bf16(x):
+    """Value of x after rounding to bf16 (as float64)."""
+    return bf16_to_f64(f64_to_bf16(x))
+
+
+# ----------------------------------------------------------------------------
+# Selection (Sec. 4.2 "Unstructured Value Pruning")
+# ----------------------------------------------------------------------------
+def kept_count(group: int, keep_permille: int) -> int:
+    """Number of kept values in a group of `group` elements."""
+    k = (keep_permille * group + 500) // 1000
+    return max(0, min(group, k))
+
+
+def weight_scores(w_u16, act_norm=None):
+    """Importance score bits of every weight.
+
+    With activation norms a_j: score = |W_ij| * a_j as one float32 multiply
+    (activation-aware rule of Sec. 4.2), compared by its uint32 pattern.
+    Without: the 15-bit magnitude pattern of the bf16 (pure magnitude).
+    """
+    w = np.asarray(w_u16, dtype=np.uint16)
+    mag = (w & np.uint16(0x7FFF))
+    if act_norm is None:
+        return mag.astype(np.uint32)
+    a = np.asarray(act_norm, dtype=np.float32)
+    absw = (mag.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    with np.errstate(invalid="ignore", over="ignore"):
+        s = (absw * a[None, :]).astype(np.float32)
+    bits = s.view(np.uint32).copy()
+    bits[np.isnan(s)] = np.uint32(0x7FFFFFFF)
+    return bits
+
+
+def kv_scores(v_u16):
+    """Per-token magnitude score for KV vectors (Sec. 4.2): the 15-bit magnitude."""
+    return (np.asarray(v_u16, dtype=np.uint16) & np.uint16(0x7FFF)).astype(np.uint32)
+
+
+def select_topk(score_bits, k: int):
+    """Keep the k highest scores of each row (last axis); equal scores go to the
+    lower index.  Returns a bool mask of the same shape."""
+    s = np.asarray(score_bits, dtype=np.uint32)
+    g = s.shape[-1]
+    flat = s.reshape(-1, g)
+    mask = np.zeros(flat.shape, dtype=bool)
+    if k <= 0:
+        return mask.reshape(s.shape)
+    # total order: higher score first, then lower index first
+    key = (flat.astype(np.uint64) << np.uint64(32)) | (np.uint64(g - 1) - np.arange(g, dtype=np.uint64))[None, :]
+    order = np.argsort(key, axis=1, kind="stable")  # ascending; keys are unique
+    top = order[:, g - k:]
+    np.put_along_axis(mask, top, True, axis=1)
+    return mask.reshape(s.shape)
+
+
+# ----------------------------------------------------------------------------
+# Truncation / split (Sec. 4.2 "Mantissa Truncation", Sec. 4.1)
+# ----------------------------------------------------------------------------
+def split_word(w_u16, t: int):
+    """hi = the 16-t leading bits (sign, exponent, leading mantissa bits), lo = the t
+    dropped mantissa bits.  No rounding: hi is a bit-prefix of the word."""
+    w = np.asarray(w_u16, dtype=np.uint16)
+    hi = (w >> np.uint16(t)).astype(np.uint16)
+    lo = (w & np.uint16((1 << t) - 1)).astype(np.uint16)
+    return hi, lo
+
+
+# ----------------------------------------------------------------------------
+# Packed representation: bitmap + speculation stream + verification streams
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass
+class Packed:
+    """One matrix whose rows are selection groups with exactly K kept values each.
+
+    bitmap[r, c//32] bit c%32       : column c of row r is kept (Sec. 5.1, bitmap
+                                      de-sparsification)
+    spec[r]   : K fields of 16-t bits, ascending column order, field e at bit e*(16-t)
+    lo[r]     : K fields of t bits (the truncated mantissa bits of the kept values)
+    pruned[r] : cols-K full 16-bit words (the unselected values, ascending column)
+    Streams are little-endian bit streams stored in uint32 words; each row starts
+    on a word boundary.  spec (+bitmap) is the speculation data, lo+pruned the
+    verification data (Sec. 4.1).
+    """
+    rows: int
+    cols: int
+    K: int
+    t: int
+    bitmap: np.ndarray
+    spec: np.ndarray
+    lo: np.ndarray
+    pruned: np.ndarray
+
+
+def _words(bits: int) -> int:
+    return (bits + 31) // 32
+
+
+def stream_words(cols: int, K: int, t: int):
+    """(bitmap, spec, lo, pruned) words per row; closed form of the byte accounting
+    behind Eq. 2's denominator, plus the bitmap the equation leaves out."""
+    return _words(cols), _words(K * (BF16_BITS - t)), _words(K * t), _words((cols - K) * 16)
+
+
+def _pack_fields(fields, width: int, nwords: int):
+    """fields [rows, m] of `width` bits -> uint32 [rows, nwords] little-endian bit stream."""
+    rows, m = fields.shape
+    if nwords == 0:
+        return np.zeros((rows, 0), dtype=np.uint32)
+    out = np.zeros((rows, nwords * 32), dtype=np.uint8)
+    if m and width:
+        f = fields.astype(np.uint32)
+        bits = ((f[:, :, None] >> np.arange(width, dtype=np.uint32)[None, None, :]) & 1).astype(np.uint8)
+        out[:, : m * width] = bits.reshape(rows, m * width)
+    packed = np.packbits(out, axis=1, bitorder="little")
+    return np.ascontiguousarray(packed).view("<u4").astype(np.uint32)
+
+
+def _unpack_fields(words, width: int, m: int):
+    rows = words.shape[0]
+    if m == 0 or width == 0:
+        return np.zeros((rows, m), dtype=np.uint16)
+    by = np.ascontiguousarray(words.astype("<u4")).view(np.uint8)
+    bits = np.unpackbits(by, axis=1, bitorder="little")[:, : m * width].reshape(rows, m, width)
+    weights = (1 << np.arange(width, dtype=np.uint32))
+    return (bits.astype(np.uint32) * weights[None, None, :]).sum(axis=2).astype(np.uint16)
+
+
+def pack(w_u16, mask, t: int) -> Packed:
+    """Write the split of Sec. 4.1/4.2 into the packed streams."""
+    w = np.asarray(w_u16, dtype=np.uint16)
+    rows, cols = w.shape
+    counts = mask.sum(axis=1)
+    K = int(counts[0]) if rows else 0
+    assert (counts == K).all(), "every row must keep the same number of values"
+    bw, sw, lw, pw = stream_words(cols, K, t)
+    hi, lo = split_word(w, t)
+    # row-major boolean indexing keeps ascending column order inside each row
+    hi_k = hi[mask].reshape(rows, K)
+    lo_k = lo[mask].reshape(rows, K)
+    pr = w[~mask].reshape(rows, cols - K)
+    bm = np.zeros((rows, bw * 32), dtype=np.uint8)
+    bm[:, :cols] = mask
+    bitmap = np.ascontiguousarray(np.packbits(bm, axis=1, bitorder="little")).view("<u4").astype(np.uint32)
+    return Packed(rows, cols, K, t, bitmap,
+                  _pack_fields(hi_k, BF16_BITS - t, sw),
+                  _pack_fields(lo_k, t, lw),
+                  _pack_fields(pr, 16, pw))
+
+
+def unpack_mask(p: Packed):
+    by = np.ascontiguousarray(p.bitmap.astype("<u4")).view(np.uint8)
+    return np.unpackbits(by, axis=1, bitorder="little")[:, : p.cols].astype(bool)
+
+
+def decode_draft(p: Packed):
+    """Draft reconstruction (Sec. 4.1): speculation data with zero padding -- kept
+    values get their leading bits back with the dropped mantissa bits as 0, pruned
+    positions read +0."""
+    mask = unpack_mask(p)
+    hi = _unpack_fields(p.spec, BF16_BITS - p.t, p.K)
+    out = np.zeros((p.rows, p.cols), dtype=np.uint16)
+    out[mask] = (hi.astype(np.uint32) << p.t).astype(np.uint16).reshape(-1)
+    return out
+
+
+def decode_full(p: Packed):
+    """Target reconstruction (Sec. 4.1, Sec. 5.1 mantissa concatenation): leading and
+    dropped mantissa bits concatenated, pruned values merged back through the bitmap."""
+    mask = unpack_mask(p)
+    hi = _unpack_fields(p.spec, BF16_BITS - p.t, p.K)
+    lo = _unpack_fields(p.lo, p.t, p.K)
+    pr = _unpack_fields(p.pruned, 16, p.cols - p.K)
+    out = np.zeros((p.rows, p.cols), dtype=np.uint16)
+    out[mask] = ((hi.astype(np.uint32) << p.t) | lo).astype(np.uint16).reshape(-1)
+    out[~mask] = pr.reshape(-1)
+    return out
+
+
+def encode_weight(w_u16, keep_permille: int, t: int, act_norm=None) -> Packed:
+    """Offline weight formatting (Sec. 5.1 last paragraph): per output row, keep the
+    K best-scoring inputs (Sec. 4.2), truncate, split, pack."""
+    w = np.asarray(w_u16, dtype=np.uint16)
+    K = kept_count(w.shape[1], keep_permille)
+    mask = select_topk(weight_scores(w, act_norm), K)
+    return pack(w, mask, t)
+
+
+def encode_kv(v_u16, keep_permille: int, t: int) -> Packed:
+    """Online KV formatting (Sec. 5.1 encoder, Sec. 4.2 per-token magnitude pruning):
+    rows are (token, head) vectors of head_dim values; K largest magnitudes kept."""
+    v = np.asarray(v_u16, dtype=np.uint16)
+    K = kept_count(v.shape[1], keep_permille)
+    mask = select_topk(kv_scores(v), K)
+    return pack(v, mask, t)
+
+
+# ----------------------------------------------------------------------------
+# GEMV / GEMM on reconstructed data (Sec. 4.1: ordinary FP units on bf16)
+# ----------------------------------------------------------------------------
+def gemv(w_u16, x_u16):
+    """y = W x with W, x widened from bf16; one column; float64."""
+    return bf16_to_f64(w_u16) @ bf16_to_f64(x_u16)
+
+
+def gemv_draft(p: Packed, x_u16):
+    """Draft GEMV: weights are the zero-padded speculation data (Sec. 4.1)."""
+    return gemv(decode_draft(p), x_u16)
+
+
+def gemm_verify(p: Packed, X_u16):
+    """Verification GEMM (Sec. 2.2 batched verification, Sec. 4.1 full reconstruction):
+    X is [ncols, n]; every column goes through the same one-column routine as plain
+    decoding.  Returns [ncols, rows]."""
+    w = decode_full(p)
+    return np.stack([gemv(w, X_u16[c]) for c in range(X_u16.shape[0])], axis=0)
+
+
+# ----------------------------------------------------------------------------
+# Attention (Fig. 2_1 structure; Sec. 4.1 for which KV data each pass sees)
+# ----------------------------------------------------------------------------
+def attention_one(q, Kmat, Vmat):
+    """softmax(q K^T / sqrt(d)) V for one query vector; q [d], K,V [T,d] float64."""
+    d = q.shape[0]
+    s = (Kmat @ q) / math.sqrt(d)
+    s = s - s.max()
+    p = np.exp(s)
+    p = p / p.sum()
+    return p @ Vmat
+
+
+def attention(q_u16, k_u16, v_u16, n_q_heads: int, n_kv_heads: int):
+    """q [n_q_heads, d] bf16; k, v [T, n_kv_heads, d] bf16 (already reconstructed for
+    the pass at hand).  Grouped-query: q head h reads kv head h // (nq/nkv).
+    Returns bf16 [n_q_heads, d]."""
+    q = bf16_to_f64(q_u16)
+    k = bf16_to_f64(k_u16)
+    v = bf16_to_f64(v_u16)
+    grp = n_q_heads // n_kv_heads
+    out = np.zeros_like(q)
+    for h in range(n_q_heads):
+        out[h] = attention_one(q[h], k[:, h // grp, :], v[:, h // grp, :])
+    return f64_to_bf16(out)
+
+
+# ----------------------------------------------------------------------------
+# Llama-3 style decoder ops; every tensor crossing an op boundary is bf16
+# ----------------------------------------------------------------------------
+def rmsnorm(h_u16, g_u16, eps: float):
+    x = bf16_to_f64(h_u16)
+    r = 1.0 / math.sqrt(float(np.mean(x * x)) + eps)
+    return f64_to_bf16(x * r * bf16_to_f64(g_u16))
+
+
+def rope(x_u16, pos: int, table):
+    """Rotate pairs (i, i + d/2) of each head by the angle of `pos`; table is
+    [max_pos, d/2, 2] cos/sin float32 (an input shared as data)."""
+    x = bf16_to_f64(x_u16)
+    half = x.shape[-1] // 2
+    c = table[pos, :, 0].astype(np.float64)
+    s = table[pos, :, 1].astype(np.float64)
+    a, b = x[..., :half], x[..., half:]
+    return f64_to_bf16(np.concatenate([a * c - b * s, b * c + a * s], axis=-1))
+
+
+def swiglu(gate_f64, up_f64):
+    g = round_bf16(gate_f64)
+    u = round_bf16(up_f64)
+    return f64_to_bf16(g / (1.0 + np.exp(-g)) * u)
+
+
+def add_bf16(h_u16, y_f64):
+    return f64_to_bf16(bf16_to_f64(h_u16) + round_bf16(y_f64))
+
+
+def argmax_lowest(logits):
+    return int(np.argmax(logits))  # numpy returns the first (lowest) index among maxima
+
+
+# ----------------------------------------------------------------------------
+# Model container and the two passes
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass
+class KVStore:
+    """Compressed cache of one layer: one Packed per committed token for K and for V
+    (rows = kv heads).  Kept as lists so the oracle stays a direct transcription."""
+    k: list
+    v: list
+
+
+class OracleModel:
+    """Weights in Cassandra format + compressed KV cache + the passes of Sec. 4.1.
+
+    shape: object with hidden, n_layers, n_q_heads, n_kv_heads, head_dim, ffn,
+    vocab, rms_eps.  weights: dict as produced by synth.model_weights.  All linear
+    layers including the output head are stored encoded; embedding and norm gains
+    stay bf16.
+    """
+
+    def __init__(self, shape, weights, rope_tab, w_keep=600, w_t=4, kv_keep=600, kv_t=4,
+                 act_norms=None):
+        self.s = shape
+        self.rope_tab = rope_tab
+        self.kv_keep, self.kv_t = kv_keep, kv_t
+        self.embed = weights["embed"]
+        self.g_final = weights["g_final"]
+        an = act_norms or {}
+        self.layers = []
+        for li, lw in enumerate(weights["layers"]):
+            enc = {}
+            for name in ("wqkv", "wo", "wgu", "wd"):
+                enc[name] = encode_weight(lw[name], w_keep, w_t, an.get((li, name)))
+            enc["g_attn"], enc["g_ffn"] = lw["g_attn"], lw["g_ffn"]
+            self.layers.append(enc)
+        self.lm_head = encode_weight(weights["lm_head"], w_keep, w_t, an.get("lm_head"))
+        # decoded views (the reconstruction is exact/defined; cache it for speed)
+        self._dec = {}
+        self.cache = [KVStore([], []) for _ in range(shape.n_layers)]
+
+    # -- reconstruction of weights for a pass
+    def W(self, layer, name, draft: bool):
+        key = (layer, name, draft)
+        if key not in self._dec:
+            p = self.lm_head if layer is None else self.layers[layer][name]
+            self._dec[key] = bf16_to_f64(decode_draft(p) if draft else decode_full(p))
+        return self._dec[key]
+
+    def cache_len(self):
+        return len(self.cache[0].k)
+
+    def _cache_kv(self, layer, draft: bool):
+        st = self.cache[layer]
+        dec = decode_draft if draft else decode_full
+        if not st.k:
+            z = np.zeros((0, self.s.n_kv_heads, self.s.head_dim), dtype=np.uint16)
+            return z, z.copy()
+        return (np.stack([dec(p) for p in st.k]), np.stack([dec(p) for p in st.v]))
+
+    def forward(self, tokens, draft: bool, extra_kv=None):
+        """Run the columns `tokens` (ids) at positions cache_len + len(extra) + c.
+
+        draft=True : speculation data only for weights and cache (Sec. 4.1 draft
+                     inference); extra_kv carries the uncompressed K/V of earlier
+                     in-flight draft tokens per layer.
+        draft=False: full reconstruction (Sec. 4.1 target inference); columns see the
+                     cache and the exact K/V of the earlier columns of this call.
+        Returns (logits [ncols, vocab] float64, new_kv per layer: list of (k, v) bf16
+        [ncols, n_kv_heads, d])."""
+        s = self.s
+        nc = len(tokens)
+        base = self.cache_len() + (0 if extra_kv is None else extra_kv[0][0].shape[0])
+        h = [self.embed[int(tk)].copy() for tk in tokens]
+        new_kv = []
+        for li in range(s.n_layers):
+            L = self.layers[li]
+            ck, cv = self._cache_kv(li, draft)
+            if extra_kv is not None:
+                ck = np.concatenate([ck, extra_kv[li][0]], axis=0)
+                cv = np.concatenate([cv, extra_kv[li][1]], axis=0)
+            nk = np.zeros((nc, s.n_kv_heads, s.head_dim), dtype=np.uint16)
+            nv = np.zeros_like(nk)
+            for c in range(nc):
+                xn = rmsnorm(h[c], L["g_attn"], s.rms_eps)
+                qkv = f64_to_bf16(self.W(li, "wqkv", draft) @ bf16_to_f64(xn))
+                q = qkv[: s.q_dim].reshape(s.n_q_heads, s.head_dim)
+                k = qkv[s.q_dim: s.q_dim + s.kv_dim].reshape(s.n_kv_heads, s.head_dim)
+                v = qkv[s.q_dim + s.kv_dim:].reshape(s.n_kv_heads, s.head_dim)
+                q = rope(q, base + c, self.rope_tab)
+                k = rope(k, base + c, self.rope_tab)
+                nk[c], nv[c] = k, v
+                kk = np.concatenate([ck, nk[: c + 1]], axis=0)
+                vv = np.concatenate([cv, nv[: c + 1]], axis=0)
+                o = attention(q, kk, vv, s.n_q_heads, s.n_kv_heads).reshape(-1)
+                h[c] = add_bf16(h[c], self.W(li, "wo", draft) @ bf16_to_f64(o))
+                xn2 = rmsnorm(h[c], L["g_ffn"], s.rms_eps)
+                gu = self.W(li, "wgu", draft) @ bf16_to_f64(xn2)
+                act = swiglu(gu[0::2], gu[1::2])
+                h[c] = add_bf16(h[c], self.W(li, "wd", draft) @ bf16_to_f64(act))
+            new_kv.append((nk, nv))
+        logits = np.zeros((nc, s.vocab))
+        for c in range(nc):
+            xn = rmsnorm(h[c], self.g_final, s.rms_eps)
+            logits[c] = self.W(None, "lm_head", draft) @ bf16_to_f64(xn)
+        return logits, new_kv
+
+    def append_kv(self, new_kv, n_cols: int):
+        """Encode and append the first n_cols columns of target-computed K/V
+        (Sec. 5.1 encoder: online formatting of the KV cache)."""
+        for li, (nk, nv) in enumerate(new_kv):
+            for c in range(n_cols):
+                self.cache[li].k.append(encode_kv(nk[c], self.kv_keep, self.kv_t))
+                self.cache[li].v.append(encode_kv(nv[c], self.kv_keep, self.kv_t))
+
+    def truncate(self, n: int):
+        for st in self.cache:
+            del st.k[n:], st.v[n:]
+
+
+# ----------------------------------------------------------------------------
+# Acceptance (Sec. 2.2, greedy rule) and the decode loops
+# ----------------------------------------------------------------------------
+def accept_greedy(draft, target):
+    """draft: k drafted tokens; target: k+1 target tokens (target[i] is the target
+    model's token after the prefix ending in draft[i-1]).  Accept the longest prefix
+    on which they are identical, then emit the target's own next token.
+    Returns (n_accepted, emitted tokens of length n_accepted + 1)."""
+    k = len(draft)
+    n = 0
+    while n < k and int(draft[n]) == int(target[n]):
+        n += 1
+    return n, [int(x) for x in draft[:n]] + [int(target[n])]
+
+
+def prefill(model: OracleModel, prompt):
+    """Fill the cache for prompt[:-1] with the target model; prompt[-1] stays pending."""
+    if len(prompt) > 1:
+        _, kv = model.forward(prompt[:-1], draft=False)
+        model.append_kv(kv, len(prompt) - 1)
+    return int(prompt[-1])
+
+
+def plain_decode(model: OracleModel, prompt, n_new: int):
+    """Autoregressive decoding with the target model (Fig. 2_3 (a))."""
+    pending = prefill(model, prompt)
+    out = []
+    while len(out) < n_new:
+        logits, kv = model.forward([pending], draft=False)
+        model.append_kv(kv, 1)
+        pending = argmax_lowest(logits[0])
+        out.append(pending)
+    return out
+
+
+def spec_decode(model: OracleModel, prompt, n_new: int, k: int, stats=None):
+    """Self-speculative decoding (Fig. 2_3 (b), Sec. 4.1): k draft steps on the
+    speculation data, one verification pass over the pending token and the k drafts,
+    greedy acceptance, commit of the accepted target K/V."""
+    pending = prefill(model, prompt)
+    out = []
+    while len(out) < n_new:
+        drafts, cur = [], pending
+        extra = [(np.zeros((0, model.s.n_kv_heads, model.s.head_dim), np.uint16),) * 2
+                 for _ in range(model.s.n_layers)]
+        for _ in range(k):
+            logits, kv = model.forward([cur], draft=True, extra_kv=extra)
+            extra = [(np.concatenate([e[0], n[0]]), np.concatenate([e[1], n[1]]))
+                     for e, n in zip(extra, kv)]
+            cur = argmax_lowest(logits[0])
+            drafts.append(cur)
+        logits, kv = model.forward([pending] + drafts, draft=False)
+        target = [argmax_lowest(logits[c]) for c in range(k + 1)]
+        n, emitted = accept_greedy(drafts, target)
+        model.append_kv(kv, n + 1)
+        out.extend(emitted)
+        pending = emitted[-1]
+        if stats is not None:
+            stats.append(n)
+    return out[:n_new]
