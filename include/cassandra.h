@@ -1,0 +1,125 @@
+/*
+ * cassandra.h -- C ABI of the MI355X (gfx950) hot path of Cassandra self-speculative decoding.
+ *
+ * The operations follow the paper's statement of the method:
+ *   - Sec. 4.1: every weight matrix and KV vector is stored as speculation data (the selected
+ *     values: sign, exponent, leading mantissa bits, plus a bitmap of their positions) and
+ *     verification data (the dropped mantissa bits of the selected values and the unselected
+ *     values verbatim).  The draft pass reads speculation data only and pads with zeros; the
+ *     target pass reads both and recovers the original bf16 exactly.
+ *   - Sec. 4.2: selection = activation-aware magnitude pruning for weights, per-token
+ *     magnitude pruning for K and V; truncation = dropping the t low mantissa bits unrounded.
+ *   - Sec. 2.2: k draft tokens, one batched verification over k+1 columns, greedy acceptance.
+ *   - Sec. 5.1 (encoder): new K/V vectors are formatted online when they are appended.
+ *
+ * Conventions
+ *   - Every function returns CAS_OK (0) or a negative CAS_E* code; no exceptions cross the ABI.
+ *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  All device memory is
+ *     allocated and owned by the caller; the library owns only the opaque host structs it
+ *     returns and frees them in the matching *_destroy.
+ *   - Device work is enqueued on the stream given to cas_ctx_create and is not synchronised;
+ *     outputs are valid once the caller synchronises that stream.
+ *   - bf16 tensors are passed as uint16_t bit patterns.  Device buffers must be 256-byte aligned.
+ *   - One cas_ctx per host thread.
+ */
+#ifndef CASSANDRA_H
+#define CASSANDRA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CAS_OK = 0,
+  CAS_EINVAL = -1,   /* bad shape, alignment, format or NULL pointer */
+  CAS_ENOTSUP = -2,  /* valid request without a kernel (e.g. exp_mode != 0) */
+  CAS_ENOMEM = -3,   /* workspace or pool too small */
+  CAS_EHIP = -4      /* a HIP call failed; cas_last_hip_error() has the code */
+};
+
+typedef struct cas_ctx cas_ctx;
+
+/* Format parameters (Sec. 4.2; defaults of Sec. 7.2.2: 40 % pruned, 4 bits truncated). */
+typedef struct {
+  int32_t keep_permille; /* kept fraction in 1/1000 (600 = 40 % pruned); K = (keep*G+500)/1000 */
+  int32_t trunc_bits;    /* t in 0..7: low mantissa bits moved to the verification data */
+  int32_t exp_mode;      /* 0 = exponent stored raw (8 bits); other values: CAS_ENOTSUP */
+} cas_fmt;
+
+/*
+ * Layout of one encoded matrix: `rows` selection groups (output rows of a linear layer, or
+ * (token, head) vectors of a KV tile) of `cols` values, K kept per row.  Streams are
+ * little-endian bit streams in 32-bit words, every row starting on a word boundary:
+ *   bitmap : bit c%32 of word c/32 is 1 iff column c is kept        (bw words per row)
+ *   spec   : K fields of 16-t bits (word >> t), ascending column     (sw words per row)
+ *   lo     : K fields of t bits (word & (2^t-1)), ascending column   (lw words per row)
+ *   pruned : cols-K unselected 16-bit words, ascending column        (pw words per row)
+ * The speculation buffer holds [bitmap | spec], the verification buffer [lo | pruned], each
+ * region 256-byte aligned and followed by 256 bytes of slack that kernels may over-read.
+ * The struct is plain data; encoded buffers can be copied or stored verbatim.
+ */
+typedef struct {
+  int64_t rows, cols;
+  int32_t K, t;
+  int32_t bw, sw, lw, pw;
+  int64_t off_bitmap, off_spec;  /* byte offsets inside the speculation buffer */
+  int64_t off_lo, off_pruned;    /* byte offsets inside the verification buffer */
+  int64_t spec_bytes, verif_bytes; /* sizes the caller must allocate */
+} cas_wdesc;
+
+/* ---- context ------------------------------------------------------------------------- */
+
+/* hip_stream: a hipStream_t (NULL = default stream).  d_workspace/ws_bytes: caller-owned
+ * device scratch used by calls that say so (attention split partials); may be NULL/0 if
+ * those calls are not used. */
+int cas_ctx_create(cas_ctx** out, void* hip_stream, void* d_workspace, size_t ws_bytes);
+int cas_ctx_destroy(cas_ctx* ctx);
+const char* cas_strerror(int code);
+int cas_last_hip_error(const cas_ctx* ctx);
+
+/* ---- weights: encode / decode (Sec. 4.2, Sec. 5.1) ------------------------------------ */
+
+/* Host only.  Fills the layout and buffer sizes for a rows x cols matrix. */
+int cas_weight_desc(int64_t rows, int64_t cols, const cas_fmt* fmt, cas_wdesc* out);
+
+/* Offline weight formatting.  d_W: bf16 [rows][ld] row-major (ld >= cols, in elements).
+ * d_act_norm: float [cols] activation norms a_j >= 0 (score |W_ij| * a_j, one fp32 multiply),
+ * or NULL for pure magnitude.  Per row the K highest scores are kept; equal scores go to the
+ * lower column.  Writes d_spec (desc->spec_bytes) and d_verif (desc->verif_bytes). */
+int cas_encode_weight(cas_ctx* ctx, const uint16_t* d_W, int64_t ld, const float* d_act_norm,
+                      const cas_wdesc* desc, void* d_spec, void* d_verif);
+
+/* Reconstruction to dense bf16 [rows][ld] (check/reference path; the step kernels decode in
+ * place).  d_verif == NULL: draft reconstruction (kept values with dropped bits 0, others
+ * +0, Sec. 4.1).  Otherwise: full reconstruction, bit-identical to the encoded matrix. */
+int cas_decode_weight(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
+                      const void* d_verif, uint16_t* d_out, int64_t ld);
+
+/* ---- stand-alone linear kernels -------------------------------------------------------- */
+
+/* Draft GEMV (Sec. 4.1 draft inference): y[b][r] = sum_c Wdraft[r][c] * x[b][c], fp32
+ * accumulation, reading only the speculation buffer.  d_x: bf16 [batch][cols];
+ * d_y: float [batch][rows]; batch in 1..4. */
+int cas_gemv_draft(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
+                   const uint16_t* d_x, int batch, float* d_y);
+
+/* Verification GEMM (Sec. 2.2 batched verification, Sec. 4.1 target inference):
+ * Y[c][r] = sum_j W[r][j] * X[c][j] with W the exact bf16 matrix rebuilt from both buffers.
+ * d_X: bf16 [ncols][cols]; d_Y: float [ncols][rows]; ncols in 1..16.  The value of a column
+ * does not depend on ncols or on the other columns. */
+int cas_gemm_verify(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
+                    const void* d_verif, const uint16_t* d_X, int ncols, float* d_Y);
+
+/* Greedy acceptance (Sec. 2.2).  Host only, no side effects.  h_draft: k drafted tokens;
+ * h_target: k+1 target tokens.  n_accepted = number of leading positions where they are
+ * identical; h_out receives those n tokens followed by h_target[n] (n+1 tokens). */
+int cas_accept(const int32_t* h_draft, const int32_t* h_target, int k, int32_t* n_accepted,
+               int32_t* h_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CASSANDRA_H */

@@ -1,0 +1,181 @@
+"""ctypes binding of libcassandra_hip.so: same names as include/cassandra.h, argument
+marshalling only.  torch tensors provide device memory and the stream; every step of the
+path runs in the HIP kernels.  Loading fails loudly if the library has not been built."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcassandra_hip.so")
+
+CAS_OK, CAS_EINVAL, CAS_ENOTSUP, CAS_ENOMEM, CAS_EHIP = 0, -1, -2, -3, -4
+
+
+class CasError(RuntimeError):
+    def __init__(self, code, what, hip=0):
+        super().__init__(f"{what}: error {code} ({_lib().cas_strerror(code).decode()})"
+                         + (f", hip error {hip}" if hip else ""))
+        self.code = code
+
+
+class cas_fmt(C.Structure):
+    _fields_ = [("keep_permille", C.c_int32), ("trunc_bits", C.c_int32), ("exp_mode", C.c_int32)]
+
+
+class cas_wdesc(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("K", C.c_int32), ("t", C.c_int32),
+                ("bw", C.c_int32), ("sw", C.c_int32), ("lw", C.c_int32), ("pw", C.c_int32),
+                ("off_bitmap", C.c_int64), ("off_spec", C.c_int64),
+                ("off_lo", C.c_int64), ("off_pruned", C.c_int64),
+                ("spec_bytes", C.c_int64), ("verif_bytes", C.c_int64)]
+
+
+_LIB = None
+
+_SIGNATURES = {
+    "cas_ctx_create": (C.c_int, [C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_size_t]),
+    "cas_ctx_destroy": (C.c_int, [C.c_void_p]),
+    "cas_strerror": (C.c_char_p, [C.c_int]),
+    "cas_last_hip_error": (C.c_int, [C.c_void_p]),
+    "cas_weight_desc": (C.c_int, [C.c_int64, C.c_int64, C.POINTER(cas_fmt), C.POINTER(cas_wdesc)]),
+    "cas_encode_weight": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(cas_wdesc),
+                                    C.c_void_p, C.c_void_p]),
+    "cas_decode_weight": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_int64]),
+    "cas_gemv_draft": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.c_void_p, C.c_int,
+                                 C.c_void_p]),
+    "cas_gemm_verify": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_int, C.c_void_p]),
+    "cas_accept": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32),
+                             C.POINTER(C.c_int32)]),
+}
+
+
+def exported_names():
+    return sorted(_SIGNATURES)
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with "
+                              "`python -c 'import __graft_entry__ as g; g.build()'` (no CPU fallback exists)")
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _LIB = lib
+    return _LIB
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    return C.c_void_p(t.data_ptr())
+
+
+class Context:
+    """Owns a cas_ctx bound to the current torch stream."""
+
+    def __init__(self, workspace=None):
+        import torch
+        self._torch = torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("the Cassandra HIP path needs a GPU; there is no CPU fallback")
+        self.workspace = workspace
+        h = C.c_void_p()
+        stream = torch.cuda.current_stream().cuda_stream
+        ws_ptr = _ptr(workspace)
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        rc = _lib().cas_ctx_create(C.byref(h), C.c_void_p(stream), ws_ptr, ws_bytes)
+        if rc != CAS_OK:
+            raise CasError(rc, "cas_ctx_create")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            _lib().cas_ctx_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc, what):
+        if rc != CAS_OK:
+            raise CasError(rc, what, _lib().cas_last_hip_error(self.h))
+
+
+def cas_weight_desc(rows, cols, keep_permille, trunc_bits, exp_mode=0):
+    fmt = cas_fmt(keep_permille, trunc_bits, exp_mode)
+    d = cas_wdesc()
+    rc = _lib().cas_weight_desc(rows, cols, C.byref(fmt), C.byref(d))
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_weight_desc")
+    return d
+
+
+class EncodedWeight:
+    """Descriptor + the two device buffers (uint8 torch tensors) of one encoded matrix."""
+
+    def __init__(self, desc, spec, verif):
+        self.desc, self.spec, self.verif = desc, spec, verif
+
+
+def cas_encode_weight(ctx: Context, W, keep_permille, trunc_bits, act_norm=None) -> EncodedWeight:
+    """W: torch int16/uint16/bfloat16 [rows, cols] on the GPU (bf16 bit patterns)."""
+    torch = ctx._torch
+    assert W.is_cuda and W.dim() == 2 and W.element_size() == 2 and W.stride(1) == 1
+    rows, cols = W.shape
+    d = cas_weight_desc(rows, cols, keep_permille, trunc_bits)
+    spec = torch.empty(d.spec_bytes, dtype=torch.uint8, device=W.device)
+    verif = torch.empty(d.verif_bytes, dtype=torch.uint8, device=W.device)
+    ctx._check(_lib().cas_encode_weight(ctx.h, _ptr(W), W.stride(0), _ptr(act_norm), C.byref(d), _ptr(spec),
+                                        _ptr(verif)), "cas_encode_weight")
+    return EncodedWeight(d, spec, verif)
+
+
+def cas_decode_weight(ctx: Context, ew: EncodedWeight, full: bool):
+    torch = ctx._torch
+    out = torch.empty((ew.desc.rows, ew.desc.cols), dtype=torch.int16, device=ew.spec.device)
+    ctx._check(_lib().cas_decode_weight(ctx.h, C.byref(ew.desc), _ptr(ew.spec), _ptr(ew.verif) if full else None,
+                                        _ptr(out), ew.desc.cols), "cas_decode_weight")
+    return out
+
+
+def cas_gemv_draft(ctx: Context, ew: EncodedWeight, x, out=None):
+    """x: bf16 bits [batch, cols] -> float32 [batch, rows]."""
+    torch = ctx._torch
+    assert x.dim() == 2 and x.shape[1] == ew.desc.cols and x.is_contiguous() and x.element_size() == 2
+    if out is None:
+        out = torch.empty((x.shape[0], ew.desc.rows), dtype=torch.float32, device=x.device)
+    ctx._check(_lib().cas_gemv_draft(ctx.h, C.byref(ew.desc), _ptr(ew.spec), _ptr(x), x.shape[0], _ptr(out)),
+               "cas_gemv_draft")
+    return out
+
+
+def cas_gemm_verify(ctx: Context, ew: EncodedWeight, X, out=None):
+    """X: bf16 bits [ncols, cols] -> float32 [ncols, rows]."""
+    torch = ctx._torch
+    assert X.dim() == 2 and X.shape[1] == ew.desc.cols and X.is_contiguous() and X.element_size() == 2
+    if out is None:
+        out = torch.empty((X.shape[0], ew.desc.rows), dtype=torch.float32, device=X.device)
+    ctx._check(_lib().cas_gemm_verify(ctx.h, C.byref(ew.desc), _ptr(ew.spec), _ptr(ew.verif), _ptr(X), X.shape[0],
+                                      _ptr(out)), "cas_gemm_verify")
+    return out
+
+
+def cas_accept(draft, target):
+    k = len(draft)
+    d = (C.c_int32 * max(k, 1))(*[int(v) for v in draft])
+    t = (C.c_int32 * (k + 1))(*[int(v) for v in target])
+    n = C.c_int32()
+    out = (C.c_int32 * (k + 1))()
+    rc = _lib().cas_accept(d, t, k, C.byref(n), out)
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_accept")
+    return n.value, [out[i] for i in range(n.value + 1)]

@@ -1,0 +1,106 @@
+// Device-side helpers shared by the gfx950 kernels: wave64 scans through DPP, bit-field
+// access to the packed streams, bf16 conversion.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+namespace cas {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ int lane_id() { return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
+
+// DPP controls (GFX9 encoding)
+constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
+constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+constexpr int DPP_QUAD_BCAST0 = 0x00, DPP_QUAD_BCAST3 = 0xFF;
+
+// Inclusive prefix sum over the 64 lanes of a wave.  Lanes whose DPP source is outside the
+// row, or that are masked off, add 0.
+__device__ __forceinline__ int wave_incl_scan(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, DPP_ROW_SHR1, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, DPP_ROW_SHR2, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, DPP_ROW_SHR4, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, DPP_ROW_SHR8, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, DPP_ROW_BCAST15, 0xa, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, DPP_ROW_BCAST31, 0xc, 0xf, false);
+  return v;
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_addf(float v) {
+  return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+
+// Sum of v over the wave, returned in every lane (same tree as the scan; lane 63 holds it).
+__device__ __forceinline__ float wave_sum(float v) {
+  v = dpp_addf<DPP_ROW_SHR1, 0xf>(v);
+  v = dpp_addf<DPP_ROW_SHR2, 0xf>(v);
+  v = dpp_addf<DPP_ROW_SHR4, 0xf>(v);
+  v = dpp_addf<DPP_ROW_SHR8, 0xf>(v);
+  v = dpp_addf<DPP_ROW_BCAST15, 0xa>(v);
+  v = dpp_addf<DPP_ROW_BCAST31, 0xc>(v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
+
+// float -> bf16, round to nearest even (NaN stays a quiet NaN).
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t b = __float_as_uint(f);
+  if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((b >> 16) | 0x40u);
+  return (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ float round_bf16(float f) { return bf16_to_f32(f32_to_bf16(f)); }
+
+// position of the lowest set bit, -1 if none (v_ffbl_b32 semantics)
+__device__ __forceinline__ int lowest_bit(uint32_t m) { return m ? __builtin_ctz(m) : -1; }
+
+// Read a `width`-bit field at bit offset `bit` of a little-endian word stream (generic path).
+__device__ __forceinline__ uint32_t read_field(const uint32_t* __restrict__ s, uint32_t bit, int width) {
+  uint32_t w = bit >> 5, sh = bit & 31;
+  uint64_t v = s[w];
+  if (sh + width > 32) v |= ((uint64_t)s[w + 1]) << 32;
+  return (uint32_t)(v >> sh) & ((1u << width) - 1u);
+}
+
+// Field i (compile-time) of `width` bits from a register window a[] whose bit 0 is field 0.
+// Returns the field shifted to the top of a 32-bit word: bits [31 : 32-width].
+template <int WIDTH, int I, int NW>
+__device__ __forceinline__ uint32_t field_top(const uint32_t (&a)[NW]) {
+  constexpr int bit = I * WIDTH, w = bit >> 5, sh = bit & 31;
+  if constexpr (sh + WIDTH <= 32) {
+    return (a[w] >> sh) << (32 - WIDTH);
+  } else {
+    return __builtin_amdgcn_alignbit(a[w + 1], a[w], sh) << (32 - WIDTH);
+  }
+}
+
+// Field i (compile-time) of `width` bits from a register window, right-aligned and masked.
+template <int WIDTH, int I, int NW>
+__device__ __forceinline__ uint32_t field_at(const uint32_t (&a)[NW]) {
+  constexpr int bit = I * WIDTH, w = bit >> 5, sh = bit & 31;
+  if constexpr (sh + WIDTH <= 32) {
+    return __builtin_amdgcn_ubfe(a[w], sh, WIDTH);
+  } else {
+    return __builtin_amdgcn_alignbit(a[w + 1], a[w], sh) & ((1u << WIDTH) - 1u);
+  }
+}
+
+// compile-time loop: f(integral_constant<int, I>) for I in [B, E)
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
+}  // namespace cas

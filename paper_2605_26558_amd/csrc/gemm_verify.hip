@@ -1,0 +1,265 @@
+// Verification GEMM: Y = W X with W rebuilt exactly from speculation + verification data
+// inside the kernel (Sec. 4.1 target inference, Sec. 5.1 mantissa concatenation and bitmap
+// de-sparsification) and X holding the k+1 columns of one verification pass (Sec. 2.2).
+//
+// Mapping.  A workgroup of four waves owns 16 output rows and walks the columns in slabs of
+// 2048; wave w takes the w-th 512-column quarter of every slab.  Inside a quarter lane (r, j)
+// owns bitmap words 4j..4j+3 of row r (128 consecutive columns), so its kept fields, dropped
+// mantissa bits and pruned words are contiguous runs of the three streams.  For each of its
+// four words the lane walks the set bits (kept: leading bits from spec, low bits from lo) and
+// then the clear bits (pruned: verbatim word) and scatters the bf16 values into a 16 x 128
+// tile in LDS.  The tile is then multiplied with the matching 128 rows of X by eight
+// 16x16x16 bf16 MFMA operations, accumulating in fp32.  Each output column uses the same
+// sequence of operations whatever the number of columns is.  The four partial tiles of a
+// workgroup are added in wave order through LDS.
+#include "cas_device.hpp"
+#include "cas_internal.hpp"
+
+namespace cas {
+
+typedef short bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct VerifyArgs {
+  int rows, cols, bw, sw, lw, pw, ncols;
+  const uint32_t* bitmap;
+  const uint32_t* spec;
+  const uint32_t* lo;
+  const uint32_t* pruned;
+  const uint16_t* X;  // [ncols][cols]
+  float* Y;           // [ncols][rows]
+};
+
+constexpr int kSlabCols = 2048;
+constexpr int kXPitch = kSlabCols + 8;  // bf16 per X row in LDS
+constexpr int kGroupPitch = 36;         // 4 dump slots + 32 columns
+constexpr int kTilePitch = 148;         // 4 groups + 4 pad, keeps 8-byte alignment, spreads banks
+
+template <int CTRL>
+__device__ __forceinline__ int quad_dpp(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+
+template <int T>
+__global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
+  constexpr int FW = 16 - T;
+  constexpr int LW = T > 0 ? T : 1;
+  extern __shared__ uint16_t lds[];
+  uint16_t* Xs = lds;                                    // [ncols][kXPitch]
+  uint16_t* tiles = lds + (size_t)a.ncols * kXPitch;     // [4][16][kTilePitch]
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  uint16_t* tile = tiles + wv * 16 * kTilePitch;
+  for (int i = tid; i < 4 * 16 * kTilePitch; i += 256) tiles[i] = 0;
+
+  const int r = lane >> 2, j = lane & 3;
+  const int row0 = blockIdx.x * 16;
+  const int row = min(row0 + r, a.rows - 1);
+  const uint32_t* bm_row = a.bitmap + (size_t)row * a.bw;
+  const uint32_t* sp_row = a.spec + (size_t)row * a.sw;
+  const uint32_t* lo_row = a.lo + (size_t)row * a.lw;
+  const uint32_t* pr_row = a.pruned + (size_t)row * a.pw;
+  uint16_t* trow = tile + r * kTilePitch + j * kGroupPitch + 4;  // column 0 of the lane's group
+
+  // MFMA operand addresses: A[i = lane%16][k = 4*(lane/16)..+3], B[k][n = lane%16]
+  const int mi = lane & 15, mq = lane >> 4;
+  const uint16_t* a_base = tile + mi * kTilePitch + 4 + 4 * mq;
+  const int bcol = mi < a.ncols ? mi : 0;
+  const uint16_t* b_base = Xs + bcol * kXPitch + wv * 512 + 4 * mq;
+
+  f32x4 C = {0.f, 0.f, 0.f, 0.f};
+  uint32_t rowpre = 0;  // kept values of the row in earlier slabs
+  const int nslab = (a.bw + 63) >> 6;
+
+  for (int slab = 0; slab < nslab; ++slab) {
+    __syncthreads();
+    // ---- stage the slab of X (bf16, zero beyond the last column)
+    for (int c = 0; c < a.ncols; ++c) {
+      for (int i = tid; i < kSlabCols; i += 256) {
+        int col = slab * kSlabCols + i;
+        Xs[c * kXPitch + i] = col < a.cols ? a.X[(size_t)c * a.cols + col] : (uint16_t)0;
+      }
+    }
+    // ---- bitmap words: lane (r, j) reads words 4j..4j+3 of each quarter v
+    uint32_t mw[4][4];
+    int cq[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      int w0 = slab * 64 + v * 16 + 4 * j;
+      cq[v] = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        mw[v][i] = (w0 + i < a.bw) ? bm_row[w0 + i] : 0u;
+        cq[v] += __popc(mw[v][i]);
+      }
+    }
+    // kept values of the row before this wave's quarter and before this lane's words
+    uint32_t before = rowpre;
+    int slab_total = 0;
+    int own = 0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      int s = cq[v];
+      s += quad_dpp<0xB1>(s);  // quad_perm [1,0,3,2]
+      s += quad_dpp<0x4E>(s);  // quad_perm [2,3,0,1]
+      slab_total += s;
+      if (v < wv) before += (uint32_t)s;
+      if (v == wv) own = cq[v];
+    }
+    {
+      int b0 = quad_dpp<0x00>(own), b1 = quad_dpp<0x55>(own), b2 = quad_dpp<0xAA>(own);
+      before += (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
+    }
+    rowpre += (uint32_t)slab_total;
+    uint32_t m4[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) m4[i] = wv == 0 ? mw[0][i] : wv == 1 ? mw[1][i] : wv == 2 ? mw[2][i] : mw[3][i];
+    __syncthreads();
+
+    const int word0 = slab * 64 + wv * 16 + 4 * j;  // first bitmap word of this lane
+    uint32_t p = before;                            // kept values before the current word
+    uint32_t u = (uint32_t)word0 * 32u - p;         // pruned values before the current word
+
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int colbase = (word0 + i) * 32;
+      uint32_t m = m4[i];
+      int nvalid = a.cols - colbase;
+      uint32_t valid = nvalid >= 32 ? 0xFFFFFFFFu : (nvalid <= 0 ? 0u : ((1u << nvalid) - 1u));
+      uint32_t pm = ~m & valid;
+      // words past the end of the row have no fields: keep their (unused) windows in range
+      const uint32_t pa = nvalid > 0 ? p : 0u, ua = nvalid > 0 ? u : 0u;
+      // ---- windows of the three streams at this word
+      uint32_t ws[FW], wl[LW], wp[16];
+      {
+        uint32_t bit = pa * FW, sh = bit & 31u;
+        const uint32_t* src = sp_row + (bit >> 5);
+        uint32_t d[FW + 1];
+#pragma unroll
+        for (int q = 0; q <= FW; ++q) d[q] = src[q];
+#pragma unroll
+        for (int q = 0; q < FW; ++q) ws[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
+      }
+      if constexpr (T > 0) {
+        uint32_t bit = pa * T, sh = bit & 31u;
+        const uint32_t* src = lo_row + (bit >> 5);
+        uint32_t d[T + 1];
+#pragma unroll
+        for (int q = 0; q <= T; ++q) d[q] = src[q];
+#pragma unroll
+        for (int q = 0; q < T; ++q) wl[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
+      }
+      {
+        uint32_t sh = (ua & 1u) << 4;
+        const uint32_t* src = pr_row + (ua >> 1);
+        uint32_t d[17];
+#pragma unroll
+        for (int q = 0; q <= 16; ++q) d[q] = src[q];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) wp[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
+      }
+      p += (uint32_t)__popc(m);
+      u += (uint32_t)__popc(pm);
+      (void)colbase;
+
+      // ---- kept values: leading bits | dropped bits
+      auto kept_group = [&](auto G) {
+        static_for<0, 8>([&](auto I) {
+          constexpr int e = decltype(G)::value * 8 + decltype(I)::value;
+          int pos = lowest_bit(m);
+          m &= m - 1u;
+          uint32_t v = field_at<FW, e>(ws) << T;
+          if constexpr (T > 0) v |= field_at<T, e>(wl);
+          trow[pos] = (uint16_t)v;  // pos == -1 lands in the dump slot in front of the group
+        });
+      };
+      kept_group(std::integral_constant<int, 0>{});
+      if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+        kept_group(std::integral_constant<int, 1>{});
+        if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+          kept_group(std::integral_constant<int, 2>{});
+          if (__builtin_amdgcn_ballot_w64(m != 0u)) kept_group(std::integral_constant<int, 3>{});
+        }
+      }
+      // ---- pruned values: verbatim words
+      auto pruned_group = [&](auto G) {
+        static_for<0, 8>([&](auto I) {
+          constexpr int e = decltype(G)::value * 8 + decltype(I)::value;
+          int pos = lowest_bit(pm);
+          pm &= pm - 1u;
+          trow[pos] = (uint16_t)(wp[e >> 1] >> ((e & 1) * 16));
+        });
+      };
+      if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
+        pruned_group(std::integral_constant<int, 0>{});
+        if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
+          pruned_group(std::integral_constant<int, 1>{});
+          if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
+            pruned_group(std::integral_constant<int, 2>{});
+            if (__builtin_amdgcn_ballot_w64(pm != 0u)) pruned_group(std::integral_constant<int, 3>{});
+          }
+        }
+      }
+      // ---- tile x X: tile column 32*g + c is slab column wv*512 + (4*g + i)*32 + c
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const int g = kk >> 1, h = kk & 1;
+        bf16x4 av = *reinterpret_cast<const bf16x4*>(a_base + g * kGroupPitch + h * 16);
+        bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + (4 * g + i) * 32 + h * 16);
+        C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, bv, C, 0, 0, 0);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+
+  // ---- add the four partial tiles in wave order; C[i][n]: i = 4*(lane/16) + e, n = lane%16
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(lds);  // [4][64][4], reuses the X slab
+  *reinterpret_cast<f32x4*>(red + (wv * 64 + lane) * 4) = C;
+  __syncthreads();
+  if (wv == 0 && mi < a.ncols) {
+    f32x4 s = *reinterpret_cast<f32x4*>(red + lane * 4);
+#pragma unroll
+    for (int w = 1; w < 4; ++w) s += *reinterpret_cast<f32x4*>(red + (w * 64 + lane) * 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      int orow = row0 + 4 * mq + e;
+      if (orow < a.rows) a.Y[(size_t)mi * a.rows + orow] = s[e];
+    }
+  }
+}
+
+int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const void* verif, const uint16_t* X,
+                       int ncols, float* Y) {
+  if (d.rows <= 0) return CAS_OK;
+  VerifyArgs a;
+  a.rows = (int)d.rows; a.cols = (int)d.cols; a.bw = d.bw; a.sw = d.sw; a.lw = d.lw; a.pw = d.pw;
+  a.ncols = ncols;
+  a.bitmap = (const uint32_t*)((const char*)spec + d.off_bitmap);
+  a.spec = (const uint32_t*)((const char*)spec + d.off_spec);
+  a.lo = (const uint32_t*)((const char*)verif + d.off_lo);
+  a.pruned = (const uint32_t*)((const char*)verif + d.off_pruned);
+  a.X = X; a.Y = Y;
+  size_t lds = sizeof(uint16_t) * ((size_t)ncols * kXPitch + 4 * 16 * kTilePitch);
+  lds = std::max(lds, sizeof(float) * 4 * 64 * 4);
+  if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
+  int grid = (int)((d.rows + 15) / 16);
+#define CAS_LAUNCH(TV)                                                                                  \
+  case TV:                                                                                              \
+    if (lds > 48 * 1024)                                                                                \
+      CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemm_verify_kernel<TV>,                             \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));          \
+    hipLaunchKernelGGL((gemm_verify_kernel<TV>), dim3(grid), dim3(256), lds, ctx->stream, a);           \
+    break;
+  switch (d.t) {
+    CAS_LAUNCH(0) CAS_LAUNCH(1) CAS_LAUNCH(2) CAS_LAUNCH(3) CAS_LAUNCH(4) CAS_LAUNCH(5) CAS_LAUNCH(6) CAS_LAUNCH(7)
+    default: return CAS_EINVAL;
+  }
+#undef CAS_LAUNCH
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
+}
+
+}  // namespace cas

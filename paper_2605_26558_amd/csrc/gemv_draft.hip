@@ -1,0 +1,192 @@
+// Draft GEMV: y = Wdraft x, reading only the speculation data (bitmap + spec stream) and
+// decoding it inside the kernel (Sec. 4.1 draft inference: zero padding of pruned positions
+// and dropped mantissa bits).
+//
+// Mapping.  One wave walks one output row at a time in chunks of 64 bitmap words (2048
+// columns): lane l owns word l of the chunk, i.e. 32 consecutive columns.  A DPP prefix sum of
+// the popcounts gives each lane the index of its first kept value, so its fields are one
+// contiguous run of the row's spec stream; neighbouring lanes read neighbouring runs.  The
+// lane loads a window of 16-t+1 words at its run, aligns it with funnel shifts, and then
+// walks the set bits of its word: field i of the window belongs to the i-th set bit.  Placing
+// a field at the top of a 32-bit register yields the fp32 value of the zero-padded bf16.
+// x sits in LDS as fp32 in segments of 1+32 entries per bitmap word; entry 0 of a segment is
+// 0.0, so a lane that has run out of set bits (bit position -1) multiplies by zero.
+// The (row, chunk) items of a wave run through a three-stage software pipeline: bitmap word of
+// item q+2, prefix + window loads of item q+1, arithmetic of item q.
+#include "cas_device.hpp"
+#include "cas_internal.hpp"
+
+namespace cas {
+
+struct GemvArgs {
+  int rows, cols, bw, sw;
+  const uint32_t* bitmap;
+  const uint32_t* spec;
+  const uint16_t* x;  // [NB][cols]
+  float* y;           // [NB][rows]
+};
+
+template <int FW>
+struct Window {
+  uint32_t m;
+  uint32_t sh;
+  uint32_t d[FW + 1];
+};
+
+struct Cursor {  // walks the (row, chunk) items of one wave in order
+  int row, chunk;
+  __device__ __forceinline__ void advance(int nchunk, int nwaves) {
+    if (++chunk == nchunk) {
+      chunk = 0;
+      row += nwaves;
+    }
+  }
+};
+
+template <int T, int NB>
+__global__ __launch_bounds__(256) void gemv_draft_kernel(GemvArgs a) {
+  constexpr int FW = 16 - T;
+  extern __shared__ float xs[];
+  const int tid = threadIdx.x;
+  const int nchunk = (a.bw + 63) >> 6;
+  const int nseg = nchunk * 64;
+  // ---- stage x as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0
+  for (int c = tid; c < nseg * 33; c += 256) {
+    int seg = c / 33, e = c - seg * 33;
+    int col = seg * 32 + e - 1;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      float v = (e > 0 && col < a.cols) ? bf16_to_f32(a.x[(size_t)b * a.cols + col]) : 0.f;
+      xs[c * NB + b] = v;
+    }
+  }
+  __syncthreads();
+
+  const int lane = tid & 63;
+  const int gw = blockIdx.x * 4 + (tid >> 6);
+  const int nwaves = gridDim.x * 4;
+  if (gw >= a.rows) return;
+
+  auto load_bm = [&](const Cursor& c) -> uint32_t {
+    int wi = c.chunk * 64 + lane;
+    return (c.row < a.rows && wi < a.bw) ? a.bitmap[(size_t)c.row * a.bw + wi] : 0u;
+  };
+  uint32_t rowprefix = 0;  // kept values of the row before the chunk being issued
+  auto issue = [&](const Cursor& c, uint32_t m, Window<FW>& w) {
+    w.m = m;
+    int cnt = __popc(m);
+    int incl = wave_incl_scan(cnt);
+    int total = __builtin_amdgcn_readlane(incl, 63);
+    uint32_t p = rowprefix + (uint32_t)(incl - cnt);
+    rowprefix = (c.chunk == nchunk - 1) ? 0u : rowprefix + (uint32_t)total;
+    uint32_t bit = p * FW;
+    w.sh = bit & 31u;
+    int row = c.row < a.rows ? c.row : gw;  // past the end: any valid row, its bitmap word is 0
+    const uint32_t* src = a.spec + (size_t)row * a.sw + (bit >> 5);
+#pragma unroll
+    for (int j = 0; j <= FW; ++j) w.d[j] = src[j];
+  };
+
+  float acc[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) acc[b] = 0.f;
+
+  auto compute = [&](const Cursor& c, const Window<FW>& w) {
+    uint32_t win[FW];
+#pragma unroll
+    for (int j = 0; j < FW; ++j) win[j] = __builtin_amdgcn_alignbit(w.d[j + 1], w.d[j], w.sh);
+    uint32_t m = w.m;
+    const float* xb = xs + ((c.chunk * 64 + lane) * 33 + 1) * NB;
+    auto group = [&](auto G) {
+      static_for<0, 8>([&](auto I) {
+        constexpr int i = decltype(G)::value * 8 + decltype(I)::value;
+        int pos = lowest_bit(m);
+        m &= m - 1u;
+        float f = __uint_as_float(field_top<FW, i>(win));
+        const float* xp = xb + pos * NB;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[b] = fmaf(f, xp[b], acc[b]);
+      });
+    };
+    group(std::integral_constant<int, 0>{});
+    if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+      group(std::integral_constant<int, 1>{});
+      if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+        group(std::integral_constant<int, 2>{});
+        if (__builtin_amdgcn_ballot_w64(m != 0u)) group(std::integral_constant<int, 3>{});
+      }
+    }
+    if (c.chunk == nchunk - 1) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        float s = wave_sum(acc[b]);
+        if (lane == 0) a.y[(size_t)b * a.rows + c.row] = s;
+        acc[b] = 0.f;
+      }
+    }
+  };
+
+  Cursor cb{gw, 0}, ci{gw, 0}, cc{gw, 0};
+  Window<FW> w0, w1;
+  uint32_t m0 = load_bm(cb); cb.advance(nchunk, nwaves);
+  uint32_t m1 = load_bm(cb); cb.advance(nchunk, nwaves);
+  issue(ci, m0, w0); ci.advance(nchunk, nwaves);
+  while (true) {
+    uint32_t m2 = load_bm(cb); cb.advance(nchunk, nwaves);
+    issue(ci, m1, w1); ci.advance(nchunk, nwaves);
+    compute(cc, w0); cc.advance(nchunk, nwaves);
+    if (cc.row >= a.rows) break;
+    m1 = load_bm(cb); cb.advance(nchunk, nwaves);
+    issue(ci, m2, w0); ci.advance(nchunk, nwaves);
+    compute(cc, w1); cc.advance(nchunk, nwaves);
+    if (cc.row >= a.rows) break;
+  }
+}
+
+template <int T>
+static int launch_t(cas_ctx* ctx, const GemvArgs& a, int batch, int grid, size_t lds) {
+#define CAS_LAUNCH(NBV)                                                                                      \
+  do {                                                                                                       \
+    if (lds > 48 * 1024)                                                                                     \
+      CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_kernel<T, NBV>,                               \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));               \
+    hipLaunchKernelGGL((gemv_draft_kernel<T, NBV>), dim3(grid), dim3(256), lds, ctx->stream, a);             \
+  } while (0)
+  switch (batch) {
+    case 1: CAS_LAUNCH(1); break;
+    case 2: CAS_LAUNCH(2); break;
+    case 3: CAS_LAUNCH(3); break;
+    case 4: CAS_LAUNCH(4); break;
+    default: return CAS_EINVAL;
+  }
+#undef CAS_LAUNCH
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
+}
+
+int launch_gemv_draft(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const uint16_t* x, int batch, float* y) {
+  if (d.rows <= 0) return CAS_OK;
+  GemvArgs a;
+  a.rows = (int)d.rows; a.cols = (int)d.cols; a.bw = d.bw; a.sw = d.sw;
+  a.bitmap = (const uint32_t*)((const char*)spec + d.off_bitmap);
+  a.spec = (const uint32_t*)((const char*)spec + d.off_spec);
+  a.x = x; a.y = y;
+  size_t lds = sizeof(float) * (size_t)((d.bw + 63) / 64 * 64) * 33 * batch;
+  if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
+  static int wg_per_cu = [] { const char* e = getenv("CAS_GEMV_WG_PER_CU"); return e ? atoi(e) : 4; }();
+  int64_t want = (d.rows + 3) / 4;
+  int grid = (int)std::min<int64_t>(want, (int64_t)ctx->num_cu * wg_per_cu);
+  switch (d.t) {
+    case 0: return launch_t<0>(ctx, a, batch, grid, lds);
+    case 1: return launch_t<1>(ctx, a, batch, grid, lds);
+    case 2: return launch_t<2>(ctx, a, batch, grid, lds);
+    case 3: return launch_t<3>(ctx, a, batch, grid, lds);
+    case 4: return launch_t<4>(ctx, a, batch, grid, lds);
+    case 5: return launch_t<5>(ctx, a, batch, grid, lds);
+    case 6: return launch_t<6>(ctx, a, batch, grid, lds);
+    case 7: return launch_t<7>(ctx, a, batch, grid, lds);
+  }
+  return CAS_EINVAL;
+}
+
+}  // namespace cas

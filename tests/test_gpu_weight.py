@@ -1,0 +1,149 @@
+"""GPU parity of the weight path (encode, decode, draft GEMV, verify GEMM) against the oracle,
+through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import cassandra_oracle as O
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2605_26558_amd import binding as B
+    return torch, B, B.Context()
+
+
+def _dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+
+
+def _regions(ew):
+    d = ew.desc
+    sp = ew.spec.cpu().numpy()
+    vf = ew.verif.cpu().numpy()
+    def reg(buf, off, rows, w):
+        return buf[off: off + rows * w * 4].view("<u4").reshape(rows, w) if w else np.zeros((rows, 0), np.uint32)
+    return (reg(sp, d.off_bitmap, d.rows, d.bw), reg(sp, d.off_spec, d.rows, d.sw),
+            reg(vf, d.off_lo, d.rows, d.lw), reg(vf, d.off_pruned, d.rows, d.pw))
+
+
+CASES = [
+    # rows, cols, keep, t, act
+    (37, 77, 600, 4, False),
+    (16, 128, 600, 4, False),
+    (5, 1, 1000, 4, False),
+    (64, 4096, 600, 4, True),
+    (33, 2500, 250, 4, True),
+    (20, 4100, 600, 0, False),
+    (20, 300, 0, 4, False),
+    (20, 300, 1000, 7, True),
+    (19, 2048, 500, 3, False),
+    (8, 14336, 600, 4, True),
+]
+
+
+@pytest.mark.parametrize("rows,cols,keep,t,act", CASES)
+def test_encode_decode_bit_exact(env, rows, cols, keep, t, act):
+    torch, B, ctx = env
+    print(f"case rows={rows} cols={cols} keep={keep} t={t} act={act}", flush=True)
+    W = synth.weight_matrix(rows, cols, seed=rows + cols)
+    if cols >= 8:
+        W[:, 3] = W[:, 5]           # ties inside rows
+        W[0, :] = W[0, 0]           # a row of equal magnitudes
+    a = synth.act_norm(cols, seed=7) if act else None
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t, None if a is None else torch.from_numpy(a).cuda())
+    torch.cuda.synchronize()
+    p = O.encode_weight(W, keep, t, a)
+    assert (ew.desc.K, ew.desc.bw, ew.desc.sw, ew.desc.lw, ew.desc.pw) == (p.K, *O.stream_words(cols, p.K, t))
+    bm, sp, lo, pr = _regions(ew)
+    np.testing.assert_array_equal(bm, p.bitmap)
+    np.testing.assert_array_equal(sp, p.spec)
+    np.testing.assert_array_equal(lo, p.lo)
+    np.testing.assert_array_equal(pr, p.pruned)
+    full = B.cas_decode_weight(ctx, ew, full=True).cpu().numpy().view(np.uint16)
+    draft = B.cas_decode_weight(ctx, ew, full=False).cpu().numpy().view(np.uint16)
+    np.testing.assert_array_equal(full, W)
+    np.testing.assert_array_equal(draft, O.decode_draft(p))
+
+
+def _tol(W, X):
+    wn = np.linalg.norm(O.bf16_to_f64(W), axis=1)
+    xn = np.linalg.norm(O.bf16_to_f64(X), axis=1)
+    return wn[None, :] * xn[:, None] + 1e-30
+
+
+@pytest.mark.parametrize("rows,cols,keep,t,act", CASES)
+@pytest.mark.parametrize("batch", [1, 3])
+def test_gemv_draft_matches_oracle(env, rows, cols, keep, t, act, batch):
+    torch, B, ctx = env
+    print(f"case rows={rows} cols={cols} keep={keep} t={t} batch={batch}", flush=True)
+    W = synth.weight_matrix(rows, cols, seed=rows + cols)
+    a = synth.act_norm(cols, seed=7) if act else None
+    X = synth.activations(cols, batch, seed=11)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t, None if a is None else torch.from_numpy(a).cuda())
+    try:
+        y = B.cas_gemv_draft(ctx, ew, _dev(torch, X)).cpu().numpy()
+    except B.CasError as e:
+        if e.code == B.CAS_ENOTSUP:
+            pytest.skip("x block does not fit LDS at this width and batch")
+        raise
+    p = O.encode_weight(W, keep, t, a)
+    ref = np.stack([O.gemv_draft(p, X[b]) for b in range(batch)])
+    err = np.abs(y - ref) / _tol(W, X)
+    # spec bar 2e-3 |W||x|; fp32 accumulation of exact bf16 products stays far below it
+    assert err.max() < 2e-3
+    assert err.max() < 2e-5, err.max()
+
+
+@pytest.mark.parametrize("rows,cols,keep,t,act", CASES)
+def test_gemm_verify_matches_oracle_and_is_column_invariant(env, rows, cols, keep, t, act):
+    torch, B, ctx = env
+    print(f"case rows={rows} cols={cols} keep={keep} t={t}", flush=True)
+    W = synth.weight_matrix(rows, cols, seed=rows + cols)
+    a = synth.act_norm(cols, seed=7) if act else None
+    X = synth.activations(cols, 5, seed=12)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t, None if a is None else torch.from_numpy(a).cuda())
+    Xd = _dev(torch, X)
+    Y = B.cas_gemm_verify(ctx, ew, Xd).cpu().numpy()
+    ref = (O.bf16_to_f64(X) @ O.bf16_to_f64(W).T)          # exact reconstruction => GEMM of W itself
+    err = np.abs(Y - ref) / _tol(W, X)
+    assert err.max() < 2e-3
+    assert err.max() < 2e-5, err.max()
+    # a column's value does not depend on how many columns ride along (Sec. 2.2)
+    for c in (0, 4):
+        y1 = B.cas_gemm_verify(ctx, ew, Xd[c:c + 1].contiguous()).cpu().numpy()
+        np.testing.assert_array_equal(y1[0], Y[c])
+    Y9 = B.cas_gemm_verify(ctx, ew, torch.cat([Xd, Xd[:4]]).contiguous()).cpu().numpy()
+    np.testing.assert_array_equal(Y9[:5], Y)
+
+
+def test_config0_full_size_linear_layer(env):
+    """W 4096x4096, 0.5 % outlier input columns, 25 % kept, t = 4, one draft GEMV and a
+    verify GEMM with k = 4 extra columns."""
+    torch, B, ctx = env
+    W = synth.weight_matrix(4096, 4096, seed=1)
+    X = synth.activations(4096, 5, seed=2)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), 250, 4)
+    p = O.encode_weight(W, 250, 4)
+    bm, sp, lo, pr = _regions(ew)
+    assert np.array_equal(bm, p.bitmap) and np.array_equal(sp, p.spec)
+    assert np.array_equal(lo, p.lo) and np.array_equal(pr, p.pruned)
+    Xd = _dev(torch, X)
+    y = B.cas_gemv_draft(ctx, ew, Xd[:1].contiguous()).cpu().numpy()[0]
+    Y = B.cas_gemm_verify(ctx, ew, Xd).cpu().numpy()
+    tol = _tol(W, X)
+    assert (np.abs(y - O.gemv_draft(p, X[0])) / tol[0]).max() < 2e-5
+    assert (np.abs(Y - O.gemm_verify(p, X)) / tol).max() < 2e-5
+
+
+def test_accept_matches_oracle(env):
+    _, B, _ = env
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        k = int(rng.integers(0, 7))
+        d = rng.integers(0, 3, size=k).tolist()
+        t = rng.integers(0, 3, size=k + 1).tolist()
+        assert B.cas_accept(d, t) == O.accept_greedy(d, t)
