@@ -113,6 +113,72 @@ int cas_gemv_draft(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
 int cas_gemm_verify(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
                     const void* d_verif, const uint16_t* d_X, int ncols, float* d_Y);
 
+/* ---- compressed, paged KV cache (Sec. 4.2 per-token pruning, Sec. 5.1 online encoder) ---- */
+
+/*
+ * Geometry of the cache.  The caller fills the first block and calls cas_kv_desc_init, which
+ * fills the derived block.  A tile holds the vectors of one (layer, page, K-or-V, kv head):
+ * page_tokens rows of head_dim values, K kept per row, streams as in cas_wdesc with row
+ * strides bw=4, sw, lw, pw words:
+ *   speculation pool tile : [page_tokens][4] bitmap words, then [page_tokens][sw] spec words
+ *   verification pool tile: [page_tokens][lw] lo words, then [page_tokens][pw] pruned words
+ * Tile index = ((layer * n_pages + page) * 2 + (0 for K, 1 for V)) * n_kv_heads + head; tiles
+ * are tile_spec_bytes / tile_verif_bytes apart.  The selection group is one vector of one
+ * token and one kv head; K and V are selected separately; ties go to the lower channel.
+ */
+typedef struct {
+  int32_t n_layers, n_kv_heads, head_dim /* must be 128 */, page_tokens /* must be 64 */;
+  int32_t n_pages, max_seqs, max_pages_per_seq;
+  cas_fmt fmt;
+  /* derived */
+  int32_t K, sw, lw, pw;
+  int64_t tile_spec_bytes, tile_verif_bytes;
+  int64_t spec_pool_bytes, verif_pool_bytes; /* sizes the caller must allocate */
+} cas_kv_desc;
+
+typedef struct cas_kv cas_kv;
+
+/* Host only. */
+int cas_kv_desc_init(cas_kv_desc* desc);
+
+/* Binds caller-owned pools and a page table to a cache object.  d_page_table: int32
+ * [max_seqs][max_pages_per_seq] of page ids in [0, n_pages), filled by the caller for every
+ * position a sequence may reach.  Lengths start at 0 and are kept on the host. */
+int cas_kv_create(const cas_kv_desc* desc, void* d_spec_pool, void* d_verif_pool,
+                  const int32_t* d_page_table, cas_kv** out);
+int cas_kv_destroy(cas_kv* kv);
+
+/* Formats n_tok new vectors and stores them at positions len(seq) .. len(seq)+n_tok-1 of
+ * `layer`.  d_K, d_V: bf16 [n_tok][n_kv_heads][head_dim].  Does not change the length: every
+ * layer appends at the same positions, then cas_kv_set_len publishes them. */
+int cas_kv_append(cas_ctx* ctx, cas_kv* kv, int layer, int seq, const uint16_t* d_K,
+                  const uint16_t* d_V, int n_tok);
+/* Host only: committed length of a sequence (set: also used to roll back). */
+int cas_kv_set_len(cas_kv* kv, int seq, int32_t len);
+int cas_kv_len(const cas_kv* kv, int seq, int32_t* len);
+
+/* Reference read-back of positions pos0 .. pos0+n_tok-1 to dense bf16
+ * [n_tok][n_kv_heads][head_dim]; full = 0 gives the zero-padded draft view. */
+int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_tok, int full,
+                uint16_t* d_K, uint16_t* d_V);
+
+/*
+ * Attention of one decode pass for one sequence and layer (Fig. 2_1; Sec. 4.1):
+ *   o[c][h] = softmax(q[c][h] . K^T / sqrt(head_dim)) V  over the committed cache positions
+ *   and the in-flight vectors 0 .. n_new - ncols + c (causal among the columns).
+ * full = 0: cache rebuilt from the speculation pool with zero padding (draft pass);
+ * full = 1: cache rebuilt exactly from both pools (verification pass).
+ * d_Q: bf16 [ncols][n_q_heads][head_dim] (after the rotary embedding);
+ * d_Knew, d_Vnew: bf16 [n_new][n_kv_heads][head_dim], uncompressed, ncols <= n_new <= 64;
+ * d_O: bf16 [ncols][n_q_heads][head_dim].  ncols * n_q_heads / n_kv_heads <= 48.
+ * Uses the context workspace for the per-split partial results (CAS_ENOMEM if too small:
+ * (splits + 1) * n_kv_heads * ncols * group * 132 floats, splits <= 2 * CUs / n_kv_heads).
+ * A column's value does not depend on ncols.
+ */
+int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q,
+                  int ncols, int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew,
+                  int n_new, uint16_t* d_O);
+
 /* Greedy acceptance (Sec. 2.2).  Host only, no side effects.  h_draft: k drafted tokens;
  * h_target: k+1 target tokens.  n_accepted = number of leading positions where they are
  * identical; h_out receives those n tokens followed by h_target[n] (n+1 tokens). */

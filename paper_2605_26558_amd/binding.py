@@ -31,6 +31,15 @@ class cas_wdesc(C.Structure):
                 ("spec_bytes", C.c_int64), ("verif_bytes", C.c_int64)]
 
 
+class cas_kv_desc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("page_tokens", C.c_int32), ("n_pages", C.c_int32), ("max_seqs", C.c_int32),
+                ("max_pages_per_seq", C.c_int32), ("fmt", cas_fmt),
+                ("K", C.c_int32), ("sw", C.c_int32), ("lw", C.c_int32), ("pw", C.c_int32),
+                ("tile_spec_bytes", C.c_int64), ("tile_verif_bytes", C.c_int64),
+                ("spec_pool_bytes", C.c_int64), ("verif_pool_bytes", C.c_int64)]
+
+
 _LIB = None
 
 _SIGNATURES = {
@@ -47,6 +56,17 @@ _SIGNATURES = {
                                  C.c_void_p]),
     "cas_gemm_verify": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                   C.c_int, C.c_void_p]),
+    "cas_kv_desc_init": (C.c_int, [C.POINTER(cas_kv_desc)]),
+    "cas_kv_create": (C.c_int, [C.POINTER(cas_kv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.POINTER(C.c_void_p)]),
+    "cas_kv_destroy": (C.c_int, [C.c_void_p]),
+    "cas_kv_append": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int]),
+    "cas_kv_set_len": (C.c_int, [C.c_void_p, C.c_int, C.c_int32]),
+    "cas_kv_len": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_int32)]),
+    "cas_kv_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                              C.c_void_p, C.c_void_p]),
+    "cas_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
+                                C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
     "cas_accept": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32),
                              C.POINTER(C.c_int32)]),
 }
@@ -179,3 +199,85 @@ def cas_accept(draft, target):
     if rc != CAS_OK:
         raise CasError(rc, "cas_accept")
     return n.value, [out[i] for i in range(n.value + 1)]
+
+
+class KVCache:
+    """Pools, page table and the cas_kv handle of a compressed paged cache."""
+
+    def __init__(self, ctx: Context, n_layers, n_kv_heads, n_pages, max_seqs, max_pages_per_seq,
+                 keep_permille=600, trunc_bits=4, head_dim=128, page_tokens=64, page_table=None):
+        torch = ctx._torch
+        d = cas_kv_desc()
+        d.n_layers, d.n_kv_heads, d.head_dim, d.page_tokens = n_layers, n_kv_heads, head_dim, page_tokens
+        d.n_pages, d.max_seqs, d.max_pages_per_seq = n_pages, max_seqs, max_pages_per_seq
+        d.fmt = cas_fmt(keep_permille, trunc_bits, 0)
+        rc = _lib().cas_kv_desc_init(C.byref(d))
+        if rc != CAS_OK:
+            raise CasError(rc, "cas_kv_desc_init")
+        self.desc = d
+        self.ctx = ctx
+        self.spec_pool = torch.empty(d.spec_pool_bytes, dtype=torch.uint8, device="cuda")
+        self.verif_pool = torch.empty(d.verif_pool_bytes, dtype=torch.uint8, device="cuda")
+        if page_table is None:
+            assert max_seqs * max_pages_per_seq <= n_pages
+            page_table = torch.arange(max_seqs * max_pages_per_seq, dtype=torch.int32).reshape(
+                max_seqs, max_pages_per_seq)
+        self.page_table = page_table.to(device="cuda", dtype=torch.int32).contiguous()
+        h = C.c_void_p()
+        rc = _lib().cas_kv_create(C.byref(d), _ptr(self.spec_pool), _ptr(self.verif_pool), _ptr(self.page_table),
+                                  C.byref(h))
+        if rc != CAS_OK:
+            raise CasError(rc, "cas_kv_create")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            _lib().cas_kv_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def cas_kv_append(ctx: Context, kv: KVCache, layer, seq, K, V):
+    """K, V: bf16 bits [n_tok, n_kv_heads, head_dim]."""
+    assert K.is_contiguous() and V.is_contiguous() and K.shape == V.shape
+    ctx._check(_lib().cas_kv_append(ctx.h, kv.h, layer, seq, _ptr(K), _ptr(V), K.shape[0]), "cas_kv_append")
+
+
+def cas_kv_set_len(kv: KVCache, seq, length):
+    rc = _lib().cas_kv_set_len(kv.h, seq, length)
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_kv_set_len")
+
+
+def cas_kv_len(kv: KVCache, seq):
+    n = C.c_int32()
+    rc = _lib().cas_kv_len(kv.h, seq, C.byref(n))
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_kv_len")
+    return n.value
+
+
+def cas_kv_read(ctx: Context, kv: KVCache, layer, seq, pos0, n_tok, full):
+    torch = ctx._torch
+    shp = (n_tok, kv.desc.n_kv_heads, kv.desc.head_dim)
+    K = torch.empty(shp, dtype=torch.int16, device="cuda")
+    V = torch.empty(shp, dtype=torch.int16, device="cuda")
+    ctx._check(_lib().cas_kv_read(ctx.h, kv.h, layer, seq, pos0, n_tok, 1 if full else 0, _ptr(K), _ptr(V)),
+               "cas_kv_read")
+    return K, V
+
+
+def cas_attention(ctx: Context, kv: KVCache, layer, seq, full, Q, Knew, Vnew, out=None):
+    """Q: bf16 bits [ncols, n_q_heads, 128]; Knew/Vnew: [n_new, n_kv_heads, 128]."""
+    torch = ctx._torch
+    assert Q.is_contiguous() and Knew.is_contiguous() and Vnew.is_contiguous()
+    if out is None:
+        out = torch.empty_like(Q)
+    ctx._check(_lib().cas_attention(ctx.h, kv.h, layer, seq, 1 if full else 0, _ptr(Q), Q.shape[0], Q.shape[1],
+                                    _ptr(Knew), _ptr(Vnew), Knew.shape[0], _ptr(out)), "cas_attention")
+    return out

@@ -1,0 +1,333 @@
+// Attention of the decode step over the compressed, paged KV cache (Fig. 2_1 structure;
+// Sec. 4.1 decides which data a pass may read): the draft pass rebuilds K and V from the
+// speculation data with zero padding, the verification pass rebuilds them exactly from both
+// pools.  The vectors of the in-flight tokens (draft tokens not yet verified, or the k+1
+// columns of the verification pass) arrive uncompressed.
+//
+// One workgroup handles one kv head and one split of the sequence, page by page:
+//   1. thread (token r, word j) decodes its 32 channels of K into a 64 x 128 bf16 tile in LDS;
+//   2. each wave multiplies its 16 tokens with the query rows (grouped-query: 4 query heads x
+//      columns share the kv head) by 16x16x16 bf16 MFMA and writes the scaled scores to LDS;
+//   3. online softmax per query row (running max / sum), probabilities split into a bf16
+//      head and a bf16 remainder so the second product keeps 16 mantissa bits;
+//   4. the V tile is decoded transposed and P V accumulates in fp32 MFMA registers.
+// Partial (max, sum, output) of every split go to the workspace; a merge kernel combines them.
+#include "cas_device.hpp"
+#include "cas_internal.hpp"
+
+namespace cas {
+
+typedef short bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct AttnArgs {
+  KvGeom g;
+  const uint32_t* spec_pool;
+  const uint32_t* verif_pool;
+  const int32_t* page_row;  // page table row of the sequence
+  int layer, len, nsplit, pages_per_split;
+  const uint16_t* Q;
+  int ncols, n_q_heads, grp;  // grp = query heads per kv head
+  const uint16_t* Knew;
+  const uint16_t* Vnew;
+  int n_new;
+  float scale;
+  float* part;  // [nsplit + 1][n_kv_heads][R][132]
+  uint16_t* O;
+};
+
+constexpr int kPT = 64;          // tokens per page
+constexpr int kQP = 136;         // Q row pitch (bf16)
+constexpr int kKG = 36, kKP = 148;  // K tile: group pitch (4 dump + 32), row pitch
+constexpr int kVP = 72;          // transposed V tile: token pitch per channel row
+constexpr int kVR = 132;         // channel rows: 4 groups x (1 dump + 32)
+constexpr int kSP = 68;          // score row pitch (float)
+constexpr int kPP = 72;          // probability row pitch (bf16)
+constexpr int kPartStride = 132;
+
+template <int MT>
+constexpr size_t attn_lds_bytes() {
+  return sizeof(uint16_t) * (MT * 16 * kQP + kPT * kKP + kVR * kVP + 2 * MT * 16 * kPP) +
+         sizeof(float) * (MT * 16 * kSP + 3 * MT * 16);
+}
+
+template <int MT, bool FULL, int T>
+__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
+  extern __shared__ uint16_t lds16[];
+  uint16_t* Qs = lds16;                       // [MT*16][kQP]
+  uint16_t* Kt = Qs + MT * 16 * kQP;          // [64][kKP]
+  uint16_t* Vt = Kt + kPT * kKP;              // [kVR][kVP]
+  uint16_t* Ph = Vt + kVR * kVP;              // [MT*16][kPP]
+  uint16_t* Pl = Ph + MT * 16 * kPP;          // [MT*16][kPP]
+  float* S = reinterpret_cast<float*>(Pl + MT * 16 * kPP);  // [MT*16][kSP]
+  float* s_m = S + MT * 16 * kSP;             // running max per row
+  float* s_l = s_m + MT * 16;                 // running sum per row
+  float* s_c = s_l + MT * 16;                 // rescale factor of the current page
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int split = blockIdx.x, head = blockIdx.y;
+  const int R = a.ncols * a.grp;
+  const KvGeom& g = a.g;
+
+  // ---- queries of this kv head: row rr = column * grp + member
+  for (int i = tid; i < MT * 16 * 128; i += 256) {
+    int rr = i >> 7, d = i & 127;
+    uint16_t v = 0;
+    if (rr < R) {
+      int c = rr / a.grp, gi = rr - c * a.grp;
+      v = a.Q[((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d];
+    }
+    Qs[rr * kQP + d] = v;
+  }
+  for (int i = tid; i < MT * 16; i += 256) {
+    s_m[i] = -INFINITY;
+    s_l[i] = 0.f;
+    s_c[i] = 1.f;
+  }
+  for (int i = tid; i < kVR * kVP; i += 256) Vt[i] = 0;
+  for (int i = tid; i < kPT * kKP; i += 256) Kt[i] = 0;
+  f32x4 Oacc[MT][2];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    Oacc[mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    Oacc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  __syncthreads();
+
+  const int r = tid >> 2, j = tid & 3;           // decode role: token r of the page, word j
+  const int mi = lane & 15, mq = lane >> 4;      // MFMA role
+  uint16_t* krow = Kt + r * kKP + j * kKG + 4;
+  uint16_t* vcol = Vt + (33 * j + 1) * kVP + r;
+
+  const bool new_tokens = split == a.nsplit;     // the last workgroup handles the in-flight tokens
+  const int page_lo = new_tokens ? 0 : split * a.pages_per_split;
+  const int total_pages = (a.len + kPT - 1) / kPT;
+  const int page_hi = new_tokens ? 1 : min(total_pages, page_lo + a.pages_per_split);
+
+  for (int pg = page_lo; pg < page_hi; ++pg) {
+    const int tok0 = pg * kPT;
+    const int ntok = new_tokens ? a.n_new : min(kPT, a.len - tok0);
+    const bool live = r < ntok;
+    const uint32_t* ks = nullptr; const uint32_t* kvf = nullptr;
+    const uint32_t* vs = nullptr; const uint32_t* vvf = nullptr;
+    if (!new_tokens) {
+      const int page = a.page_row[pg];
+      const size_t tk = (((size_t)a.layer * g.n_pages + page) * 2 + 0) * g.n_kv_heads + head;
+      const size_t tv = tk + g.n_kv_heads;
+      ks = a.spec_pool + tk * g.tile_spec_words;
+      vs = a.spec_pool + tv * g.tile_spec_words;
+      kvf = a.verif_pool + tk * g.tile_verif_words;
+      vvf = a.verif_pool + tv * g.tile_verif_words;
+    }
+    // ---- 1. K tile
+    {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) *reinterpret_cast<uint64_t*>(krow + 4 * q) = 0ull;
+      if (new_tokens) {
+        if (live) {
+          const uint16_t* src = a.Knew + ((size_t)r * g.n_kv_heads + head) * 128 + 32 * j;
+#pragma unroll
+          for (int q = 0; q < 8; ++q)
+            *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
+        }
+      } else {
+        uint32_t m = live ? ks[r * 4 + j] : 0u;
+        int cnt = __popc(m);
+        int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
+        uint32_t p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
+        uint32_t u = 32u * j - p;
+        uint32_t pm = (FULL && live) ? ~m : 0u;
+        decode_word<T, FULL>(m, pm, p, u, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw,
+                             [&](int pos, uint16_t v) { krow[pos] = v; });
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    // ---- 2. scores of this wave's 16 tokens against all query rows
+    {
+      const uint16_t* b_base = Kt + (16 * wv + mi) * kKP + 4 + 4 * mq;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        f32x4 C = {0.f, 0.f, 0.f, 0.f};
+        const uint16_t* a_base = Qs + (mt * 16 + mi) * kQP + 4 * mq;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+          bf16x4 av = *reinterpret_cast<const bf16x4*>(a_base + kk * 16);
+          bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + (kk >> 1) * kKG + (kk & 1) * 16);
+          C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, bv, C, 0, 0, 0);
+        }
+        const int t = 16 * wv + mi;  // token of this lane's score column
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int rr = mt * 16 + 4 * mq + e;
+          bool ok = t < ntok;
+          if (new_tokens) {  // column c sees in-flight tokens 0 .. n_new - ncols + c
+            int c = rr / a.grp;
+            ok = ok && (t <= a.n_new - a.ncols + c);
+          }
+          S[rr * kSP + t] = ok ? C[e] * a.scale : -INFINITY;
+        }
+      }
+    }
+    __syncthreads();
+    // ---- 3. online softmax: wave w owns rows w, w+4, ...; lane = token
+    for (int rr = wv; rr < R; rr += 4) {
+      float s = S[rr * kSP + lane];
+      float mx = wave_max(s);
+      float m_old = s_m[rr];
+      float m_new = fmaxf(m_old, mx);
+      float p = (s == -INFINITY) ? 0.f : __expf(s - m_new);
+      float sc = (m_old == -INFINITY) ? 0.f : __expf(m_old - m_new);
+      float ps = wave_sum(p);
+      uint16_t ph = f32_to_bf16(p);
+      uint16_t pl = f32_to_bf16(p - bf16_to_f32(ph));
+      Ph[rr * kPP + lane] = ph;
+      Pl[rr * kPP + lane] = pl;
+      if (lane == 0) {
+        s_m[rr] = m_new;
+        s_l[rr] = s_l[rr] * sc + ps;
+        s_c[rr] = sc;
+      }
+    }
+    // ---- 4. V tile, transposed: Vt[channel][token]
+    {
+#pragma unroll
+      for (int c = 0; c < 32; ++c) vcol[c * kVP] = 0;
+      if (new_tokens) {
+        if (live) {
+          const uint16_t* src = a.Vnew + ((size_t)r * g.n_kv_heads + head) * 128 + 32 * j;
+#pragma unroll
+          for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
+        }
+      } else {
+        uint32_t m = live ? vs[r * 4 + j] : 0u;
+        int cnt = __popc(m);
+        int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
+        uint32_t p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
+        uint32_t u = 32u * j - p;
+        uint32_t pm = (FULL && live) ? ~m : 0u;
+        decode_word<T, FULL>(m, pm, p, u, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw,
+                             [&](int pos, uint16_t v) { vcol[pos * kVP] = v; });
+      }
+    }
+    __syncthreads();
+    // ---- 5. O = O * rescale + P V ; wave w owns channels 32w .. 32w+31
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      f32x4 scv;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) scv[e] = s_c[mt * 16 + 4 * mq + e];
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        f32x4 C = Oacc[mt][nt] * scv;
+        const uint16_t* b_base = Vt + (33 * wv + 1 + nt * 16 + mi) * kVP + 4 * mq;
+        const uint16_t* ah = Ph + (mt * 16 + mi) * kPP + 4 * mq;
+        const uint16_t* al = Pl + (mt * 16 + mi) * kPP + 4 * mq;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+          bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + kb * 16);
+          C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*reinterpret_cast<const bf16x4*>(ah + kb * 16), bv, C, 0, 0, 0);
+          C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*reinterpret_cast<const bf16x4*>(al + kb * 16), bv, C, 0, 0, 0);
+        }
+        Oacc[mt][nt] = C;
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- partial result of this split
+  float* part = a.part + ((size_t)split * g.n_kv_heads + head) * R * kPartStride;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        int rr = mt * 16 + 4 * mq + e;
+        if (rr < R) part[rr * kPartStride + 32 * wv + nt * 16 + mi] = Oacc[mt][nt][e];
+      }
+  if (tid < R) {
+    part[tid * kPartStride + 128] = s_m[tid];
+    part[tid * kPartStride + 129] = s_l[tid];
+  }
+}
+
+// Combine the splits: o = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, rounded to bf16.
+__global__ __launch_bounds__(128) void attn_merge_kernel(AttnArgs a) {
+  const int rr = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
+  const int R = a.ncols * a.grp;
+  float M = -INFINITY;
+  for (int s = 0; s <= a.nsplit; ++s)
+    M = fmaxf(M, a.part[(((size_t)s * a.g.n_kv_heads + head) * R + rr) * kPartStride + 128]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s <= a.nsplit; ++s) {
+    const float* p = a.part + (((size_t)s * a.g.n_kv_heads + head) * R + rr) * kPartStride;
+    float m = p[128];
+    if (m == -INFINITY) continue;
+    float w = __expf(m - M);
+    num += w * p[d];
+    den += w * p[129];
+  }
+  const int c = rr / a.grp, gi = rr - c * a.grp;
+  a.O[((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d] = f32_to_bf16(num / den);
+}
+
+template <int MT, bool FULL>
+static int launch_mt(cas_ctx* ctx, const AttnArgs& a, dim3 grid) {
+  constexpr size_t lds = attn_lds_bytes<MT>();
+#define CAS_LAUNCH(TV)                                                                                          \
+  case TV:                                                                                                      \
+    if (lds > 48 * 1024)                                                                                        \
+      CAS_HIP(ctx, hipFuncSetAttribute((const void*)attn_partial_kernel<MT, FULL, TV>,                          \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                  \
+    hipLaunchKernelGGL((attn_partial_kernel<MT, FULL, TV>), grid, dim3(256), lds, ctx->stream, a);              \
+    break;
+  switch (a.g.t) {
+    CAS_LAUNCH(0) CAS_LAUNCH(1) CAS_LAUNCH(2) CAS_LAUNCH(3) CAS_LAUNCH(4) CAS_LAUNCH(5) CAS_LAUNCH(6) CAS_LAUNCH(7)
+    default: return CAS_EINVAL;
+  }
+#undef CAS_LAUNCH
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
+}
+
+int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
+  const KvGeom& g = kv->geom;
+  AttnArgs a;
+  a.g = g;
+  a.spec_pool = (const uint32_t*)kv->d_spec;
+  a.verif_pool = (const uint32_t*)kv->d_verif;
+  a.page_row = kv->d_page_table + (size_t)c.seq * g.max_pages_per_seq;
+  a.layer = c.layer;
+  a.len = kv->h_len[c.seq];
+  a.Q = c.Q; a.ncols = c.ncols; a.n_q_heads = c.n_q_heads; a.grp = c.n_q_heads / g.n_kv_heads;
+  a.Knew = c.Knew; a.Vnew = c.Vnew; a.n_new = c.n_new;
+  a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
+  a.O = c.O;
+  const int R = a.ncols * a.grp;
+  const int MT = (R + 15) / 16;
+  if (MT < 1 || MT > 3 || c.n_new > kPT || c.n_new < c.ncols) return CAS_EINVAL;
+  const int pages = (a.len + kPT - 1) / kPT;
+  int want = std::max(1, (ctx->num_cu * 2) / g.n_kv_heads);
+  a.nsplit = std::min(pages, want);
+  a.pages_per_split = a.nsplit ? (pages + a.nsplit - 1) / a.nsplit : 1;
+  a.nsplit = a.nsplit ? (pages + a.pages_per_split - 1) / a.pages_per_split : 0;
+  size_t need = sizeof(float) * (size_t)(a.nsplit + 1) * g.n_kv_heads * R * kPartStride;
+  if (need > ctx->ws_bytes || !ctx->d_ws) return CAS_ENOMEM;
+  a.part = (float*)ctx->d_ws;
+  dim3 grid(a.nsplit + 1, g.n_kv_heads);
+  int rc;
+  if (c.full) {
+    rc = MT == 1 ? launch_mt<1, true>(ctx, a, grid) : MT == 2 ? launch_mt<2, true>(ctx, a, grid)
+                                                               : launch_mt<3, true>(ctx, a, grid);
+  } else {
+    rc = MT == 1 ? launch_mt<1, false>(ctx, a, grid) : MT == 2 ? launch_mt<2, false>(ctx, a, grid)
+                                                                : launch_mt<3, false>(ctx, a, grid);
+  }
+  if (rc != CAS_OK) return rc;
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(R, g.n_kv_heads), dim3(128), 0, ctx->stream, a);
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
+}
+
+}  // namespace cas

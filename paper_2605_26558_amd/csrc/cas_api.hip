@@ -109,6 +109,104 @@ int cas_gemm_verify(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, con
   return cas::launch_gemm_verify(ctx, *desc, d_spec, d_verif, d_X, ncols, d_Y);
 }
 
+int cas_kv_desc_init(cas_kv_desc* d) {
+  if (!d) return CAS_EINVAL;
+  if (d->head_dim != 128 || d->page_tokens != 64) return CAS_ENOTSUP;
+  if (d->n_layers < 1 || d->n_kv_heads < 1 || d->n_pages < 1 || d->max_seqs < 1 || d->max_pages_per_seq < 1)
+    return CAS_EINVAL;
+  if (d->fmt.trunc_bits < 0 || d->fmt.trunc_bits > 7 || d->fmt.keep_permille < 0 || d->fmt.keep_permille > 1000)
+    return CAS_EINVAL;
+  if (d->fmt.exp_mode != 0) return CAS_ENOTSUP;
+  const int t = d->fmt.trunc_bits;
+  int64_t K = ((int64_t)d->fmt.keep_permille * d->head_dim + 500) / 1000;
+  K = std::max<int64_t>(0, std::min<int64_t>(d->head_dim, K));
+  d->K = (int32_t)K;
+  d->sw = (int32_t)words(K * (16 - t));
+  d->lw = (int32_t)words(K * t);
+  d->pw = (int32_t)words((d->head_dim - K) * 16);
+  d->tile_spec_bytes = up256((int64_t)d->page_tokens * (4 + d->sw) * 4);
+  d->tile_verif_bytes = up256((int64_t)d->page_tokens * (d->lw + d->pw) * 4);
+  const int64_t tiles = (int64_t)d->n_layers * d->n_pages * 2 * d->n_kv_heads;
+  d->spec_pool_bytes = tiles * d->tile_spec_bytes + kSlack;
+  d->verif_pool_bytes = tiles * d->tile_verif_bytes + kSlack;
+  return CAS_OK;
+}
+
+int cas_kv_create(const cas_kv_desc* desc, void* d_spec_pool, void* d_verif_pool, const int32_t* d_page_table,
+                  cas_kv** out) {
+  if (!desc || !d_spec_pool || !d_verif_pool || !d_page_table || !out) return CAS_EINVAL;
+  cas_kv_desc chk = *desc;
+  int rc = cas_kv_desc_init(&chk);
+  if (rc != CAS_OK) return rc;
+  if (chk.spec_pool_bytes != desc->spec_pool_bytes || chk.verif_pool_bytes != desc->verif_pool_bytes) return CAS_EINVAL;
+  if (!cas::aligned256(d_spec_pool) || !cas::aligned256(d_verif_pool)) return CAS_EINVAL;
+  cas_kv* kv = new (std::nothrow) cas_kv();
+  if (!kv) return CAS_ENOMEM;
+  kv->desc = chk;
+  cas::KvGeom& g = kv->geom;
+  g.n_layers = chk.n_layers; g.n_kv_heads = chk.n_kv_heads; g.page_tokens = chk.page_tokens;
+  g.n_pages = chk.n_pages; g.max_pages_per_seq = chk.max_pages_per_seq;
+  g.K = chk.K; g.t = chk.fmt.trunc_bits; g.sw = chk.sw; g.lw = chk.lw; g.pw = chk.pw;
+  g.tile_spec_words = (int)(chk.tile_spec_bytes / 4);
+  g.tile_verif_words = (int)(chk.tile_verif_bytes / 4);
+  kv->d_spec = d_spec_pool; kv->d_verif = d_verif_pool; kv->d_page_table = d_page_table;
+  kv->h_len = new (std::nothrow) int32_t[chk.max_seqs]();
+  if (!kv->h_len) { delete kv; return CAS_ENOMEM; }
+  *out = kv;
+  return CAS_OK;
+}
+
+int cas_kv_destroy(cas_kv* kv) {
+  if (kv) { delete[] kv->h_len; delete kv; }
+  return CAS_OK;
+}
+
+static int check_seq(const cas_kv* kv, int layer, int seq) {
+  if (!kv || seq < 0 || seq >= kv->desc.max_seqs || layer < 0 || layer >= kv->desc.n_layers) return CAS_EINVAL;
+  return CAS_OK;
+}
+
+int cas_kv_append(cas_ctx* ctx, cas_kv* kv, int layer, int seq, const uint16_t* d_K, const uint16_t* d_V, int n_tok) {
+  if (!ctx || !d_K || !d_V || n_tok < 0 || check_seq(kv, layer, seq) != CAS_OK) return CAS_EINVAL;
+  const int64_t cap = (int64_t)kv->desc.max_pages_per_seq * kv->desc.page_tokens;
+  if ((int64_t)kv->h_len[seq] + n_tok > cap) return CAS_ENOMEM;
+  return cas::launch_kv_append(ctx, kv, layer, seq, d_K, d_V, n_tok, kv->h_len[seq]);
+}
+
+int cas_kv_set_len(cas_kv* kv, int seq, int32_t len) {
+  if (check_seq(kv, 0, seq) != CAS_OK || len < 0) return CAS_EINVAL;
+  if ((int64_t)len > (int64_t)kv->desc.max_pages_per_seq * kv->desc.page_tokens) return CAS_ENOMEM;
+  kv->h_len[seq] = len;
+  return CAS_OK;
+}
+
+int cas_kv_len(const cas_kv* kv, int seq, int32_t* len) {
+  if (check_seq(kv, 0, seq) != CAS_OK || !len) return CAS_EINVAL;
+  *len = kv->h_len[seq];
+  return CAS_OK;
+}
+
+int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_tok, int full, uint16_t* d_K,
+                uint16_t* d_V) {
+  if (!ctx || !d_K || !d_V || n_tok < 0 || pos0 < 0 || check_seq(kv, layer, seq) != CAS_OK) return CAS_EINVAL;
+  if ((int64_t)pos0 + n_tok > (int64_t)kv->desc.max_pages_per_seq * kv->desc.page_tokens) return CAS_EINVAL;
+  return cas::launch_kv_read(ctx, kv, layer, seq, pos0, n_tok, full, d_K, d_V);
+}
+
+int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q, int ncols,
+                  int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew, int n_new, uint16_t* d_O) {
+  if (!ctx || !d_Q || !d_Knew || !d_Vnew || !d_O || check_seq(kv, layer, seq) != CAS_OK) return CAS_EINVAL;
+  if (ncols < 1 || n_new < ncols || n_new > 64 || n_q_heads < kv->desc.n_kv_heads ||
+      n_q_heads % kv->desc.n_kv_heads != 0)
+    return CAS_EINVAL;
+  if (ncols * (n_q_heads / kv->desc.n_kv_heads) > 48) return CAS_EINVAL;
+  cas::AttnCall c;
+  c.layer = layer; c.seq = seq; c.full = full ? 1 : 0;
+  c.Q = d_Q; c.ncols = ncols; c.n_q_heads = n_q_heads;
+  c.Knew = d_Knew; c.Vnew = d_Vnew; c.n_new = n_new; c.O = d_O;
+  return cas::launch_attention(ctx, kv, c);
+}
+
 int cas_accept(const int32_t* h_draft, const int32_t* h_target, int k, int32_t* n_accepted, int32_t* h_out) {
   if (k < 0 || !h_target || !n_accepted || !h_out || (k > 0 && !h_draft)) return CAS_EINVAL;
   int n = 0;

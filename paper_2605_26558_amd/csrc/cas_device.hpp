@@ -103,4 +103,90 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// Decode the values of one 32-column bitmap word from the packed streams and hand each
+// (column position, bf16 word) to `write`.  m: kept mask, pm: pruned mask (0 when only the
+// speculation data is read), p / u: kept / pruned values of the row before this word.
+// A lane that runs out of bits keeps calling write with position -1 and a don't-care value:
+// the caller maps -1 to a dump slot.  All 64 lanes of the wave must call this together.
+template <int T, bool FULL, class W>
+__device__ __forceinline__ void decode_word(uint32_t m, uint32_t pm, uint32_t p, uint32_t u,
+                                            const uint32_t* __restrict__ sp_row, const uint32_t* __restrict__ lo_row,
+                                            const uint32_t* __restrict__ pr_row, W&& write) {
+  constexpr int FW = 16 - T;
+  constexpr int LW = T > 0 ? T : 1;
+  uint32_t ws[FW], wl[LW], wp[16];
+  {
+    uint32_t bit = p * FW, sh = bit & 31u;
+    const uint32_t* src = sp_row + (bit >> 5);
+    uint32_t d[FW + 1];
+#pragma unroll
+    for (int q = 0; q <= FW; ++q) d[q] = src[q];
+#pragma unroll
+    for (int q = 0; q < FW; ++q) ws[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
+  }
+  if constexpr (FULL && T > 0) {
+    uint32_t bit = p * T, sh = bit & 31u;
+    const uint32_t* src = lo_row + (bit >> 5);
+    uint32_t d[T + 1];
+#pragma unroll
+    for (int q = 0; q <= T; ++q) d[q] = src[q];
+#pragma unroll
+    for (int q = 0; q < T; ++q) wl[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
+  }
+  if constexpr (FULL) {
+    uint32_t sh = (u & 1u) << 4;
+    const uint32_t* src = pr_row + (u >> 1);
+    uint32_t d[17];
+#pragma unroll
+    for (int q = 0; q <= 16; ++q) d[q] = src[q];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) wp[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
+  }
+  auto kept_group = [&](auto G) {
+    static_for<0, 8>([&](auto I) {
+      constexpr int e = decltype(G)::value * 8 + decltype(I)::value;
+      int pos = lowest_bit(m);
+      m &= m - 1u;
+      uint32_t v = field_at<FW, e>(ws) << T;
+      if constexpr (FULL && T > 0) v |= field_at<T, e>(wl);
+      write(pos, (uint16_t)v);
+    });
+  };
+  if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+    kept_group(std::integral_constant<int, 0>{});
+    if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+      kept_group(std::integral_constant<int, 1>{});
+      if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+        kept_group(std::integral_constant<int, 2>{});
+        if (__builtin_amdgcn_ballot_w64(m != 0u)) kept_group(std::integral_constant<int, 3>{});
+      }
+    }
+  }
+  if constexpr (FULL) {
+    auto pruned_group = [&](auto G) {
+      static_for<0, 8>([&](auto I) {
+        constexpr int e = decltype(G)::value * 8 + decltype(I)::value;
+        int pos = lowest_bit(pm);
+        pm &= pm - 1u;
+        write(pos, (uint16_t)(wp[e >> 1] >> ((e & 1) * 16)));
+      });
+    };
+    if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
+      pruned_group(std::integral_constant<int, 0>{});
+      if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
+        pruned_group(std::integral_constant<int, 1>{});
+        if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
+          pruned_group(std::integral_constant<int, 2>{});
+          if (__builtin_amdgcn_ballot_w64(pm != 0u)) pruned_group(std::integral_constant<int, 3>{});
+        }
+      }
+    }
+  }
+}
+
+template <int CTRL>
+__device__ __forceinline__ int quad_dpp(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+
 }  // namespace cas

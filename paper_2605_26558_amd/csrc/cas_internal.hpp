@@ -23,10 +23,40 @@ struct cas_ctx {
   } while (0)
 
 namespace cas {
+// geometry of the compressed KV cache as the kernels see it (sizes in 32-bit words)
+struct KvGeom {
+  int n_layers, n_kv_heads, page_tokens, n_pages, max_pages_per_seq;
+  int K, t, sw, lw, pw;
+  int tile_spec_words, tile_verif_words;
+};
+}  // namespace cas
+
+struct cas_kv {
+  cas_kv_desc desc;
+  cas::KvGeom geom;
+  void* d_spec;
+  void* d_verif;
+  const int32_t* d_page_table;
+  int32_t* h_len;  // committed length of every sequence (host mirror; kernels get it as an argument)
+};
+
+namespace cas {
 inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
 int launch_encode_weight(cas_ctx*, const uint16_t* W, int64_t ld, const float* act, const cas_wdesc&, void* spec, void* verif);
 int launch_decode_weight(cas_ctx*, const cas_wdesc&, const void* spec, const void* verif, uint16_t* out, int64_t ld);
 int launch_gemv_draft(cas_ctx*, const cas_wdesc&, const void* spec, const uint16_t* x, int batch, float* y);
 int launch_gemm_verify(cas_ctx*, const cas_wdesc&, const void* spec, const void* verif, const uint16_t* X, int ncols, float* Y);
+int launch_kv_append(cas_ctx*, cas_kv*, int layer, int seq, const uint16_t* K, const uint16_t* V, int n_tok, int pos0);
+int launch_kv_read(cas_ctx*, cas_kv*, int layer, int seq, int pos0, int n_tok, int full, uint16_t* K, uint16_t* V);
+struct AttnCall {
+  int layer, seq, full;        // full: 0 = speculation data only (draft), 1 = exact reconstruction
+  const uint16_t* Q;           // [ncols][n_q_heads][128]
+  int ncols, n_q_heads;
+  const uint16_t* Knew;        // [n_new][n_kv_heads][128] uncompressed in-flight vectors
+  const uint16_t* Vnew;
+  int n_new;
+  uint16_t* O;                 // [ncols][n_q_heads][128]
+};
+int launch_attention(cas_ctx*, cas_kv*, const AttnCall&);
 }  // namespace cas

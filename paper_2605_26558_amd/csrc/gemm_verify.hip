@@ -35,11 +35,6 @@ constexpr int kXPitch = kSlabCols + 8;  // bf16 per X row in LDS
 constexpr int kGroupPitch = 36;         // 4 dump slots + 32 columns
 constexpr int kTilePitch = 148;         // 4 groups + 4 pad, keeps 8-byte alignment, spreads banks
 
-template <int CTRL>
-__device__ __forceinline__ int quad_dpp(int v) {
-  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
-}
-
 template <int T>
 __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
   constexpr int FW = 16 - T;

@@ -1,0 +1,140 @@
+"""GPU parity of the compressed KV cache (online encode, read-back) and of draft / verify
+attention against the oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import cassandra_oracle as O
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2605_26558_amd import binding as B
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    return torch, B, B.Context(workspace=ws)
+
+
+def _dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+
+
+def _host(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("keep,t", [(600, 4), (1000, 4), (250, 0), (0, 4), (500, 7)])
+def test_kv_append_is_bit_exact(env, keep, t):
+    torch, B, ctx = env
+    print(f"case keep={keep} t={t}", flush=True)
+    heads, layers, ntok = 2, 2, 75
+    perm = torch.tensor([[3, 0, 2, 1]], dtype=torch.int32)          # a non-trivial page table
+    kv = B.KVCache(ctx, layers, heads, n_pages=4, max_seqs=1, max_pages_per_seq=4, keep_permille=keep,
+                   trunc_bits=t, page_table=perm)
+    Kh = synth.kv_tensor(ntok, heads, 128, seed=1)
+    Vh = synth.kv_tensor(ntok, heads, 128, seed=2, outlier_channels=0)
+    Kh[5, 0, :] = Kh[5, 0, 0]                                        # all-equal magnitudes: tie rule
+    Kh[6, 1, 10] = Kh[6, 1, 90]
+    for layer in range(layers):
+        B.cas_kv_append(ctx, kv, layer, 0, _dev(torch, Kh[:70]), _dev(torch, Vh[:70]))
+    B.cas_kv_set_len(kv, 0, 70)
+    for layer in range(layers):
+        B.cas_kv_append(ctx, kv, layer, 0, _dev(torch, Kh[70:]), _dev(torch, Vh[70:]))
+    B.cas_kv_set_len(kv, 0, ntok)
+    assert B.cas_kv_len(kv, 0) == ntok
+    for layer in range(layers):
+        Kf, Vf = B.cas_kv_read(ctx, kv, layer, 0, 0, ntok, full=True)
+        np.testing.assert_array_equal(_host(Kf), Kh)
+        np.testing.assert_array_equal(_host(Vf), Vh)
+        Kd, Vd = B.cas_kv_read(ctx, kv, layer, 0, 0, ntok, full=False)
+        pk = O.encode_kv(Kh.reshape(-1, 128), keep, t)
+        pv = O.encode_kv(Vh.reshape(-1, 128), keep, t)
+        np.testing.assert_array_equal(_host(Kd).reshape(-1, 128), O.decode_draft(pk))
+        np.testing.assert_array_equal(_host(Vd).reshape(-1, 128), O.decode_draft(pv))
+    # raw streams of one tile against the oracle's packing (layer 1, K, head 1, page slot 0 -> page 3)
+    d = kv.desc
+    spec = kv.spec_pool.cpu().numpy()
+    verif = kv.verif_pool.cpu().numpy()
+    tile = ((1 * d.n_pages + 3) * 2 + 0) * heads + 1
+    ts = spec[tile * d.tile_spec_bytes: (tile + 1) * d.tile_spec_bytes].view("<u4")
+    tv = verif[tile * d.tile_verif_bytes: (tile + 1) * d.tile_verif_bytes].view("<u4")
+    p = O.encode_kv(Kh[:64, 1, :], keep, t)
+    np.testing.assert_array_equal(ts[: 64 * 4].reshape(64, 4), p.bitmap)
+    np.testing.assert_array_equal(ts[64 * 4: 64 * (4 + d.sw)].reshape(64, d.sw), p.spec)
+    np.testing.assert_array_equal(tv[: 64 * d.lw].reshape(64, d.lw), p.lo)
+    np.testing.assert_array_equal(tv[64 * d.lw: 64 * (d.lw + d.pw)].reshape(64, d.pw), p.pruned)
+    assert (d.K, d.sw, d.lw, d.pw) == (p.K, *O.stream_words(128, p.K, t)[1:])
+
+
+def _ref_attention(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv):
+    """Column c sees the cache and in-flight vectors 0 .. n_new - ncols + c."""
+    out = np.zeros((ncols, nq, 128), dtype=np.uint16)
+    n_new = Kn.shape[0]
+    for c in range(ncols):
+        vis = n_new - ncols + c + 1
+        k = np.concatenate([Kc, Kn[:vis]], axis=0)
+        v = np.concatenate([Vc, Vn[:vis]], axis=0)
+        out[c] = O.attention(Q[c], k, v, nq, nkv)
+    return out
+
+
+def _attn_tol(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv, ref):
+    """2e-3 |p| |V_d| per channel plus half a bf16 ulp of the rounded output."""
+    grp = nq // nkv
+    n_new = Kn.shape[0]
+    tol = np.zeros(ref.shape)
+    for c in range(ncols):
+        vis = n_new - ncols + c + 1
+        k = O.bf16_to_f64(np.concatenate([Kc, Kn[:vis]], axis=0))
+        v = O.bf16_to_f64(np.concatenate([Vc, Vn[:vis]], axis=0))
+        q = O.bf16_to_f64(Q[c])
+        for h in range(nq):
+            s = k[:, h // grp, :] @ q[h] / np.sqrt(128.0)
+            p = np.exp(s - s.max()); p /= p.sum()
+            tol[c, h] = 2e-3 * np.linalg.norm(p) * np.linalg.norm(v[:, h // grp, :], axis=0)
+    return tol + 2.0 ** -8 * np.abs(ref)
+
+
+@pytest.mark.parametrize("len_cache,ncols,n_new,full", [
+    (150, 1, 1, False), (150, 1, 3, False), (0, 1, 1, False), (64, 1, 2, False), (1, 1, 1, False),
+    (150, 5, 5, True), (0, 3, 3, True), (130, 7, 7, True), (200, 9, 9, True), (63, 1, 1, True),
+])
+def test_attention_matches_oracle(env, len_cache, ncols, n_new, full):
+    torch, B, ctx = env
+    print(f"case len={len_cache} ncols={ncols} n_new={n_new} full={full}", flush=True)
+    nq, nkv, layers = 8, 2, 2
+    kv = B.KVCache(ctx, layers, nkv, n_pages=8, max_seqs=2, max_pages_per_seq=4,
+                   page_table=torch.tensor([[5, 1, 7, 2], [0, 3, 4, 6]], dtype=torch.int32))
+    seq, layer = 1, 1
+    Kh = synth.kv_tensor(max(len_cache, 1), nkv, 128, seed=3)
+    Vh = synth.kv_tensor(max(len_cache, 1), nkv, 128, seed=4, outlier_channels=0)
+    if len_cache:
+        B.cas_kv_append(ctx, kv, layer, seq, _dev(torch, Kh[:len_cache]), _dev(torch, Vh[:len_cache]))
+    B.cas_kv_set_len(kv, seq, len_cache)
+    Q = synth.normal_bf16((ncols, nq, 128), 1.0, seed=5)
+    Kn = synth.kv_tensor(n_new, nkv, 128, seed=6)
+    Vn = synth.kv_tensor(n_new, nkv, 128, seed=7, outlier_channels=0)
+    out = _host(B.cas_attention(ctx, kv, layer, seq, full, _dev(torch, Q), _dev(torch, Kn), _dev(torch, Vn)))
+    if len_cache:
+        pk = O.encode_kv(Kh[:len_cache].reshape(-1, 128), 600, 4)
+        pv = O.encode_kv(Vh[:len_cache].reshape(-1, 128), 600, 4)
+        dec = O.decode_full if full else O.decode_draft
+        Kc = dec(pk).reshape(len_cache, nkv, 128)
+        Vc = dec(pv).reshape(len_cache, nkv, 128)
+    else:
+        Kc = np.zeros((0, nkv, 128), np.uint16); Vc = Kc.copy()
+    ref = _ref_attention(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv)
+    reff = O.bf16_to_f64(ref)
+    err = np.abs(O.bf16_to_f64(out) - reff)
+    tol = _attn_tol(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv, reff)
+    assert (err <= tol).all(), float((err / tol).max())
+    print("max err / tol", float((err / tol).max()), flush=True)
+    if full and ncols > 1:
+        # a column's output does not depend on how many columns are verified together
+        for c in (0, ncols - 1):
+            vis = n_new - ncols + c + 1
+            o1 = _host(B.cas_attention(ctx, kv, layer, seq, True, _dev(torch, Q[c:c + 1]),
+                                       _dev(torch, Kn[:vis]), _dev(torch, Vn[:vis])))
+            np.testing.assert_array_equal(o1[0], out[c])
