@@ -172,12 +172,88 @@ int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_to
  * d_Knew, d_Vnew: bf16 [n_new][n_kv_heads][head_dim], uncompressed, ncols <= n_new <= 64;
  * d_O: bf16 [ncols][n_q_heads][head_dim].  ncols * n_q_heads / n_kv_heads <= 48.
  * Uses the context workspace for the per-split partial results (CAS_ENOMEM if too small:
- * (splits + 1) * n_kv_heads * ncols * group * 132 floats, splits <= 2 * CUs / n_kv_heads).
- * A column's value does not depend on ncols.
+ * splits * n_kv_heads * ncols * group * 132 floats, one split per 128 positions).
+ * A column's value depends only on the positions it sees: not on ncols, and not on whether an
+ * earlier position is already committed or still in flight.
  */
 int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q,
                   int ncols, int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew,
                   int n_new, uint16_t* d_O);
+
+/* ---- model-level steps of one speculative round (Sec. 2.2, Sec. 4.1) --------------------- */
+
+/* Llama-3 style decoder (Fig. 2_1): RMSNorm -> q,k,v projection -> rotary embedding ->
+ * grouped-query attention -> output projection -> residual -> RMSNorm -> SwiGLU feed-forward
+ * -> residual; final RMSNorm and output head; greedy token = lowest index among the maxima. */
+typedef struct {
+  int32_t hidden, n_layers, n_q_heads, n_kv_heads, head_dim /* 128 */, ffn, vocab;
+  int32_t max_cols; /* largest k+1 (1..16); also the number of in-flight K/V slots per layer */
+  int32_t max_pos;  /* rows of the rotary table */
+  float rms_eps;
+} cas_model_cfg;
+
+/* One encoded linear layer: layout + the two device buffers (caller-owned). */
+typedef struct {
+  cas_wdesc desc;
+  const void* d_spec;
+  const void* d_verif;
+} cas_tensor;
+
+/* wqkv: [(n_q_heads + 2 n_kv_heads) * head_dim][hidden], rows ordered q heads, k heads, v heads;
+ * wo: [hidden][n_q_heads * head_dim]; wgu: [2 ffn][hidden] with the gate row of unit i at 2i
+ * and its up row at 2i+1; wd: [hidden][ffn]; d_g_*: bf16 [hidden] RMSNorm gains. */
+typedef struct {
+  cas_tensor wqkv, wo, wgu, wd;
+  const uint16_t* d_g_attn;
+  const uint16_t* d_g_ffn;
+} cas_layer_weights;
+
+typedef struct {
+  const cas_layer_weights* layers; /* HOST array [n_layers]; copied by cas_model_create */
+  cas_tensor lm_head;              /* [vocab][hidden] */
+  const uint16_t* d_embed;         /* bf16 [vocab][hidden], not encoded (one row is gathered) */
+  const uint16_t* d_g_final;       /* bf16 [hidden] */
+  const float* d_rope;             /* float [max_pos][head_dim/2][2] = cos, sin of the position angle */
+} cas_model_weights;
+
+typedef struct cas_model cas_model;
+
+/* Host only: bytes of activation scratch cas_model_create needs for this configuration. */
+int cas_model_act_bytes(const cas_model_cfg* cfg, size_t* bytes);
+/* d_act: caller-owned device block of at least that size (256-byte aligned); it holds the
+ * activations of a pass and the uncompressed K/V of the in-flight positions of ONE sequence. */
+int cas_model_create(const cas_model_cfg* cfg, const cas_model_weights* weights, void* d_act,
+                     size_t act_bytes, cas_model** out);
+int cas_model_destroy(cas_model* model);
+
+/* One draft pass (Sec. 4.1 draft inference): speculation data only for every linear layer and
+ * for the cache.  d_token_in: the token at in-flight slot `slot` (position len + slot);
+ * its K/V go to slot `slot`, earlier slots must hold the K/V of the previous draft passes of
+ * this round.  d_token_out: the drafted next token.  d_logits: NULL or float [vocab]. */
+int cas_draft_step(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const int32_t* d_token_in,
+                   int slot, int32_t* d_token_out, float* d_logits);
+
+/* One verification pass (Sec. 2.2, Sec. 4.1 target inference) over k+1 columns: d_tokens =
+ * pending token followed by the k drafts, at positions len .. len+k.  Exact weights and cache.
+ * d_target[c] = target model's token after column c.  Overwrites in-flight slots 0..k with the
+ * target's K/V.  d_logits: NULL or float [k+1][vocab].  k = 0 is plain decoding. */
+int cas_verify_step(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const int32_t* d_tokens,
+                    int k, int32_t* d_target, float* d_logits);
+
+/* After acceptance: format and append the target K/V of the pending token and the n_accepted
+ * accepted drafts (slots 0..n_accepted) to every layer of the cache, advance the length by
+ * n_accepted + 1, drop the remaining slots. */
+int cas_commit(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, int n_accepted);
+
+/* One whole round for one sequence: k draft passes chained on the device from `pending`, one
+ * verification pass, greedy acceptance, commit.  Synchronises the stream once to read the
+ * tokens.  h_out receives n_accepted + 1 tokens; the last one is the next pending token. */
+int cas_spec_round(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, int32_t pending, int k,
+                   int32_t* h_out, int32_t* n_accepted);
+
+/* Prefill (functional): runs n prompt tokens through the target path in chunks of max_cols
+ * columns and commits all of them.  d_tokens: int32 [n] on the device. */
+int cas_prefill(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const int32_t* d_tokens, int n);
 
 /* Greedy acceptance (Sec. 2.2).  Host only, no side effects.  h_draft: k drafted tokens;
  * h_target: k+1 target tokens.  n_accepted = number of leading positions where they are

@@ -40,6 +40,26 @@ class cas_kv_desc(C.Structure):
                 ("spec_pool_bytes", C.c_int64), ("verif_pool_bytes", C.c_int64)]
 
 
+class cas_model_cfg(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_layers", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32),
+                ("max_cols", C.c_int32), ("max_pos", C.c_int32), ("rms_eps", C.c_float)]
+
+
+class cas_tensor(C.Structure):
+    _fields_ = [("desc", cas_wdesc), ("d_spec", C.c_void_p), ("d_verif", C.c_void_p)]
+
+
+class cas_layer_weights(C.Structure):
+    _fields_ = [("wqkv", cas_tensor), ("wo", cas_tensor), ("wgu", cas_tensor), ("wd", cas_tensor),
+                ("d_g_attn", C.c_void_p), ("d_g_ffn", C.c_void_p)]
+
+
+class cas_model_weights(C.Structure):
+    _fields_ = [("layers", C.POINTER(cas_layer_weights)), ("lm_head", cas_tensor), ("d_embed", C.c_void_p),
+                ("d_g_final", C.c_void_p), ("d_rope", C.c_void_p)]
+
+
 _LIB = None
 
 _SIGNATURES = {
@@ -67,6 +87,18 @@ _SIGNATURES = {
                               C.c_void_p, C.c_void_p]),
     "cas_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
                                 C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
+    "cas_model_act_bytes": (C.c_int, [C.POINTER(cas_model_cfg), C.POINTER(C.c_size_t)]),
+    "cas_model_create": (C.c_int, [C.POINTER(cas_model_cfg), C.POINTER(cas_model_weights), C.c_void_p, C.c_size_t,
+                                   C.POINTER(C.c_void_p)]),
+    "cas_model_destroy": (C.c_int, [C.c_void_p]),
+    "cas_draft_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
+                                 C.c_void_p]),
+    "cas_verify_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
+                                  C.c_void_p]),
+    "cas_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
+    "cas_spec_round": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int,
+                                 C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "cas_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int]),
     "cas_accept": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32),
                              C.POINTER(C.c_int32)]),
 }
@@ -281,3 +313,74 @@ def cas_attention(ctx: Context, kv: KVCache, layer, seq, full, Q, Knew, Vnew, ou
     ctx._check(_lib().cas_attention(ctx.h, kv.h, layer, seq, 1 if full else 0, _ptr(Q), Q.shape[0], Q.shape[1],
                                     _ptr(Knew), _ptr(Vnew), Knew.shape[0], _ptr(out)), "cas_attention")
     return out
+
+
+def _tensor(ew: EncodedWeight) -> cas_tensor:
+    return cas_tensor(ew.desc, ew.spec.data_ptr(), ew.verif.data_ptr())
+
+
+class Model:
+    """Holds the encoded weights (device tensors stay referenced here) and the cas_model handle.
+
+    layers: list of dicts with EncodedWeight entries wqkv, wo, wgu, wd and bf16-bit tensors
+    g_attn, g_ffn; lm_head: EncodedWeight; embed, g_final: bf16-bit tensors; rope: float32
+    tensor [max_pos, 64, 2]."""
+
+    def __init__(self, ctx: Context, shape, layers, lm_head, embed, g_final, rope, max_cols):
+        torch = ctx._torch
+        self.ctx, self.shape = ctx, shape
+        self._keep = (layers, lm_head, embed, g_final, rope)
+        cfg = cas_model_cfg(shape.hidden, len(layers), shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                            shape.ffn, shape.vocab, max_cols, rope.shape[0], shape.rms_eps)
+        self.cfg = cfg
+        nbytes = C.c_size_t()
+        rc = _lib().cas_model_act_bytes(C.byref(cfg), C.byref(nbytes))
+        if rc != CAS_OK:
+            raise CasError(rc, "cas_model_act_bytes")
+        self.act = torch.empty(nbytes.value, dtype=torch.uint8, device="cuda")
+        arr = (cas_layer_weights * len(layers))()
+        for i, L in enumerate(layers):
+            arr[i] = cas_layer_weights(_tensor(L["wqkv"]), _tensor(L["wo"]), _tensor(L["wgu"]), _tensor(L["wd"]),
+                                       L["g_attn"].data_ptr(), L["g_ffn"].data_ptr())
+        w = cas_model_weights(arr, _tensor(lm_head), embed.data_ptr(), g_final.data_ptr(), rope.data_ptr())
+        h = C.c_void_p()
+        rc = _lib().cas_model_create(C.byref(cfg), C.byref(w), _ptr(self.act), nbytes.value, C.byref(h))
+        if rc != CAS_OK:
+            raise CasError(rc, "cas_model_create")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            _lib().cas_model_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def cas_draft_step(ctx, model: Model, kv: KVCache, seq, token_in, slot, token_out, logits=None):
+    ctx._check(_lib().cas_draft_step(ctx.h, model.h, kv.h, seq, _ptr(token_in), slot, _ptr(token_out),
+                                     _ptr(logits)), "cas_draft_step")
+
+
+def cas_verify_step(ctx, model: Model, kv: KVCache, seq, tokens, k, target, logits=None):
+    ctx._check(_lib().cas_verify_step(ctx.h, model.h, kv.h, seq, _ptr(tokens), k, _ptr(target), _ptr(logits)),
+               "cas_verify_step")
+
+
+def cas_commit(ctx, model: Model, kv: KVCache, seq, n_accepted):
+    ctx._check(_lib().cas_commit(ctx.h, model.h, kv.h, seq, n_accepted), "cas_commit")
+
+
+def cas_spec_round(ctx, model: Model, kv: KVCache, seq, pending, k):
+    out = (C.c_int32 * (k + 1))()
+    n = C.c_int32()
+    ctx._check(_lib().cas_spec_round(ctx.h, model.h, kv.h, seq, int(pending), k, out, C.byref(n)), "cas_spec_round")
+    return n.value, [out[i] for i in range(n.value + 1)]
+
+
+def cas_prefill(ctx, model: Model, kv: KVCache, seq, tokens):
+    ctx._check(_lib().cas_prefill(ctx.h, model.h, kv.h, seq, _ptr(tokens), tokens.numel()), "cas_prefill")

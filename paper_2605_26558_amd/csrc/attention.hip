@@ -2,7 +2,10 @@
 // Sec. 4.1 decides which data a pass may read): the draft pass rebuilds K and V from the
 // speculation data with zero padding, the verification pass rebuilds them exactly from both
 // pools.  The vectors of the in-flight tokens (draft tokens not yet verified, or the k+1
-// columns of the verification pass) arrive uncompressed.
+// columns of the verification pass) arrive uncompressed and are placed at the page rows their
+// positions will occupy, and a split always covers the same fixed number of pages: the value
+// of a query therefore depends only on the tokens it sees, not on whether they are already
+// committed, nor on the number of columns or the total length.
 //
 // One workgroup handles one kv head and one split of the sequence, page by page:
 //   1. thread (token r, word j) decodes its 32 channels of K into a 64 x 128 bf16 tile in LDS;
@@ -32,7 +35,7 @@ struct AttnArgs {
   const uint16_t* Vnew;
   int n_new;
   float scale;
-  float* part;  // [nsplit + 1][n_kv_heads][R][132]
+  float* part;  // [nsplit][n_kv_heads][R][132]
   uint16_t* O;
 };
 
@@ -44,6 +47,7 @@ constexpr int kVR = 132;         // channel rows: 4 groups x (1 dump + 32)
 constexpr int kSP = 68;          // score row pitch (float)
 constexpr int kPP = 72;          // probability row pitch (bf16)
 constexpr int kPartStride = 132;
+constexpr int kPagesPerSplit = 2;
 
 template <int MT>
 constexpr size_t attn_lds_bytes() {
@@ -99,38 +103,34 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   uint16_t* krow = Kt + r * kKP + j * kKG + 4;
   uint16_t* vcol = Vt + (33 * j + 1) * kVP + r;
 
-  const bool new_tokens = split == a.nsplit;     // the last workgroup handles the in-flight tokens
-  const int page_lo = new_tokens ? 0 : split * a.pages_per_split;
-  const int total_pages = (a.len + kPT - 1) / kPT;
-  const int page_hi = new_tokens ? 1 : min(total_pages, page_lo + a.pages_per_split);
+  const int page_lo = split * a.pages_per_split;
+  const int total = a.len + a.n_new;             // committed + in-flight positions
+  const int page_hi = min((total + kPT - 1) / kPT, page_lo + a.pages_per_split);
 
   for (int pg = page_lo; pg < page_hi; ++pg) {
     const int tok0 = pg * kPT;
-    const int ntok = new_tokens ? a.n_new : min(kPT, a.len - tok0);
-    const bool live = r < ntok;
-    const uint32_t* ks = nullptr; const uint32_t* kvf = nullptr;
-    const uint32_t* vs = nullptr; const uint32_t* vvf = nullptr;
-    if (!new_tokens) {
-      const int page = a.page_row[pg];
-      const size_t tk = (((size_t)a.layer * g.n_pages + page) * 2 + 0) * g.n_kv_heads + head;
-      const size_t tv = tk + g.n_kv_heads;
-      ks = a.spec_pool + tk * g.tile_spec_words;
-      vs = a.spec_pool + tv * g.tile_spec_words;
-      kvf = a.verif_pool + tk * g.tile_verif_words;
-      vvf = a.verif_pool + tv * g.tile_verif_words;
-    }
+    const int ntok = min(kPT, total - tok0);
+    const int pos = tok0 + r;                      // position of this thread's token
+    const bool live = pos < a.len;                 // committed: decode from the cache
+    const bool fresh = !live && pos < total;       // in flight: copy the uncompressed vector
+    const int page = a.page_row[pg];
+    const size_t tk = (((size_t)a.layer * g.n_pages + page) * 2 + 0) * g.n_kv_heads + head;
+    const size_t tv = tk + g.n_kv_heads;
+    const uint32_t* ks = a.spec_pool + tk * g.tile_spec_words;
+    const uint32_t* vs = a.spec_pool + tv * g.tile_spec_words;
+    const uint32_t* kvf = a.verif_pool + tk * g.tile_verif_words;
+    const uint32_t* vvf = a.verif_pool + tv * g.tile_verif_words;
     // ---- 1. K tile
     {
 #pragma unroll
       for (int q = 0; q < 8; ++q) *reinterpret_cast<uint64_t*>(krow + 4 * q) = 0ull;
-      if (new_tokens) {
-        if (live) {
-          const uint16_t* src = a.Knew + ((size_t)r * g.n_kv_heads + head) * 128 + 32 * j;
+      if (fresh) {
+        const uint16_t* src = a.Knew + ((size_t)(pos - a.len) * g.n_kv_heads + head) * 128 + 32 * j;
 #pragma unroll
-          for (int q = 0; q < 8; ++q)
-            *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
-        }
-      } else {
+        for (int q = 0; q < 8; ++q)
+          *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
+      }
+      {
         uint32_t m = live ? ks[r * 4 + j] : 0u;
         int cnt = __popc(m);
         int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
@@ -160,11 +160,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int rr = mt * 16 + 4 * mq + e;
-          bool ok = t < ntok;
-          if (new_tokens) {  // column c sees in-flight tokens 0 .. n_new - ncols + c
-            int c = rr / a.grp;
-            ok = ok && (t <= a.n_new - a.ncols + c);
-          }
+          // column c sees positions 0 .. len + n_new - ncols + c
+          const int c = rr / a.grp;
+          const bool ok = t < ntok && (tok0 + t <= total - a.ncols + c);
           S[rr * kSP + t] = ok ? C[e] * a.scale : -INFINITY;
         }
       }
@@ -193,13 +191,12 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     {
 #pragma unroll
       for (int c = 0; c < 32; ++c) vcol[c * kVP] = 0;
-      if (new_tokens) {
-        if (live) {
-          const uint16_t* src = a.Vnew + ((size_t)r * g.n_kv_heads + head) * 128 + 32 * j;
+      if (fresh) {
+        const uint16_t* src = a.Vnew + ((size_t)(pos - a.len) * g.n_kv_heads + head) * 128 + 32 * j;
 #pragma unroll
-          for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
-        }
-      } else {
+        for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
+      }
+      {
         uint32_t m = live ? vs[r * 4 + j] : 0u;
         int cnt = __popc(m);
         int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
@@ -257,10 +254,10 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(AttnArgs a) {
   const int rr = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
   const int R = a.ncols * a.grp;
   float M = -INFINITY;
-  for (int s = 0; s <= a.nsplit; ++s)
+  for (int s = 0; s < a.nsplit; ++s)
     M = fmaxf(M, a.part[(((size_t)s * a.g.n_kv_heads + head) * R + rr) * kPartStride + 128]);
   float num = 0.f, den = 0.f;
-  for (int s = 0; s <= a.nsplit; ++s) {
+  for (int s = 0; s < a.nsplit; ++s) {
     const float* p = a.part + (((size_t)s * a.g.n_kv_heads + head) * R + rr) * kPartStride;
     float m = p[128];
     if (m == -INFINITY) continue;
@@ -307,15 +304,14 @@ int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
   const int R = a.ncols * a.grp;
   const int MT = (R + 15) / 16;
   if (MT < 1 || MT > 3 || c.n_new > kPT || c.n_new < c.ncols) return CAS_EINVAL;
-  const int pages = (a.len + kPT - 1) / kPT;
-  int want = std::max(1, (ctx->num_cu * 2) / g.n_kv_heads);
-  a.nsplit = std::min(pages, want);
-  a.pages_per_split = a.nsplit ? (pages + a.nsplit - 1) / a.nsplit : 1;
-  a.nsplit = a.nsplit ? (pages + a.pages_per_split - 1) / a.pages_per_split : 0;
-  size_t need = sizeof(float) * (size_t)(a.nsplit + 1) * g.n_kv_heads * R * kPartStride;
+  const int pages = (a.len + a.n_new + kPT - 1) / kPT;
+  if (pages > g.max_pages_per_seq) return CAS_ENOMEM;
+  a.pages_per_split = kPagesPerSplit;  // fixed: a query's value must not depend on the length
+  a.nsplit = (pages + kPagesPerSplit - 1) / kPagesPerSplit;
+  size_t need = sizeof(float) * (size_t)a.nsplit * g.n_kv_heads * R * kPartStride;
   if (need > ctx->ws_bytes || !ctx->d_ws) return CAS_ENOMEM;
   a.part = (float*)ctx->d_ws;
-  dim3 grid(a.nsplit + 1, g.n_kv_heads);
+  dim3 grid(a.nsplit, g.n_kv_heads);
   int rc;
   if (c.full) {
     rc = MT == 1 ? launch_mt<1, true>(ctx, a, grid) : MT == 2 ? launch_mt<2, true>(ctx, a, grid)

@@ -1,0 +1,346 @@
+// Llama-3 style decoder around the Cassandra kernels (Fig. 2_1 structure): the small
+// element-wise kernels between the linear layers and attention, and the draft / verify /
+// commit sequence of one speculative round (Sec. 2.2, Sec. 4.1).  Every tensor that passes
+// from one operation to the next is rounded to bf16; inside an operation arithmetic is fp32.
+#include <algorithm>
+#include <new>
+#include "cas_device.hpp"
+#include "cas_internal.hpp"
+
+struct cas_model {
+  cas_model_cfg cfg;
+  cas_layer_weights* layers;  // host copy
+  cas_tensor lm_head;
+  const uint16_t* d_embed;
+  const uint16_t* d_g_final;
+  const float* d_rope;
+  // activation buffers (device, carved from the caller's block)
+  uint16_t *h, *xn, *q, *ao, *act, *knew, *vnew;
+  float *y, *logits;
+  int32_t *tok, *tgt;  // token chain of a round: pending + drafts, and the target's tokens
+};
+
+namespace cas {
+
+__global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ tok, const uint16_t* __restrict__ emb,
+                                                    uint16_t* __restrict__ h, int hidden, int vocab) {
+  const int c = blockIdx.x;
+  int t = tok[c];
+  t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+  for (int i = threadIdx.x; i < hidden; i += 256) h[(size_t)c * hidden + i] = emb[(size_t)t * hidden + i];
+}
+
+__device__ __forceinline__ float block_sum256(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+// xn = bf16(x * rsqrt(mean(x^2) + eps) * g), one workgroup per column
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict__ h, const uint16_t* __restrict__ g,
+                                                      uint16_t* __restrict__ out, int n, float eps) {
+  __shared__ float red[4];
+  const int c = blockIdx.x;
+  const uint16_t* x = h + (size_t)c * n;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) {
+    float v = bf16_to_f32(x[i]);
+    ss += v * v;
+  }
+  ss = block_sum256(ss, red);
+  const float r = 1.0f / sqrtf(ss / (float)n + eps);
+  for (int i = threadIdx.x; i < n; i += 256)
+    out[(size_t)c * n + i] = f32_to_bf16(bf16_to_f32(x[i]) * r * bf16_to_f32(g[i]));
+}
+
+// Split the qkv projection: round to bf16, rotate q and k by the position angle (pairs
+// (i, i + d/2) of a head), write q to its buffer and k, v to the in-flight slots.
+__global__ __launch_bounds__(64) void qkv_post_kernel(const float* __restrict__ y, int ystride, int n_q_heads,
+                                                      int n_kv_heads, const float* __restrict__ rope, int pos0,
+                                                      int slot0, uint16_t* __restrict__ q, uint16_t* __restrict__ knew,
+                                                      uint16_t* __restrict__ vnew) {
+  const int c = blockIdx.y, hd = blockIdx.x, i = threadIdx.x;  // head index over q, k, v heads
+  const float* src = y + (size_t)c * ystride + (size_t)hd * 128;
+  const float a = round_bf16(src[i]), b = round_bf16(src[i + 64]);
+  const int kvd = n_kv_heads * 128;
+  if (hd < n_q_heads + n_kv_heads) {
+    const float cs = rope[((size_t)(pos0 + c) * 64 + i) * 2], sn = rope[((size_t)(pos0 + c) * 64 + i) * 2 + 1];
+    const uint16_t o0 = f32_to_bf16(a * cs - b * sn), o1 = f32_to_bf16(b * cs + a * sn);
+    uint16_t* dst = hd < n_q_heads ? q + ((size_t)c * n_q_heads + hd) * 128
+                                   : knew + (size_t)(slot0 + c) * kvd + (size_t)(hd - n_q_heads) * 128;
+    dst[i] = o0;
+    dst[i + 64] = o1;
+  } else {
+    uint16_t* dst = vnew + (size_t)(slot0 + c) * kvd + (size_t)(hd - n_q_heads - n_kv_heads) * 128;
+    dst[i] = f32_to_bf16(a);
+    dst[i + 64] = f32_to_bf16(b);
+  }
+}
+
+// h = bf16(h + bf16(y))
+__global__ __launch_bounds__(256) void resid_add_kernel(uint16_t* __restrict__ h, const float* __restrict__ y,
+                                                        int n, int ystride) {
+  const int c = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) {
+    size_t o = (size_t)c * n + i;
+    h[o] = f32_to_bf16(bf16_to_f32(h[o]) + round_bf16(y[(size_t)c * ystride + i]));
+  }
+}
+
+// act = bf16(silu(bf16(gate)) * bf16(up)); gate of unit i at y[2i], up at y[2i+1]
+__global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ y, int ystride,
+                                                     uint16_t* __restrict__ act, int ffn) {
+  const int c = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < ffn) {
+    const float g = round_bf16(y[(size_t)c * ystride + 2 * i]);
+    const float u = round_bf16(y[(size_t)c * ystride + 2 * i + 1]);
+    act[(size_t)c * ffn + i] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
+  }
+}
+
+// token = lowest index among the maxima of a logits row
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int vocab,
+                                                      int32_t* __restrict__ out) {
+  __shared__ float bv[16];
+  __shared__ int bi[16];
+  const int c = blockIdx.x;
+  const float* x = logits + (size_t)c * vocab;
+  float best = -INFINITY;
+  int idx = 0x7FFFFFFF;
+  for (int i = threadIdx.x; i < vocab; i += 1024) {
+    float v = x[i];
+    if (v > best || (v == best && i < idx)) { best = v; idx = i; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(best, o, 64);
+    int oi = __shfl_xor(idx, o, 64);
+    if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+  }
+  if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = idx; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 16; ++w)
+      if (bv[w] > best || (bv[w] == best && bi[w] < idx)) { best = bv[w]; idx = bi[w]; }
+    out[c] = idx == 0x7FFFFFFF ? 0 : idx;
+  }
+}
+
+static int linear(cas_ctx* ctx, const cas_tensor& w, const uint16_t* x, int ncols, bool full, float* y) {
+  if (full) return launch_gemm_verify(ctx, w.desc, w.d_spec, w.d_verif, x, ncols, y);
+  return launch_gemv_draft(ctx, w.desc, w.d_spec, x, ncols, y);
+}
+
+#define CAS_TRY(expr)            \
+  do {                           \
+    int rc__ = (expr);           \
+    if (rc__ != CAS_OK) return rc__; \
+  } while (0)
+
+// Runs `ncols` columns (token ids on the device) through the model.  slot0: index of the
+// first column among the in-flight positions of the sequence (its position is len + slot0).
+static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_tokens, int ncols, bool full,
+                   int slot0, int32_t* d_out, float* d_logits) {
+  const cas_model_cfg& c = m->cfg;
+  const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+  const int pos0 = kv->h_len[seq] + slot0;
+  if (pos0 + ncols > c.max_pos || slot0 + ncols > c.max_cols) return CAS_EINVAL;
+  hipStream_t st = ctx->stream;
+  float* logits = d_logits ? d_logits : m->logits;
+  hipLaunchKernelGGL(embed_kernel, dim3(ncols), dim3(256), 0, st, d_tokens, m->d_embed, m->h, c.hidden, c.vocab);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const cas_layer_weights& L = m->layers[l];
+    uint16_t* kn = m->knew + (size_t)l * c.max_cols * kvd;
+    uint16_t* vn = m->vnew + (size_t)l * c.max_cols * kvd;
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, L.d_g_attn, m->xn, c.hidden, c.rms_eps);
+    CAS_TRY(linear(ctx, L.wqkv, m->xn, ncols, full, m->y));
+    hipLaunchKernelGGL(qkv_post_kernel, dim3(c.n_q_heads + 2 * c.n_kv_heads, ncols), dim3(64), 0, st, m->y,
+                       qd + 2 * kvd, c.n_q_heads, c.n_kv_heads, m->d_rope, pos0, slot0, m->q, kn, vn);
+    AttnCall ac;
+    ac.layer = l; ac.seq = seq; ac.full = full ? 1 : 0;
+    ac.Q = m->q; ac.ncols = ncols; ac.n_q_heads = c.n_q_heads;
+    ac.Knew = kn; ac.Vnew = vn; ac.n_new = slot0 + ncols; ac.O = m->ao;
+    CAS_TRY(launch_attention(ctx, kv, ac));
+    CAS_TRY(linear(ctx, L.wo, m->ao, ncols, full, m->y));
+    hipLaunchKernelGGL(resid_add_kernel, dim3((c.hidden + 255) / 256, ncols), dim3(256), 0, st, m->h, m->y, c.hidden,
+                       c.hidden);
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, L.d_g_ffn, m->xn, c.hidden, c.rms_eps);
+    CAS_TRY(linear(ctx, L.wgu, m->xn, ncols, full, m->y));
+    hipLaunchKernelGGL(swiglu_kernel, dim3((c.ffn + 255) / 256, ncols), dim3(256), 0, st, m->y, 2 * c.ffn, m->act,
+                       c.ffn);
+    CAS_TRY(linear(ctx, L.wd, m->act, ncols, full, m->y));
+    hipLaunchKernelGGL(resid_add_kernel, dim3((c.hidden + 255) / 256, ncols), dim3(256), 0, st, m->h, m->y, c.hidden,
+                       c.hidden);
+  }
+  hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, m->d_g_final, m->xn, c.hidden, c.rms_eps);
+  CAS_TRY(linear(ctx, m->lm_head, m->xn, ncols, full, logits));
+  if (d_out) hipLaunchKernelGGL(argmax_kernel, dim3(ncols), dim3(1024), 0, st, logits, c.vocab, d_out);
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
+}
+
+static size_t carve(size_t& off, size_t bytes) {
+  size_t o = off;
+  off = (off + bytes + 255) / 256 * 256;
+  return o;
+}
+
+struct ActLayout {
+  size_t h, xn, q, ao, act, knew, vnew, y, logits, tok, tgt, total;
+};
+
+static ActLayout act_layout(const cas_model_cfg& c) {
+  const size_t nc = c.max_cols, qd = (size_t)c.n_q_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim;
+  const size_t ymax = std::max<size_t>({qd + 2 * kvd, 2 * (size_t)c.ffn, (size_t)c.hidden});
+  ActLayout L;
+  size_t off = 0;
+  L.h = carve(off, nc * c.hidden * 2);
+  L.xn = carve(off, nc * std::max<size_t>(c.hidden, qd) * 2);
+  L.q = carve(off, nc * qd * 2);
+  L.ao = carve(off, nc * qd * 2);
+  L.act = carve(off, nc * c.ffn * 2);
+  L.knew = carve(off, (size_t)c.n_layers * nc * kvd * 2);
+  L.vnew = carve(off, (size_t)c.n_layers * nc * kvd * 2);
+  L.y = carve(off, nc * ymax * 4);
+  L.logits = carve(off, nc * (size_t)c.vocab * 4);
+  L.tok = carve(off, (nc + 1) * 4);
+  L.tgt = carve(off, (nc + 1) * 4);
+  L.total = off;
+  return L;
+}
+
+static int check_cfg(const cas_model_cfg* c) {
+  if (!c || c->hidden < 1 || c->n_layers < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->ffn < 1 || c->vocab < 1)
+    return CAS_EINVAL;
+  if (c->head_dim != 128) return CAS_ENOTSUP;
+  if (c->n_q_heads % c->n_kv_heads != 0 || c->max_cols < 1 || c->max_cols > 16 || c->max_pos < 1) return CAS_EINVAL;
+  if (c->max_cols * (c->n_q_heads / c->n_kv_heads) > 48) return CAS_EINVAL;
+  return CAS_OK;
+}
+
+}  // namespace cas
+
+extern "C" {
+
+int cas_model_act_bytes(const cas_model_cfg* cfg, size_t* bytes) {
+  if (!bytes) return CAS_EINVAL;
+  int rc = cas::check_cfg(cfg);
+  if (rc != CAS_OK) return rc;
+  *bytes = cas::act_layout(*cfg).total;
+  return CAS_OK;
+}
+
+int cas_model_create(const cas_model_cfg* cfg, const cas_model_weights* w, void* d_act, size_t act_bytes,
+                     cas_model** out) {
+  if (!w || !d_act || !out || !w->layers || !w->d_embed || !w->d_g_final || !w->d_rope) return CAS_EINVAL;
+  int rc = cas::check_cfg(cfg);
+  if (rc != CAS_OK) return rc;
+  const cas::ActLayout L = cas::act_layout(*cfg);
+  if (act_bytes < L.total) return CAS_ENOMEM;
+  if (!cas::aligned256(d_act)) return CAS_EINVAL;
+  const int qd = cfg->n_q_heads * cfg->head_dim, kvd = cfg->n_kv_heads * cfg->head_dim;
+  auto shape_ok = [](const cas_tensor& t, int64_t rows, int64_t cols) {
+    return t.d_spec && t.d_verif && t.desc.rows == rows && t.desc.cols == cols;
+  };
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const cas_layer_weights& lw = w->layers[l];
+    if (!shape_ok(lw.wqkv, qd + 2 * kvd, cfg->hidden) || !shape_ok(lw.wo, cfg->hidden, qd) ||
+        !shape_ok(lw.wgu, 2 * (int64_t)cfg->ffn, cfg->hidden) || !shape_ok(lw.wd, cfg->hidden, cfg->ffn) ||
+        !lw.d_g_attn || !lw.d_g_ffn)
+      return CAS_EINVAL;
+  }
+  if (!shape_ok(w->lm_head, cfg->vocab, cfg->hidden)) return CAS_EINVAL;
+  cas_model* m = new (std::nothrow) cas_model();
+  if (!m) return CAS_ENOMEM;
+  m->cfg = *cfg;
+  m->layers = new (std::nothrow) cas_layer_weights[cfg->n_layers];
+  if (!m->layers) { delete m; return CAS_ENOMEM; }
+  std::copy(w->layers, w->layers + cfg->n_layers, m->layers);
+  m->lm_head = w->lm_head;
+  m->d_embed = w->d_embed; m->d_g_final = w->d_g_final; m->d_rope = w->d_rope;
+  char* b = (char*)d_act;
+  m->h = (uint16_t*)(b + L.h); m->xn = (uint16_t*)(b + L.xn); m->q = (uint16_t*)(b + L.q);
+  m->ao = (uint16_t*)(b + L.ao); m->act = (uint16_t*)(b + L.act);
+  m->knew = (uint16_t*)(b + L.knew); m->vnew = (uint16_t*)(b + L.vnew);
+  m->y = (float*)(b + L.y); m->logits = (float*)(b + L.logits);
+  m->tok = (int32_t*)(b + L.tok); m->tgt = (int32_t*)(b + L.tgt);
+  *out = m;
+  return CAS_OK;
+}
+
+int cas_model_destroy(cas_model* m) {
+  if (m) { delete[] m->layers; delete m; }
+  return CAS_OK;
+}
+
+static int check_step(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq) {
+  if (!ctx || !m || !kv || seq < 0 || seq >= kv->desc.max_seqs) return CAS_EINVAL;
+  if (kv->desc.n_layers != m->cfg.n_layers || kv->desc.n_kv_heads != m->cfg.n_kv_heads) return CAS_EINVAL;
+  return CAS_OK;
+}
+
+int cas_draft_step(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_token_in, int slot,
+                   int32_t* d_token_out, float* d_logits) {
+  if (check_step(ctx, m, kv, seq) != CAS_OK || !d_token_in || !d_token_out || slot < 0) return CAS_EINVAL;
+  return cas::forward(ctx, m, kv, seq, d_token_in, 1, false, slot, d_token_out, d_logits);
+}
+
+int cas_verify_step(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_tokens, int k,
+                    int32_t* d_target, float* d_logits) {
+  if (check_step(ctx, m, kv, seq) != CAS_OK || !d_tokens || k < 0) return CAS_EINVAL;
+  return cas::forward(ctx, m, kv, seq, d_tokens, k + 1, true, 0, d_target, d_logits);
+}
+
+int cas_commit(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int n_accepted) {
+  if (check_step(ctx, m, kv, seq) != CAS_OK || n_accepted < 0 || n_accepted + 1 > m->cfg.max_cols) return CAS_EINVAL;
+  const cas_model_cfg& c = m->cfg;
+  const int kvd = c.n_kv_heads * c.head_dim, n = n_accepted + 1;
+  const int64_t cap = (int64_t)kv->desc.max_pages_per_seq * kv->desc.page_tokens;
+  if ((int64_t)kv->h_len[seq] + n > cap) return CAS_ENOMEM;
+  for (int l = 0; l < c.n_layers; ++l) {
+    int rc = cas::launch_kv_append(ctx, kv, l, seq, m->knew + (size_t)l * c.max_cols * kvd,
+                                   m->vnew + (size_t)l * c.max_cols * kvd, n, kv->h_len[seq]);
+    if (rc != CAS_OK) return rc;
+  }
+  kv->h_len[seq] += n;
+  return CAS_OK;
+}
+
+int cas_spec_round(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int32_t pending, int k, int32_t* h_out,
+                   int32_t* n_accepted) {
+  if (check_step(ctx, m, kv, seq) != CAS_OK || !h_out || !n_accepted || k < 0 || k + 1 > m->cfg.max_cols)
+    return CAS_EINVAL;
+  CAS_HIP(ctx, hipMemcpyAsync(m->tok, &pending, sizeof(int32_t), hipMemcpyHostToDevice, ctx->stream));
+  for (int i = 0; i < k; ++i) {
+    int rc = cas::forward(ctx, m, kv, seq, m->tok + i, 1, false, i, m->tok + i + 1, nullptr);
+    if (rc != CAS_OK) return rc;
+  }
+  int rc = cas::forward(ctx, m, kv, seq, m->tok, k + 1, true, 0, m->tgt, nullptr);
+  if (rc != CAS_OK) return rc;
+  int32_t h_tok[17], h_tgt[17];
+  CAS_HIP(ctx, hipMemcpyAsync(h_tok, m->tok, sizeof(int32_t) * (k + 1), hipMemcpyDeviceToHost, ctx->stream));
+  CAS_HIP(ctx, hipMemcpyAsync(h_tgt, m->tgt, sizeof(int32_t) * (k + 1), hipMemcpyDeviceToHost, ctx->stream));
+  CAS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  rc = cas_accept(h_tok + 1, h_tgt, k, n_accepted, h_out);
+  if (rc != CAS_OK) return rc;
+  return cas_commit(ctx, m, kv, seq, *n_accepted);
+}
+
+int cas_prefill(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_tokens, int n) {
+  if (check_step(ctx, m, kv, seq) != CAS_OK || !d_tokens || n < 0) return CAS_EINVAL;
+  for (int done = 0; done < n;) {
+    const int nc = std::min(n - done, (int)m->cfg.max_cols);
+    int rc = cas::forward(ctx, m, kv, seq, d_tokens + done, nc, true, 0, nullptr, nullptr);
+    if (rc != CAS_OK) return rc;
+    rc = cas_commit(ctx, m, kv, seq, nc - 1);
+    if (rc != CAS_OK) return rc;
+    done += nc;
+  }
+  return CAS_OK;
+}
+
+}  // extern "C"
