@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--keep", type=int, default=600, help="kept fraction in 1/1000 (paper default 40 %% pruned)")
     ap.add_argument("--trunc", type=int, default=4)
     ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--context", type=int, default=8192, help="committed KV positions when a step starts")
+    ap.add_argument("--workload", choices=["model", "linear"], default="model")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 

@@ -80,6 +80,17 @@ int cas_ctx_destroy(cas_ctx* ctx);
 const char* cas_strerror(int code);
 int cas_last_hip_error(const cas_ctx* ctx);
 
+/* Measurement hooks.  While enabled, every launch of the four streaming kernels is bracketed
+ * by HIP events on the context stream.  kernel_class: 0 draft GEMV, 1 verification GEMM,
+ * 2 draft attention, 3 verification attention.  cas_prof_read synchronises the stream and
+ * returns the number of launches, the summed kernel time and the summed algorithmic bytes
+ * (bytes of the packed streams the launch is obliged to read).  Not for use under graph
+ * capture. */
+int cas_prof_enable(cas_ctx* ctx, int on);
+int cas_prof_read(cas_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms,
+                  double* total_bytes);
+int cas_prof_reset(cas_ctx* ctx);
+
 /* ---- weights: encode / decode (Sec. 4.2, Sec. 5.1) ------------------------------------ */
 
 /* Host only.  Fills the layout and buffer sizes for a rows x cols matrix. */

@@ -67,6 +67,10 @@ _SIGNATURES = {
     "cas_ctx_destroy": (C.c_int, [C.c_void_p]),
     "cas_strerror": (C.c_char_p, [C.c_int]),
     "cas_last_hip_error": (C.c_int, [C.c_void_p]),
+    "cas_prof_enable": (C.c_int, [C.c_void_p, C.c_int]),
+    "cas_prof_read": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                C.POINTER(C.c_double)]),
+    "cas_prof_reset": (C.c_int, [C.c_void_p]),
     "cas_weight_desc": (C.c_int, [C.c_int64, C.c_int64, C.POINTER(cas_fmt), C.POINTER(cas_wdesc)]),
     "cas_encode_weight": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(cas_wdesc),
                                     C.c_void_p, C.c_void_p]),
@@ -160,6 +164,23 @@ class Context:
     def _check(self, rc, what):
         if rc != CAS_OK:
             raise CasError(rc, what, _lib().cas_last_hip_error(self.h))
+
+
+PROF_GEMV_DRAFT, PROF_GEMM_VERIFY, PROF_ATTN_DRAFT, PROF_ATTN_VERIFY = 0, 1, 2, 3
+
+
+def cas_prof_enable(ctx: Context, on: bool):
+    ctx._check(_lib().cas_prof_enable(ctx.h, 1 if on else 0), "cas_prof_enable")
+
+
+def cas_prof_read(ctx: Context, kernel_class: int):
+    n, ms, by = C.c_int64(), C.c_double(), C.c_double()
+    ctx._check(_lib().cas_prof_read(ctx.h, kernel_class, C.byref(n), C.byref(ms), C.byref(by)), "cas_prof_read")
+    return n.value, ms.value, by.value
+
+
+def cas_prof_reset(ctx: Context):
+    ctx._check(_lib().cas_prof_reset(ctx.h), "cas_prof_reset")
 
 
 def cas_weight_desc(rows, cols, keep_permille, trunc_bits, exp_mode=0):

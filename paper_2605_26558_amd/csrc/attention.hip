@@ -313,12 +313,18 @@ int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
   a.part = (float*)ctx->d_ws;
   dim3 grid(a.nsplit, g.n_kv_heads);
   int rc;
+  {
+    // committed positions: bitmap + spec (+ lo + pruned) of K and V; in-flight ones: plain bf16
+    const double per_tok = 4.0 * (4 + g.sw + (c.full ? g.lw + g.pw : 0));
+    const double bytes = 2.0 * g.n_kv_heads * (per_tok * a.len + 256.0 * a.n_new);
+    ProfScope prof(ctx, c.full ? PROF_ATTN_VERIFY : PROF_ATTN_DRAFT, bytes);
   if (c.full) {
     rc = MT == 1 ? launch_mt<1, true>(ctx, a, grid) : MT == 2 ? launch_mt<2, true>(ctx, a, grid)
                                                                : launch_mt<3, true>(ctx, a, grid);
   } else {
     rc = MT == 1 ? launch_mt<1, false>(ctx, a, grid) : MT == 2 ? launch_mt<2, false>(ctx, a, grid)
                                                                 : launch_mt<3, false>(ctx, a, grid);
+  }
   }
   if (rc != CAS_OK) return rc;
   hipLaunchKernelGGL(attn_merge_kernel, dim3(R, g.n_kv_heads), dim3(128), 0, ctx->stream, a);

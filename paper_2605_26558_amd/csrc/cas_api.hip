@@ -32,6 +32,7 @@ int cas_ctx_create(cas_ctx** out, void* hip_stream, void* d_workspace, size_t ws
 }
 
 int cas_ctx_destroy(cas_ctx* ctx) {
+  if (ctx) cas_prof_reset(ctx);
   delete ctx;
   return CAS_OK;
 }
@@ -48,6 +49,34 @@ const char* cas_strerror(int code) {
 }
 
 int cas_last_hip_error(const cas_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+int cas_prof_enable(cas_ctx* ctx, int on) {
+  if (!ctx) return CAS_EINVAL;
+  ctx->prof_on = on != 0;
+  return CAS_OK;
+}
+
+int cas_prof_read(cas_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms, double* total_bytes) {
+  if (!ctx || kernel_class < 0 || kernel_class >= cas::PROF_NCLASS || !launches || !total_ms || !total_bytes)
+    return CAS_EINVAL;
+  CAS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  *launches = 0; *total_ms = 0; *total_bytes = 0;
+  for (const cas::ProfRec& r : ctx->prof) {
+    if (r.cls != kernel_class) continue;
+    float ms = 0.f;
+    CAS_HIP(ctx, hipEventElapsedTime(&ms, r.e0, r.e1));
+    *launches += 1; *total_ms += ms; *total_bytes += r.bytes;
+  }
+  return CAS_OK;
+}
+
+int cas_prof_reset(cas_ctx* ctx) {
+  if (!ctx) return CAS_EINVAL;
+  CAS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  for (cas::ProfRec& r : ctx->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  ctx->prof.clear();
+  return CAS_OK;
+}
 
 int cas_weight_desc(int64_t rows, int64_t cols, const cas_fmt* fmt, cas_wdesc* out) {
   if (!fmt || !out || rows < 0 || cols < 1 || cols > (1 << 20)) return CAS_EINVAL;

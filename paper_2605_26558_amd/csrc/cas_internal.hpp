@@ -4,7 +4,16 @@
 #include <stdint.h>
 #include "../../include/cassandra.h"
 
+#include <vector>
+
+namespace cas {
+enum ProfClass { PROF_GEMV_DRAFT = 0, PROF_GEMM_VERIFY = 1, PROF_ATTN_DRAFT = 2, PROF_ATTN_VERIFY = 3, PROF_NCLASS = 4 };
+struct ProfRec { int cls; double bytes; hipEvent_t e0, e1; };
+}  // namespace cas
+
 struct cas_ctx {
+  bool prof_on = false;
+  std::vector<cas::ProfRec> prof;
   hipStream_t stream;
   void* d_ws;
   size_t ws_bytes;
@@ -59,4 +68,21 @@ struct AttnCall {
   uint16_t* O;                 // [ncols][n_q_heads][128]
 };
 int launch_attention(cas_ctx*, cas_kv*, const AttnCall&);
+// Brackets one kernel launch with HIP events on the context stream when profiling is on.
+struct ProfScope {
+  cas_ctx* ctx;
+  bool on;
+  ProfRec rec;
+  ProfScope(cas_ctx* c, int cls, double bytes) : ctx(c), on(c->prof_on) {
+    if (!on) return;
+    rec.cls = cls; rec.bytes = bytes;
+    if (hipEventCreate(&rec.e0) != hipSuccess || hipEventCreate(&rec.e1) != hipSuccess) { on = false; return; }
+    (void)hipEventRecord(rec.e0, ctx->stream);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(rec.e1, ctx->stream);
+    ctx->prof.push_back(rec);
+  }
+};
 }  // namespace cas

@@ -241,6 +241,7 @@ int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const
   lds = std::max(lds, sizeof(float) * 4 * 64 * 4);
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
   int grid = (int)((d.rows + 15) / 16);
+  ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + d.sw + d.lw + d.pw));
 #define CAS_LAUNCH(TV)                                                                                  \
   case TV:                                                                                              \
     if (lds > 48 * 1024)                                                                                \

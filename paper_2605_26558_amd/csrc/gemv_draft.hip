@@ -176,6 +176,7 @@ int launch_gemv_draft(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const 
   static int wg_per_cu = [] { const char* e = getenv("CAS_GEMV_WG_PER_CU"); return e ? atoi(e) : 4; }();
   int64_t want = (d.rows + 3) / 4;
   int grid = (int)std::min<int64_t>(want, (int64_t)ctx->num_cu * wg_per_cu);
+  ProfScope prof(ctx, PROF_GEMV_DRAFT, 4.0 * (double)d.rows * (d.bw + d.sw));
   switch (d.t) {
     case 0: return launch_t<0>(ctx, a, batch, grid, lds);
     case 1: return launch_t<1>(ctx, a, batch, grid, lds);

@@ -100,5 +100,121 @@ class LinearRoundWorkload:
         }
 
 
+class ModelRoundWorkload:
+    """Whole model: one speculative round (k draft passes, verification over k+1 columns,
+    greedy acceptance, commit with online KV encoding) per step, at a fixed context length.
+    The cache is pre-filled with synthetic K/V (keys with 4 outlier channels per head x10)
+    through the library's online encoder."""
+
+    def __init__(self, B, args, dev):
+        import torch
+        self.torch, self.B = torch, B
+        self.k, self.ctx_len = args.k, args.context
+        shape = synth.LlamaShape("llama3-8b", 4096, args.layers, 32, 8, 128, 14336, 128256)
+        self.shape = shape
+        self.ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        self.ctx = B.Context(workspace=self.ws)
+        ctx = self.ctx
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(1234)
+        dims = {"wqkv": (shape.q_dim + 2 * shape.kv_dim, shape.hidden), "wo": (shape.hidden, shape.q_dim),
+                "wgu": (2 * shape.ffn, shape.hidden), "wd": (shape.hidden, shape.ffn)}
+
+        def enc(r, c):
+            act = torch.exp(0.5 * torch.randn(c, device="cuda", generator=gen))
+            return B.cas_encode_weight(ctx, _random_weight(torch, r, c, gen), args.keep, args.trunc, act)
+
+        def gain():
+            return (1.0 + 0.1 * torch.randn(shape.hidden, device="cuda", generator=gen)).to(torch.bfloat16).view(
+                torch.int16)
+
+        layers = []
+        for _ in range(shape.n_layers):
+            L = {n: enc(r, c) for n, (r, c) in dims.items()}
+            L["g_attn"], L["g_ffn"] = gain(), gain()
+            layers.append(L)
+        head = enc(shape.vocab, shape.hidden)
+        embed = torch.randn((shape.vocab, shape.hidden), device="cuda", generator=gen).to(torch.bfloat16).view(
+            torch.int16)
+        max_pos = self.ctx_len + 1024
+        rope = torch.from_numpy(synth.rope_table(max_pos, shape.head_dim, shape.rope_theta)).cuda()
+        self.model = B.Model(ctx, shape, layers, head, embed, gain(), rope, max_cols=self.k + 1)
+        pages = (max_pos + 63) // 64
+        self.kv = B.KVCache(ctx, shape.n_layers, shape.n_kv_heads, n_pages=pages, max_seqs=1,
+                            max_pages_per_seq=pages, keep_permille=args.keep, trunc_bits=args.trunc)
+        # synthetic cache contents
+        chunk = 1024
+        for layer in range(shape.n_layers):
+            out_idx = torch.randperm(128, device="cuda", generator=gen)[:4]
+            done = 0
+            while done < self.ctx_len:
+                n = min(chunk, self.ctx_len - done)
+                K = torch.randn((n, shape.n_kv_heads, 128), device="cuda", generator=gen)
+                K[:, :, out_idx] *= 10.0
+                V = torch.randn((n, shape.n_kv_heads, 128), device="cuda", generator=gen)
+                B.cas_kv_set_len(self.kv, 0, done)
+                B.cas_kv_append(ctx, self.kv, layer, 0, K.to(torch.bfloat16).view(torch.int16).contiguous(),
+                                V.to(torch.bfloat16).view(torch.int16).contiguous())
+                done += n
+        B.cas_kv_set_len(self.kv, 0, self.ctx_len)
+        torch.cuda.synchronize()
+        mats = [L[n] for L in layers for n in dims] + [head]
+        self.draft_w = sum(m.desc.rows * (m.desc.bw + m.desc.sw) * 4 for m in mats)
+        self.verify_w = sum(m.desc.rows * (m.desc.bw + m.desc.sw + m.desc.lw + m.desc.pw) * 4 for m in mats)
+        d = self.kv.desc
+        per_tok_draft = 2 * shape.n_layers * shape.n_kv_heads * 4 * (4 + d.sw)
+        per_tok_full = 2 * shape.n_layers * shape.n_kv_heads * 4 * (4 + d.sw + d.lw + d.pw)
+        self.draft_kv = per_tok_draft * self.ctx_len
+        self.verify_kv = per_tok_full * self.ctx_len
+        self.values = sum(m.desc.rows * m.desc.cols for m in mats)
+        self.bytes_per_step = self.k * (self.draft_w + self.draft_kv) + self.verify_w + self.verify_kv
+        self.pending = 1
+        self.accepted, self.rounds = 0, 0
+        self.config = {"workload": f"Llama-3-8B-shaped random-init model ({shape.n_layers} layers, vocab {shape.vocab}, "
+                                   f"{self.values / 1e9:.2f} G encoded weights), batch 1, KV context {self.ctx_len} "
+                                   f"(synthetic K/V, 4 outlier key channels per head), draft length k={self.k}, "
+                                   "greedy acceptance; weights + KV in Cassandra format",
+                       "keep_permille": args.keep, "trunc_bits": args.trunc, "k": self.k, "context": self.ctx_len,
+                       "step": "one speculative round: k draft passes + verify(k+1) + accept + commit"}
+
+    def step(self):
+        n, out = self.B.cas_spec_round(self.ctx, self.model, self.kv, 0, self.pending, self.k)
+        self.pending = out[-1]
+        self.accepted += n
+        self.rounds += 1
+        # keep the context length fixed across steps (roll the committed tokens back)
+        self.B.cas_kv_set_len(self.kv, 0, self.ctx_len)
+
+    def roofline_pass(self):
+        B, ctx = self.B, self.ctx
+        B.cas_prof_reset(ctx)
+        B.cas_prof_enable(ctx, True)
+        acc0, r0 = self.accepted, self.rounds
+        for _ in range(2):
+            self.step()
+        B.cas_prof_enable(ctx, False)
+        self.accepted, self.rounds = acc0, r0
+        self.prof = {name: B.cas_prof_read(ctx, cls) for name, cls in
+                     (("gemv_draft", 0), ("gemm_verify", 1), ("attn_draft", 2), ("attn_verify", 3))}
+        B.cas_prof_reset(ctx)
+        n, ms, by = self.prof["gemv_draft"]
+        ach = by / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "kernel": "gemv_draft_kernel", "achieved": ach, "peak": 8000.0, "unit": "GB/s",
+                "frac": ach / 8000.0, "traffic": None, "launches": n, "avg_launch_us": ms / n * 1e3,
+                "bytes_per_launch": by / n}
+
+    def extra(self, ms_per_step):
+        out = {"tokens_per_s": (self.accepted + self.rounds) / max(self.rounds, 1) / (ms_per_step * 1e-3),
+               "accepted_per_round": self.accepted / max(self.rounds, 1),
+               "kernels": {}}
+        for name, (n, ms, by) in self.prof.items():
+            if n:
+                out["kernels"][name] = {"launches": n, "avg_us": ms / n * 1e3, "GBps": by / (ms * 1e-3) / 1e9,
+                                        "frac_of_peak": by / (ms * 1e-3) / 1e9 / 8000.0}
+        return out
+
+
 def build(B, args, dev):
-    return LinearRoundWorkload(B, args, dev)
+    if args.workload == "linear":
+        return LinearRoundWorkload(B, args, dev)
+    return ModelRoundWorkload(B, args, dev)
