@@ -250,21 +250,35 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 }
 
 // Combine the splits: o = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, rounded to bf16.
+// One workgroup per (query row, kv head); the split weights are computed once into LDS, then
+// every thread sums its channel over the splits with independent loads.
 __global__ __launch_bounds__(128) void attn_merge_kernel(AttnArgs a) {
+  extern __shared__ float sw[];  // [nsplit] weights
+  __shared__ float red[4];
   const int rr = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
   const int R = a.ncols * a.grp;
-  float M = -INFINITY;
-  for (int s = 0; s < a.nsplit; ++s)
-    M = fmaxf(M, a.part[(((size_t)s * a.g.n_kv_heads + head) * R + rr) * kPartStride + 128]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < a.nsplit; ++s) {
-    const float* p = a.part + (((size_t)s * a.g.n_kv_heads + head) * R + rr) * kPartStride;
-    float m = p[128];
-    if (m == -INFINITY) continue;
-    float w = __expf(m - M);
-    num += w * p[d];
-    den += w * p[129];
+  const size_t sstride = (size_t)a.g.n_kv_heads * R * kPartStride;
+  const float* base = a.part + ((size_t)head * R + rr) * kPartStride;
+  float mx = -INFINITY;
+  for (int s = d; s < a.nsplit; s += 128) mx = fmaxf(mx, base[s * sstride + 128]);
+  mx = wave_max(mx);
+  if ((d & 63) == 0) red[d >> 6] = mx;
+  __syncthreads();
+  const float M = fmaxf(red[0], red[1]);
+  float den = 0.f;
+  for (int s = d; s < a.nsplit; s += 128) {
+    float m = base[s * sstride + 128];
+    float w = (m == -INFINITY) ? 0.f : __expf(m - M);
+    sw[s] = w;
+    den += w * base[s * sstride + 129];
   }
+  den = wave_sum(den);
+  if ((d & 63) == 0) red[2 + (d >> 6)] = den;
+  __syncthreads();
+  den = red[2] + red[3];
+  float num = 0.f;
+#pragma unroll 8
+  for (int s = 0; s < a.nsplit; ++s) num += sw[s] * base[s * sstride + d];
   const int c = rr / a.grp, gi = rr - c * a.grp;
   a.O[((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d] = f32_to_bf16(num / den);
 }
@@ -274,9 +288,14 @@ static int launch_mt(cas_ctx* ctx, const AttnArgs& a, dim3 grid) {
   constexpr size_t lds = attn_lds_bytes<MT>();
 #define CAS_LAUNCH(TV)                                                                                          \
   case TV:                                                                                                      \
-    if (lds > 48 * 1024)                                                                                        \
-      CAS_HIP(ctx, hipFuncSetAttribute((const void*)attn_partial_kernel<MT, FULL, TV>,                          \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                  \
+    if (lds > 48 * 1024) {                                                                                      \
+      static bool raised = false;                                                                               \
+      if (!raised) {                                                                                            \
+        CAS_HIP(ctx, hipFuncSetAttribute((const void*)attn_partial_kernel<MT, FULL, TV>,                        \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, ctx->lds_max));            \
+        raised = true;                                                                                          \
+      }                                                                                                         \
+    }                                                                                                           \
     hipLaunchKernelGGL((attn_partial_kernel<MT, FULL, TV>), grid, dim3(256), lds, ctx->stream, a);              \
     break;
   switch (a.g.t) {
@@ -327,7 +346,7 @@ int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
   }
   }
   if (rc != CAS_OK) return rc;
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(R, g.n_kv_heads), dim3(128), 0, ctx->stream, a);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(R, g.n_kv_heads), dim3(128), sizeof(float) * a.nsplit, ctx->stream, a);
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;
 }

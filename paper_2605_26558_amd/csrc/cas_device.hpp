@@ -60,8 +60,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 }
 __device__ __forceinline__ float round_bf16(float f) { return bf16_to_f32(f32_to_bf16(f)); }
 
-// position of the lowest set bit, -1 if none (v_ffbl_b32 semantics)
-__device__ __forceinline__ int lowest_bit(uint32_t m) { return m ? __builtin_ctz(m) : -1; }
+// position of the lowest set bit, -1 if none: exactly what v_ffbl_b32 returns, so no select
+__device__ __forceinline__ int lowest_bit(uint32_t m) {
+  int r;
+  asm("v_ffbl_b32 %0, %1" : "=v"(r) : "v"(m));
+  return r;
+}
 
 // Read a `width`-bit field at bit offset `bit` of a little-endian word stream (generic path).
 __device__ __forceinline__ uint32_t read_field(const uint32_t* __restrict__ s, uint32_t bit, int width) {

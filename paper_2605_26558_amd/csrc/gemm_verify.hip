@@ -244,9 +244,14 @@ int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const
   ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + d.sw + d.lw + d.pw));
 #define CAS_LAUNCH(TV)                                                                                  \
   case TV:                                                                                              \
-    if (lds > 48 * 1024)                                                                                \
-      CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemm_verify_kernel<TV>,                             \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));          \
+    if (lds > 48 * 1024) {                                                                            \
+      static bool raised = false;                                                                      \
+      if (!raised) {                                                                                   \
+        CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemm_verify_kernel<TV>,                                              \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, ctx->lds_max));   \
+        raised = true;                                                                                 \
+      }                                                                                                \
+    }          \
     hipLaunchKernelGGL((gemm_verify_kernel<TV>), dim3(grid), dim3(256), lds, ctx->stream, a);           \
     break;
   switch (d.t) {

@@ -19,7 +19,7 @@
 namespace cas {
 
 struct GemvArgs {
-  int rows, cols, bw, sw;
+  int rows, cols, bw, sw, nwaves;
   const uint32_t* bitmap;
   const uint32_t* spec;
   const uint16_t* x;  // [NB][cols]
@@ -43,29 +43,20 @@ struct Cursor {  // walks the (row, chunk) items of one wave in order
   }
 };
 
+constexpr int kGemvThreads = 1024;  // 16 waves share one staged copy of x
+constexpr int kGemvWaves = kGemvThreads / 64;
+
 template <int T, int NB>
-__global__ __launch_bounds__(256) void gemv_draft_kernel(GemvArgs a) {
+__global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   constexpr int FW = 16 - T;
   extern __shared__ float xs[];
   const int tid = threadIdx.x;
   const int nchunk = (a.bw + 63) >> 6;
   const int nseg = nchunk * 64;
-  // ---- stage x as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0
-  for (int c = tid; c < nseg * 33; c += 256) {
-    int seg = c / 33, e = c - seg * 33;
-    int col = seg * 32 + e - 1;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      float v = (e > 0 && col < a.cols) ? bf16_to_f32(a.x[(size_t)b * a.cols + col]) : 0.f;
-      xs[c * NB + b] = v;
-    }
-  }
-  __syncthreads();
-
   const int lane = tid & 63;
-  const int gw = blockIdx.x * 4 + (tid >> 6);
-  const int nwaves = gridDim.x * 4;
-  if (gw >= a.rows) return;
+  const int gw = blockIdx.x * kGemvWaves + (tid >> 6);
+  const int nwaves = a.nwaves;  // rows are dealt round-robin to this many waves
+  const bool idle = gw >= nwaves;  // still helps staging x
 
   auto load_bm = [&](const Cursor& c) -> uint32_t {
     int wi = c.chunk * 64 + lane;
@@ -97,25 +88,28 @@ __global__ __launch_bounds__(256) void gemv_draft_kernel(GemvArgs a) {
     for (int j = 0; j < FW; ++j) win[j] = __builtin_amdgcn_alignbit(w.d[j + 1], w.d[j], w.sh);
     uint32_t m = w.m;
     const float* xb = xs + ((c.chunk * 64 + lane) * 33 + 1) * NB;
-    auto group = [&](auto G) {
-      static_for<0, 8>([&](auto I) {
-        constexpr int i = decltype(G)::value * 8 + decltype(I)::value;
-        int pos = lowest_bit(m);
-        m &= m - 1u;
-        float f = __uint_as_float(field_top<FW, i>(win));
-        const float* xp = xb + pos * NB;
+    auto step = [&](auto I) {
+      constexpr int i = decltype(I)::value;
+      int pos = lowest_bit(m);
+      m &= m - 1u;
+      float f = __uint_as_float(field_top<FW, i>(win));
+      const float* xp = xb + pos * NB;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) acc[b] = fmaf(f, xp[b], acc[b]);
-      });
+      for (int b = 0; b < NB; ++b) acc[b] = fmaf(f, xp[b], acc[b]);
     };
-    group(std::integral_constant<int, 0>{});
-    if (__builtin_amdgcn_ballot_w64(m != 0u)) {
-      group(std::integral_constant<int, 1>{});
-      if (__builtin_amdgcn_ballot_w64(m != 0u)) {
-        group(std::integral_constant<int, 2>{});
-        if (__builtin_amdgcn_ballot_w64(m != 0u)) group(std::integral_constant<int, 3>{});
+    // the first 16 set bits unconditionally, then pairs until every lane has run out
+    static_for<0, 16>(step);
+    auto tail = [&](auto self, auto I) -> void {
+      constexpr int i = decltype(I)::value;
+      if constexpr (i < 32) {
+        if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+          step(std::integral_constant<int, i>{});
+          step(std::integral_constant<int, i + 1>{});
+          self(self, std::integral_constant<int, i + 2>{});
+        }
       }
-    }
+    };
+    tail(tail, std::integral_constant<int, 16>{});
     if (c.chunk == nchunk - 1) {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
@@ -126,11 +120,29 @@ __global__ __launch_bounds__(256) void gemv_draft_kernel(GemvArgs a) {
     }
   };
 
+  auto stage_x = [&]() {
+  // ---- stage x as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0
+  for (int c = tid; c < nseg * 33; c += kGemvThreads) {
+    int seg = c / 33, e = c - seg * 33;
+    int col = seg * 32 + e - 1;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      float v = (e > 0 && col < a.cols) ? bf16_to_f32(a.x[(size_t)b * a.cols + col]) : 0.f;
+      xs[c * NB + b] = v;
+    }
+  }
+  __syncthreads();
+  };
   Cursor cb{gw, 0}, ci{gw, 0}, cc{gw, 0};
   Window<FW> w0, w1;
+  if (idle) {
+    stage_x();
+    return;
+  }
   uint32_t m0 = load_bm(cb); cb.advance(nchunk, nwaves);
   uint32_t m1 = load_bm(cb); cb.advance(nchunk, nwaves);
   issue(ci, m0, w0); ci.advance(nchunk, nwaves);
+  stage_x();  // overlaps the first bitmap and window loads
   while (true) {
     uint32_t m2 = load_bm(cb); cb.advance(nchunk, nwaves);
     issue(ci, m1, w1); ci.advance(nchunk, nwaves);
@@ -147,10 +159,13 @@ template <int T>
 static int launch_t(cas_ctx* ctx, const GemvArgs& a, int batch, int grid, size_t lds) {
 #define CAS_LAUNCH(NBV)                                                                                      \
   do {                                                                                                       \
-    if (lds > 48 * 1024)                                                                                     \
+    static bool raised = false;                                                                              \
+    if (lds > 48 * 1024 && !raised) {                                                                        \
       CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_kernel<T, NBV>,                               \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));               \
-    hipLaunchKernelGGL((gemv_draft_kernel<T, NBV>), dim3(grid), dim3(256), lds, ctx->stream, a);             \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, ctx->lds_max));           \
+      raised = true;                                                                                         \
+    }                                                                                                        \
+    hipLaunchKernelGGL((gemv_draft_kernel<T, NBV>), dim3(grid), dim3(kGemvThreads), lds, ctx->stream, a);             \
   } while (0)
   switch (batch) {
     case 1: CAS_LAUNCH(1); break;
@@ -173,9 +188,12 @@ int launch_gemv_draft(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const 
   a.x = x; a.y = y;
   size_t lds = sizeof(float) * (size_t)((d.bw + 63) / 64 * 64) * 33 * batch;
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
-  static int wg_per_cu = [] { const char* e = getenv("CAS_GEMV_WG_PER_CU"); return e ? atoi(e) : 4; }();
-  int64_t want = (d.rows + 3) / 4;
-  int grid = (int)std::min<int64_t>(want, (int64_t)ctx->num_cu * wg_per_cu);
+  // every wave gets the same number of rows (within one): r rows per wave, as many waves as fit at once
+  static int waves_per_cu = [] { const char* e = getenv("CAS_GEMV_WAVES_PER_CU"); return e ? atoi(e) : 32; }();
+  const int64_t max_waves = (int64_t)ctx->num_cu * waves_per_cu;
+  const int64_t r = (d.rows + max_waves - 1) / max_waves;
+  a.nwaves = (int)((d.rows + r - 1) / r);
+  int grid = (a.nwaves + kGemvWaves - 1) / kGemvWaves;
   ProfScope prof(ctx, PROF_GEMV_DRAFT, 4.0 * (double)d.rows * (d.bw + d.sw));
   switch (d.t) {
     case 0: return launch_t<0>(ctx, a, batch, grid, lds);
