@@ -107,85 +107,113 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// Decode the values of one 32-column bitmap word from the packed streams and hand each
-// (column position, bf16 word) to `write`.  m: kept mask, pm: pruned mask (0 when only the
-// speculation data is read), p / u: kept / pruned values of the row before this word.
-// A lane that runs out of bits keeps calling write with position -1 and a don't-care value:
-// the caller maps -1 to a dump slot.  All 64 lanes of the wave must call this together.
-template <int T, bool FULL, class W>
-__device__ __forceinline__ void decode_word(uint32_t m, uint32_t pm, uint32_t p, uint32_t u,
-                                            const uint32_t* __restrict__ sp_row, const uint32_t* __restrict__ lo_row,
-                                            const uint32_t* __restrict__ pr_row, W&& write) {
-  constexpr int FW = 16 - T;
-  constexpr int LW = T > 0 ? T : 1;
-  uint32_t ws[FW], wl[LW], wp[16];
-  {
-    uint32_t bit = p * FW, sh = bit & 31u;
-    const uint32_t* src = sp_row + (bit >> 5);
-    uint32_t d[FW + 1];
+// Raw windows of the packed streams at one 32-column bitmap word: the words that hold the
+// word's kept fields (spec), their dropped bits (lo) and its pruned values, before alignment.
+// Loading and decoding are separate so the loads of the next word can be in flight while the
+// current one is decoded.
+template <int T, bool FULL>
+struct WordWindows {
+  static constexpr int FW = 16 - T;
+  static constexpr int LW = T > 0 ? T : 1;
+  uint32_t ds[FW + 1];
+  uint32_t dl[LW + 1];
+  uint32_t dp[17];
+  uint32_t shs, shl, shp;
+
+  // p / u: kept / pruned values of the row before this word
+  __device__ __forceinline__ void load(uint32_t p, uint32_t u, const uint32_t* __restrict__ sp_row,
+                                       const uint32_t* __restrict__ lo_row, const uint32_t* __restrict__ pr_row) {
+    {
+      uint32_t bit = p * FW;
+      shs = bit & 31u;
+      const uint32_t* src = sp_row + (bit >> 5);
 #pragma unroll
-    for (int q = 0; q <= FW; ++q) d[q] = src[q];
+      for (int q = 0; q <= FW; ++q) ds[q] = src[q];
+    }
+    if constexpr (FULL && T > 0) {
+      uint32_t bit = p * T;
+      shl = bit & 31u;
+      const uint32_t* src = lo_row + (bit >> 5);
 #pragma unroll
-    for (int q = 0; q < FW; ++q) ws[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
+      for (int q = 0; q <= T; ++q) dl[q] = src[q];
+    }
+    if constexpr (FULL) {
+      shp = (u & 1u) << 4;
+      const uint32_t* src = pr_row + (u >> 1);
+#pragma unroll
+      for (int q = 0; q <= 16; ++q) dp[q] = src[q];
+    }
   }
-  if constexpr (FULL && T > 0) {
-    uint32_t bit = p * T, sh = bit & 31u;
-    const uint32_t* src = lo_row + (bit >> 5);
-    uint32_t d[T + 1];
+
+  // Hands each (column position, bf16 word) of the word to `write`.  m: kept mask, pm: pruned
+  // mask (0 when only the speculation data is read).  A lane that runs out of bits keeps
+  // calling write with position -1 and a don't-care value: the caller maps -1 to a dump slot.
+  // All 64 lanes of the wave must call this together.
+  template <class W>
+  __device__ __forceinline__ void decode(uint32_t m, uint32_t pm, W&& write) const {
+    uint32_t ws[FW], wl[LW], wp[16];
 #pragma unroll
-    for (int q = 0; q <= T; ++q) d[q] = src[q];
+    for (int q = 0; q < FW; ++q) ws[q] = __builtin_amdgcn_alignbit(ds[q + 1], ds[q], shs);
+    if constexpr (FULL && T > 0) {
 #pragma unroll
-    for (int q = 0; q < T; ++q) wl[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
-  }
-  if constexpr (FULL) {
-    uint32_t sh = (u & 1u) << 4;
-    const uint32_t* src = pr_row + (u >> 1);
-    uint32_t d[17];
+      for (int q = 0; q < T; ++q) wl[q] = __builtin_amdgcn_alignbit(dl[q + 1], dl[q], shl);
+    }
+    if constexpr (FULL) {
 #pragma unroll
-    for (int q = 0; q <= 16; ++q) d[q] = src[q];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) wp[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
-  }
-  auto kept_group = [&](auto G) {
-    static_for<0, 8>([&](auto I) {
-      constexpr int e = decltype(G)::value * 8 + decltype(I)::value;
+      for (int q = 0; q < 16; ++q) wp[q] = __builtin_amdgcn_alignbit(dp[q + 1], dp[q], shp);
+    }
+    auto kept = [&](auto E) {
+      constexpr int e = decltype(E)::value;
       int pos = lowest_bit(m);
       m &= m - 1u;
       uint32_t v = field_at<FW, e>(ws) << T;
       if constexpr (FULL && T > 0) v |= field_at<T, e>(wl);
       write(pos, (uint16_t)v);
-    });
-  };
-  if (__builtin_amdgcn_ballot_w64(m != 0u)) {
-    kept_group(std::integral_constant<int, 0>{});
-    if (__builtin_amdgcn_ballot_w64(m != 0u)) {
-      kept_group(std::integral_constant<int, 1>{});
-      if (__builtin_amdgcn_ballot_w64(m != 0u)) {
-        kept_group(std::integral_constant<int, 2>{});
-        if (__builtin_amdgcn_ballot_w64(m != 0u)) kept_group(std::integral_constant<int, 3>{});
+    };
+    auto kept_tail = [&](auto self, auto E) -> void {
+      constexpr int e = decltype(E)::value;
+      if constexpr (e < 32) {
+        if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+          kept(std::integral_constant<int, e>{});
+          kept(std::integral_constant<int, e + 1>{});
+          self(self, std::integral_constant<int, e + 2>{});
+        }
       }
+    };
+    if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+      static_for<0, 8>(kept);
+      kept_tail(kept_tail, std::integral_constant<int, 8>{});
     }
-  }
-  if constexpr (FULL) {
-    auto pruned_group = [&](auto G) {
-      static_for<0, 8>([&](auto I) {
-        constexpr int e = decltype(G)::value * 8 + decltype(I)::value;
+    if constexpr (FULL) {
+      auto pruned = [&](auto E) {
+        constexpr int e = decltype(E)::value;
         int pos = lowest_bit(pm);
         pm &= pm - 1u;
         write(pos, (uint16_t)(wp[e >> 1] >> ((e & 1) * 16)));
-      });
-    };
-    if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
-      pruned_group(std::integral_constant<int, 0>{});
-      if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
-        pruned_group(std::integral_constant<int, 1>{});
-        if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
-          pruned_group(std::integral_constant<int, 2>{});
-          if (__builtin_amdgcn_ballot_w64(pm != 0u)) pruned_group(std::integral_constant<int, 3>{});
+      };
+      auto pruned_tail = [&](auto self, auto E) -> void {
+        constexpr int e = decltype(E)::value;
+        if constexpr (e < 32) {
+          if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
+            pruned(std::integral_constant<int, e>{});
+            pruned(std::integral_constant<int, e + 1>{});
+            self(self, std::integral_constant<int, e + 2>{});
+          }
         }
-      }
+      };
+      pruned_tail(pruned_tail, std::integral_constant<int, 0>{});
     }
   }
+};
+
+// One-shot form: load the windows of a word and decode it.
+template <int T, bool FULL, class W>
+__device__ __forceinline__ void decode_word(uint32_t m, uint32_t pm, uint32_t p, uint32_t u,
+                                            const uint32_t* __restrict__ sp_row, const uint32_t* __restrict__ lo_row,
+                                            const uint32_t* __restrict__ pr_row, W&& write) {
+  WordWindows<T, FULL> w;
+  w.load(p, u, sp_row, lo_row, pr_row);
+  w.decode(m, pm, write);
 }
 
 template <int CTRL>

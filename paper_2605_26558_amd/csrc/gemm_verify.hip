@@ -37,8 +37,6 @@ constexpr int kTilePitch = 148;         // 4 groups + 4 pad, keeps 8-byte alignm
 
 template <int T>
 __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
-  constexpr int FW = 16 - T;
-  constexpr int LW = T > 0 ? T : 1;
   extern __shared__ uint16_t lds[];
   uint16_t* Xs = lds;                                    // [ncols][kXPitch]
   uint16_t* tiles = lds + (size_t)a.ncols * kXPitch;     // [4][16][kTilePitch]
@@ -64,41 +62,50 @@ __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
   f32x4 C = {0.f, 0.f, 0.f, 0.f};
   uint32_t rowpre = 0;  // kept values of the row in earlier slabs
   const int nslab = (a.bw + 63) >> 6;
+  const bool xvec = (a.cols & 7) == 0;  // rows of X are 16-byte aligned
+
+  // bitmap words of a slab: lane (r, j) reads words 4j..4j+3 of each quarter v
+  uint32_t mw[4][4];
+  auto load_bitmaps = [&](int slab) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      int w0 = slab * 64 + v * 16 + 4 * j;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mw[v][i] = (w0 + i < a.bw) ? bm_row[w0 + i] : 0u;
+    }
+  };
+  load_bitmaps(0);
 
   for (int slab = 0; slab < nslab; ++slab) {
     __syncthreads();
     // ---- stage the slab of X (bf16, zero beyond the last column)
-    for (int c = 0; c < a.ncols; ++c) {
-      for (int i = tid; i < kSlabCols; i += 256) {
-        int col = slab * kSlabCols + i;
-        Xs[c * kXPitch + i] = col < a.cols ? a.X[(size_t)c * a.cols + col] : (uint16_t)0;
+    if (xvec) {
+      for (int i = tid; i < a.ncols * (kSlabCols / 8); i += 256) {
+        int c = i / (kSlabCols / 8), o = (i - c * (kSlabCols / 8)) * 8;
+        int col = slab * kSlabCols + o;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (col < a.cols) v = *reinterpret_cast<const uint4*>(a.X + (size_t)c * a.cols + col);
+        *reinterpret_cast<uint4*>(Xs + c * kXPitch + o) = v;
       }
+    } else {
+      for (int c = 0; c < a.ncols; ++c)
+        for (int i = tid; i < kSlabCols; i += 256) {
+          int col = slab * kSlabCols + i;
+          Xs[c * kXPitch + i] = col < a.cols ? a.X[(size_t)c * a.cols + col] : (uint16_t)0;
+        }
     }
-    // ---- bitmap words: lane (r, j) reads words 4j..4j+3 of each quarter v
-    uint32_t mw[4][4];
-    int cq[4];
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      int w0 = slab * 64 + v * 16 + 4 * j;
-      cq[v] = 0;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        mw[v][i] = (w0 + i < a.bw) ? bm_row[w0 + i] : 0u;
-        cq[v] += __popc(mw[v][i]);
-      }
-    }
-    // kept values of the row before this wave's quarter and before this lane's words
+    // ---- kept values of the row before this wave's quarter and before this lane's words
     uint32_t before = rowpre;
-    int slab_total = 0;
-    int own = 0;
+    int slab_total = 0, own = 0;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      int s = cq[v];
+      int cq = __popc(mw[v][0]) + __popc(mw[v][1]) + __popc(mw[v][2]) + __popc(mw[v][3]);
+      int s = cq;
       s += quad_dpp<0xB1>(s);  // quad_perm [1,0,3,2]
       s += quad_dpp<0x4E>(s);  // quad_perm [2,3,0,1]
       slab_total += s;
       if (v < wv) before += (uint32_t)s;
-      if (v == wv) own = cq[v];
+      if (v == wv) own = cq;
     }
     {
       int b0 = quad_dpp<0x00>(own), b1 = quad_dpp<0x55>(own), b2 = quad_dpp<0xAA>(own);
@@ -108,92 +115,33 @@ __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
     uint32_t m4[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) m4[i] = wv == 0 ? mw[0][i] : wv == 1 ? mw[1][i] : wv == 2 ? mw[2][i] : mw[3][i];
+    if (slab + 1 < nslab) load_bitmaps(slab + 1);  // in flight while this slab is decoded
+
+    // per word: kept / pruned masks and the positions of its first fields in the streams
+    const int word0 = slab * 64 + wv * 16 + 4 * j;
+    uint32_t pm4[4], p4[4], u4[4];
+    {
+      uint32_t p = before;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int nvalid = a.cols - (word0 + i) * 32;
+        const uint32_t valid = nvalid >= 32 ? 0xFFFFFFFFu : (nvalid <= 0 ? 0u : ((1u << nvalid) - 1u));
+        pm4[i] = ~m4[i] & valid;
+        // words past the end of the row have no fields: keep their (unused) windows in range
+        p4[i] = nvalid > 0 ? p : 0u;
+        u4[i] = nvalid > 0 ? (uint32_t)(word0 + i) * 32u - p : 0u;
+        p += (uint32_t)__popc(m4[i]);
+      }
+    }
+    WordWindows<T, true> win[2];
+    win[0].load(p4[0], u4[0], sp_row, lo_row, pr_row);
     __syncthreads();
 
-    const int word0 = slab * 64 + wv * 16 + 4 * j;  // first bitmap word of this lane
-    uint32_t p = before;                            // kept values before the current word
-    uint32_t u = (uint32_t)word0 * 32u - p;         // pruned values before the current word
-
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int colbase = (word0 + i) * 32;
-      uint32_t m = m4[i];
-      int nvalid = a.cols - colbase;
-      uint32_t valid = nvalid >= 32 ? 0xFFFFFFFFu : (nvalid <= 0 ? 0u : ((1u << nvalid) - 1u));
-      uint32_t pm = ~m & valid;
-      // words past the end of the row have no fields: keep their (unused) windows in range
-      const uint32_t pa = nvalid > 0 ? p : 0u, ua = nvalid > 0 ? u : 0u;
-      // ---- windows of the three streams at this word
-      uint32_t ws[FW], wl[LW], wp[16];
-      {
-        uint32_t bit = pa * FW, sh = bit & 31u;
-        const uint32_t* src = sp_row + (bit >> 5);
-        uint32_t d[FW + 1];
-#pragma unroll
-        for (int q = 0; q <= FW; ++q) d[q] = src[q];
-#pragma unroll
-        for (int q = 0; q < FW; ++q) ws[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
-      }
-      if constexpr (T > 0) {
-        uint32_t bit = pa * T, sh = bit & 31u;
-        const uint32_t* src = lo_row + (bit >> 5);
-        uint32_t d[T + 1];
-#pragma unroll
-        for (int q = 0; q <= T; ++q) d[q] = src[q];
-#pragma unroll
-        for (int q = 0; q < T; ++q) wl[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
-      }
-      {
-        uint32_t sh = (ua & 1u) << 4;
-        const uint32_t* src = pr_row + (ua >> 1);
-        uint32_t d[17];
-#pragma unroll
-        for (int q = 0; q <= 16; ++q) d[q] = src[q];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) wp[q] = __builtin_amdgcn_alignbit(d[q + 1], d[q], sh);
-      }
-      p += (uint32_t)__popc(m);
-      u += (uint32_t)__popc(pm);
-      (void)colbase;
-
-      // ---- kept values: leading bits | dropped bits
-      auto kept_group = [&](auto G) {
-        static_for<0, 8>([&](auto I) {
-          constexpr int e = decltype(G)::value * 8 + decltype(I)::value;
-          int pos = lowest_bit(m);
-          m &= m - 1u;
-          uint32_t v = field_at<FW, e>(ws) << T;
-          if constexpr (T > 0) v |= field_at<T, e>(wl);
-          trow[pos] = (uint16_t)v;  // pos == -1 lands in the dump slot in front of the group
-        });
-      };
-      kept_group(std::integral_constant<int, 0>{});
-      if (__builtin_amdgcn_ballot_w64(m != 0u)) {
-        kept_group(std::integral_constant<int, 1>{});
-        if (__builtin_amdgcn_ballot_w64(m != 0u)) {
-          kept_group(std::integral_constant<int, 2>{});
-          if (__builtin_amdgcn_ballot_w64(m != 0u)) kept_group(std::integral_constant<int, 3>{});
-        }
-      }
-      // ---- pruned values: verbatim words
-      auto pruned_group = [&](auto G) {
-        static_for<0, 8>([&](auto I) {
-          constexpr int e = decltype(G)::value * 8 + decltype(I)::value;
-          int pos = lowest_bit(pm);
-          pm &= pm - 1u;
-          trow[pos] = (uint16_t)(wp[e >> 1] >> ((e & 1) * 16));
-        });
-      };
-      if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
-        pruned_group(std::integral_constant<int, 0>{});
-        if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
-          pruned_group(std::integral_constant<int, 1>{});
-          if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
-            pruned_group(std::integral_constant<int, 2>{});
-            if (__builtin_amdgcn_ballot_w64(pm != 0u)) pruned_group(std::integral_constant<int, 3>{});
-          }
-        }
-      }
+    static_for<0, 4>([&](auto I) {
+      constexpr int i = decltype(I)::value;
+      if constexpr (i + 1 < 4) win[(i + 1) & 1].load(p4[i + 1], u4[i + 1], sp_row, lo_row, pr_row);
+      // pos == -1 (lane out of bits) lands in the dump slot in front of the group
+      win[i & 1].decode(m4[i], pm4[i], [&](int pos, uint16_t v) { trow[pos] = v; });
       // ---- tile x X: tile column 32*g + c is slab column wv*512 + (4*g + i)*32 + c
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -206,7 +154,7 @@ __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       __builtin_amdgcn_wave_barrier();
-    }
+    });
   }
 
   // ---- add the four partial tiles in wave order; C[i][n]: i = 4*(lane/16) + e, n = lane%16
