@@ -289,11 +289,11 @@ static int launch_mt(cas_ctx* ctx, const AttnArgs& a, dim3 grid) {
 #define CAS_LAUNCH(TV)                                                                                          \
   case TV:                                                                                                      \
     if (lds > 48 * 1024) {                                                                                      \
-      static bool raised = false;                                                                               \
-      if (!raised) {                                                                                            \
+      static size_t raised = 48 * 1024;                                                                               \
+      if (lds > raised) {                                                                                            \
         CAS_HIP(ctx, hipFuncSetAttribute((const void*)attn_partial_kernel<MT, FULL, TV>,                        \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, ctx->lds_max));            \
-        raised = true;                                                                                          \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));            \
+        raised = lds;                                                                                           \
       }                                                                                                         \
     }                                                                                                           \
     hipLaunchKernelGGL((attn_partial_kernel<MT, FULL, TV>), grid, dim3(256), lds, ctx->stream, a);              \

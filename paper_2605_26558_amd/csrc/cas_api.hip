@@ -27,6 +27,10 @@ int cas_ctx_create(cas_ctx** out, void* hip_stream, void* d_workspace, size_t ws
   e = hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
   if (e != hipSuccess) { c->last_hip = (int)e; delete c; return CAS_EHIP; }
   c->lds_max = v;
+  // gfx950 lets a workgroup opt in to more LDS than the default limit
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeSharedMemPerBlockOptin, dev) == hipSuccess && v > c->lds_max)
+    c->lds_max = v;
+  (void)hipGetLastError();
   *out = c;
   return CAS_OK;
 }

@@ -55,6 +55,8 @@ inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 int launch_encode_weight(cas_ctx*, const uint16_t* W, int64_t ld, const float* act, const cas_wdesc&, void* spec, void* verif);
 int launch_decode_weight(cas_ctx*, const cas_wdesc&, const void* spec, const void* verif, uint16_t* out, int64_t ld);
 int launch_gemv_draft(cas_ctx*, const cas_wdesc&, const void* spec, const uint16_t* x, int batch, float* y);
+int launch_gemv_draft_fused(cas_ctx*, const cas_wdesc&, const void* spec, const uint16_t* x, int batch, float* y,
+                            const uint16_t* gain, float eps, int epi, uint16_t* out16);
 int launch_gemm_verify(cas_ctx*, const cas_wdesc&, const void* spec, const void* verif, const uint16_t* X, int ncols, float* Y);
 int launch_kv_append(cas_ctx*, cas_kv*, int layer, int seq, const uint16_t* K, const uint16_t* V, int n_tok, int pos0);
 int launch_kv_read(cas_ctx*, cas_kv*, int layer, int seq, int pos0, int n_tok, int full, uint16_t* K, uint16_t* V);

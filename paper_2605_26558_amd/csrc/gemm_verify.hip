@@ -193,11 +193,11 @@ int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const
 #define CAS_LAUNCH(TV)                                                                                  \
   case TV:                                                                                              \
     if (lds > 48 * 1024) {                                                                            \
-      static bool raised = false;                                                                      \
-      if (!raised) {                                                                                   \
+      static size_t raised = 48 * 1024;                                                                      \
+      if (lds > raised) {                                                                                   \
         CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemm_verify_kernel<TV>,                                              \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, ctx->lds_max));   \
-        raised = true;                                                                                 \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));   \
+        raised = lds;                                                                                  \
       }                                                                                                \
     }          \
     hipLaunchKernelGGL((gemm_verify_kernel<TV>), dim3(grid), dim3(256), lds, ctx->stream, a);           \

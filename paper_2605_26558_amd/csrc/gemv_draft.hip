@@ -23,7 +23,12 @@ struct GemvArgs {
   const uint32_t* bitmap;
   const uint32_t* spec;
   const uint16_t* x;  // [NB][cols]
-  float* y;           // [NB][rows]
+  float* y;           // [NB][rows] (epilogue 0)
+  // optional fused neighbours of the linear layer
+  const uint16_t* gain;  // non-null: x is first RMS-normalised with this gain (rounded to bf16)
+  float eps;
+  int epi;               // 0: y = W x;  1: h = bf16(h + bf16(W x));  2: act[i] = swiglu(rows 2i, 2i+1)
+  uint16_t* out16;       // h [NB][rows] (epilogue 1) or act [NB][rows/2] (epilogue 2)
 };
 
 template <int FW>
@@ -35,10 +40,11 @@ struct Window {
 
 struct Cursor {  // walks the (row, chunk) items of one wave in order
   int row, chunk;
-  __device__ __forceinline__ void advance(int nchunk, int nwaves) {
+  // pair == 0: rows gw, gw + nwaves, ...; pair == 1: row pairs (2u, 2u+1) for u = gw, gw + nwaves, ...
+  __device__ __forceinline__ void advance(int nchunk, int nwaves, int pair) {
     if (++chunk == nchunk) {
       chunk = 0;
-      row += nwaves;
+      row += pair ? ((row & 1) ? 2 * nwaves - 1 : 1) : nwaves;
     }
   }
 };
@@ -57,6 +63,8 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   const int gw = blockIdx.x * kGemvWaves + (tid >> 6);
   const int nwaves = a.nwaves;  // rows are dealt round-robin to this many waves
   const bool idle = gw >= nwaves;  // still helps staging x
+  const int pair = a.epi == 2;
+  const int row_first = pair ? 2 * gw : gw;
 
   auto load_bm = [&](const Cursor& c) -> uint32_t {
     int wi = c.chunk * 64 + lane;
@@ -72,15 +80,15 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
     rowprefix = (c.chunk == nchunk - 1) ? 0u : rowprefix + (uint32_t)total;
     uint32_t bit = p * FW;
     w.sh = bit & 31u;
-    int row = c.row < a.rows ? c.row : gw;  // past the end: any valid row, its bitmap word is 0
+    int row = c.row < a.rows ? c.row : row_first;  // past the end: any valid row, its bitmap word is 0
     const uint32_t* src = a.spec + (size_t)row * a.sw + (bit >> 5);
 #pragma unroll
     for (int j = 0; j <= FW; ++j) w.d[j] = src[j];
   };
 
-  float acc[NB];
+  float acc[NB], gate[NB];
 #pragma unroll
-  for (int b = 0; b < NB; ++b) acc[b] = 0.f;
+  for (int b = 0; b < NB; ++b) acc[b] = gate[b] = 0.f;
 
   auto compute = [&](const Cursor& c, const Window<FW>& w) {
     uint32_t win[FW];
@@ -114,43 +122,83 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
         float s = wave_sum(acc[b]);
-        if (lane == 0) a.y[(size_t)b * a.rows + c.row] = s;
         acc[b] = 0.f;
+        if (a.epi == 0) {
+          if (lane == 0) a.y[(size_t)b * a.rows + c.row] = s;
+        } else if (a.epi == 1) {
+          uint16_t* hp = a.out16 + (size_t)b * a.rows + c.row;
+          if (lane == 0) *hp = f32_to_bf16(bf16_to_f32(*hp) + round_bf16(s));
+        } else {
+          if (c.row & 1) {  // up row: the gate row came just before
+            const float g = round_bf16(gate[b]), u = round_bf16(s);
+            if (lane == 0) a.out16[(size_t)b * (a.rows >> 1) + (c.row >> 1)] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
+          } else {
+            gate[b] = s;
+          }
+        }
       }
     }
   };
 
   auto stage_x = [&]() {
-  // ---- stage x as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0
-  for (int c = tid; c < nseg * 33; c += kGemvThreads) {
-    int seg = c / 33, e = c - seg * 33;
-    int col = seg * 32 + e - 1;
+    // ---- stage x as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0
+    float rn[NB];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      float v = (e > 0 && col < a.cols) ? bf16_to_f32(a.x[(size_t)b * a.cols + col]) : 0.f;
-      xs[c * NB + b] = v;
+    for (int b = 0; b < NB; ++b) rn[b] = 1.f;
+    if (a.gain) {  // RMSNorm of the input vector, recomputed by every workgroup
+      __shared__ float red[NB][kGemvWaves];
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        float ss = 0.f;
+        for (int c = tid; c < a.cols; c += kGemvThreads) {
+          float v = bf16_to_f32(a.x[(size_t)b * a.cols + c]);
+          ss += v * v;
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) red[b][tid >> 6] = ss;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        float ss = 0.f;
+#pragma unroll
+        for (int w = 0; w < kGemvWaves; ++w) ss += red[b][w];
+        rn[b] = 1.0f / sqrtf(ss / (float)a.cols + a.eps);
+      }
     }
-  }
-  __syncthreads();
+    for (int c = tid; c < nseg * 33; c += kGemvThreads) {
+      int seg = c / 33, e = c - seg * 33;
+      int col = seg * 32 + e - 1;
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        float v = 0.f;
+        if (e > 0 && col < a.cols) {
+          v = bf16_to_f32(a.x[(size_t)b * a.cols + col]);
+          if (a.gain) v = round_bf16(v * rn[b] * bf16_to_f32(a.gain[col]));
+        }
+        xs[c * NB + b] = v;
+      }
+    }
+    __syncthreads();
   };
-  Cursor cb{gw, 0}, ci{gw, 0}, cc{gw, 0};
+  Cursor cb{row_first, 0}, ci{row_first, 0}, cc{row_first, 0};
   Window<FW> w0, w1;
   if (idle) {
     stage_x();
     return;
   }
-  uint32_t m0 = load_bm(cb); cb.advance(nchunk, nwaves);
-  uint32_t m1 = load_bm(cb); cb.advance(nchunk, nwaves);
-  issue(ci, m0, w0); ci.advance(nchunk, nwaves);
+  uint32_t m0 = load_bm(cb); cb.advance(nchunk, nwaves, pair);
+  uint32_t m1 = load_bm(cb); cb.advance(nchunk, nwaves, pair);
+  issue(ci, m0, w0); ci.advance(nchunk, nwaves, pair);
   stage_x();  // overlaps the first bitmap and window loads
   while (true) {
-    uint32_t m2 = load_bm(cb); cb.advance(nchunk, nwaves);
-    issue(ci, m1, w1); ci.advance(nchunk, nwaves);
-    compute(cc, w0); cc.advance(nchunk, nwaves);
+    uint32_t m2 = load_bm(cb); cb.advance(nchunk, nwaves, pair);
+    issue(ci, m1, w1); ci.advance(nchunk, nwaves, pair);
+    compute(cc, w0); cc.advance(nchunk, nwaves, pair);
     if (cc.row >= a.rows) break;
-    m1 = load_bm(cb); cb.advance(nchunk, nwaves);
-    issue(ci, m2, w0); ci.advance(nchunk, nwaves);
-    compute(cc, w1); cc.advance(nchunk, nwaves);
+    m1 = load_bm(cb); cb.advance(nchunk, nwaves, pair);
+    issue(ci, m2, w0); ci.advance(nchunk, nwaves, pair);
+    compute(cc, w1); cc.advance(nchunk, nwaves, pair);
     if (cc.row >= a.rows) break;
   }
 }
@@ -159,11 +207,11 @@ template <int T>
 static int launch_t(cas_ctx* ctx, const GemvArgs& a, int batch, int grid, size_t lds) {
 #define CAS_LAUNCH(NBV)                                                                                      \
   do {                                                                                                       \
-    static bool raised = false;                                                                              \
-    if (lds > 48 * 1024 && !raised) {                                                                        \
+    static size_t raised = 48 * 1024;                                                                              \
+    if (lds > raised) {                                                                        \
       CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_kernel<T, NBV>,                               \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, ctx->lds_max));           \
-      raised = true;                                                                                         \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));           \
+      raised = lds;                                                                                          \
     }                                                                                                        \
     hipLaunchKernelGGL((gemv_draft_kernel<T, NBV>), dim3(grid), dim3(kGemvThreads), lds, ctx->stream, a);             \
   } while (0)
@@ -180,8 +228,15 @@ static int launch_t(cas_ctx* ctx, const GemvArgs& a, int batch, int grid, size_t
 }
 
 int launch_gemv_draft(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const uint16_t* x, int batch, float* y) {
+  return launch_gemv_draft_fused(ctx, d, spec, x, batch, y, nullptr, 0.f, 0, nullptr);
+}
+
+int launch_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const uint16_t* x, int batch,
+                            float* y, const uint16_t* gain, float eps, int epi, uint16_t* out16) {
   if (d.rows <= 0) return CAS_OK;
+  if (epi == 2 && (d.rows & 1)) return CAS_EINVAL;
   GemvArgs a;
+  a.gain = gain; a.eps = eps; a.epi = epi; a.out16 = out16;
   a.rows = (int)d.rows; a.cols = (int)d.cols; a.bw = d.bw; a.sw = d.sw;
   a.bitmap = (const uint32_t*)((const char*)spec + d.off_bitmap);
   a.spec = (const uint32_t*)((const char*)spec + d.off_spec);
@@ -191,8 +246,9 @@ int launch_gemv_draft(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const 
   // every wave gets the same number of rows (within one): r rows per wave, as many waves as fit at once
   static int waves_per_cu = [] { const char* e = getenv("CAS_GEMV_WAVES_PER_CU"); return e ? atoi(e) : 32; }();
   const int64_t max_waves = (int64_t)ctx->num_cu * waves_per_cu;
-  const int64_t r = (d.rows + max_waves - 1) / max_waves;
-  a.nwaves = (int)((d.rows + r - 1) / r);
+  const int64_t units = epi == 2 ? d.rows / 2 : d.rows;  // a gate/up row pair stays in one wave
+  const int64_t r = (units + max_waves - 1) / max_waves;
+  a.nwaves = (int)((units + r - 1) / r);
   int grid = (a.nwaves + kGemvWaves - 1) / kGemvWaves;
   ProfScope prof(ctx, PROF_GEMV_DRAFT, 4.0 * (double)d.rows * (d.bw + d.sw));
   switch (d.t) {

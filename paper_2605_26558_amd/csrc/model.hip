@@ -18,6 +18,8 @@ struct cas_model {
   uint16_t *h, *xn, *q, *ao, *act, *knew, *vnew;
   float *y, *logits;
   int32_t *tok, *tgt;  // token chain of a round: pending + drafts, and the target's tokens
+  float* amax_v;       // per-slice argmax candidates
+  int32_t* amax_i;
 };
 
 namespace cas {
@@ -102,37 +104,40 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ y
   }
 }
 
-// token = lowest index among the maxima of a logits row
-__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int vocab,
-                                                      int32_t* __restrict__ out) {
-  __shared__ float bv[16];
-  __shared__ int bi[16];
-  const int c = blockIdx.x;
+// token = lowest index among the maxima of a logits row; stage 1: one candidate per slice
+constexpr int kArgmaxSlices = 64;
+__device__ __forceinline__ void argmax_fold(float& best, int& idx, float v, int i) {
+  if (v > best || (v == best && i < idx)) { best = v; idx = i; }
+}
+__global__ __launch_bounds__(256) void argmax_part_kernel(const float* __restrict__ logits, int vocab,
+                                                          float* __restrict__ pv, int32_t* __restrict__ pi) {
+  __shared__ float bv[4];
+  __shared__ int bi[4];
+  const int c = blockIdx.y, sl = blockIdx.x;
+  const int per = (vocab + kArgmaxSlices - 1) / kArgmaxSlices;
+  const int lo = sl * per, hi = min(vocab, lo + per);
   const float* x = logits + (size_t)c * vocab;
   float best = -INFINITY;
   int idx = 0x7FFFFFFF;
-  for (int i = threadIdx.x; i < vocab; i += 1024) {
-    float v = x[i];
-    if (v > best || (v == best && i < idx)) { best = v; idx = i; }
-  }
+  for (int i = lo + threadIdx.x; i < hi; i += 256) argmax_fold(best, idx, x[i], i);
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    float ov = __shfl_xor(best, o, 64);
-    int oi = __shfl_xor(idx, o, 64);
-    if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
-  }
+  for (int o = 32; o > 0; o >>= 1) argmax_fold(best, idx, __shfl_xor(best, o, 64), __shfl_xor(idx, o, 64));
   if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = idx; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    for (int w = 1; w < 16; ++w)
-      if (bv[w] > best || (bv[w] == best && bi[w] < idx)) { best = bv[w]; idx = bi[w]; }
-    out[c] = idx == 0x7FFFFFFF ? 0 : idx;
+    for (int w = 1; w < 4; ++w) argmax_fold(best, idx, bv[w], bi[w]);
+    pv[c * kArgmaxSlices + sl] = best;
+    pi[c * kArgmaxSlices + sl] = idx;
   }
 }
-
-static int linear(cas_ctx* ctx, const cas_tensor& w, const uint16_t* x, int ncols, bool full, float* y) {
-  if (full) return launch_gemm_verify(ctx, w.desc, w.d_spec, w.d_verif, x, ncols, y);
-  return launch_gemv_draft(ctx, w.desc, w.d_spec, x, ncols, y);
+__global__ __launch_bounds__(64) void argmax_final_kernel(const float* __restrict__ pv, const int32_t* __restrict__ pi,
+                                                          int32_t* __restrict__ out) {
+  const int c = blockIdx.x;
+  float best = pv[c * kArgmaxSlices + threadIdx.x];
+  int idx = pi[c * kArgmaxSlices + threadIdx.x];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) argmax_fold(best, idx, __shfl_xor(best, o, 64), __shfl_xor(idx, o, 64));
+  if (threadIdx.x == 0) out[c] = idx == 0x7FFFFFFF ? 0 : idx;
 }
 
 #define CAS_TRY(expr)            \
@@ -156,8 +161,14 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_
     const cas_layer_weights& L = m->layers[l];
     uint16_t* kn = m->knew + (size_t)l * c.max_cols * kvd;
     uint16_t* vn = m->vnew + (size_t)l * c.max_cols * kvd;
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, L.d_g_attn, m->xn, c.hidden, c.rms_eps);
-    CAS_TRY(linear(ctx, L.wqkv, m->xn, ncols, full, m->y));
+    // the draft pass fuses the norms, residual adds and SwiGLU into its GEMV launches
+    if (full) {
+      hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, L.d_g_attn, m->xn, c.hidden, c.rms_eps);
+      CAS_TRY(launch_gemm_verify(ctx, L.wqkv.desc, L.wqkv.d_spec, L.wqkv.d_verif, m->xn, ncols, m->y));
+    } else {
+      CAS_TRY(launch_gemv_draft_fused(ctx, L.wqkv.desc, L.wqkv.d_spec, m->h, ncols, m->y, L.d_g_attn, c.rms_eps, 0,
+                                      nullptr));
+    }
     hipLaunchKernelGGL(qkv_post_kernel, dim3(c.n_q_heads + 2 * c.n_kv_heads, ncols), dim3(64), 0, st, m->y,
                        qd + 2 * kvd, c.n_q_heads, c.n_kv_heads, m->d_rope, pos0, slot0, m->q, kn, vn);
     AttnCall ac;
@@ -165,20 +176,36 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_
     ac.Q = m->q; ac.ncols = ncols; ac.n_q_heads = c.n_q_heads;
     ac.Knew = kn; ac.Vnew = vn; ac.n_new = slot0 + ncols; ac.O = m->ao;
     CAS_TRY(launch_attention(ctx, kv, ac));
-    CAS_TRY(linear(ctx, L.wo, m->ao, ncols, full, m->y));
-    hipLaunchKernelGGL(resid_add_kernel, dim3((c.hidden + 255) / 256, ncols), dim3(256), 0, st, m->h, m->y, c.hidden,
-                       c.hidden);
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, L.d_g_ffn, m->xn, c.hidden, c.rms_eps);
-    CAS_TRY(linear(ctx, L.wgu, m->xn, ncols, full, m->y));
-    hipLaunchKernelGGL(swiglu_kernel, dim3((c.ffn + 255) / 256, ncols), dim3(256), 0, st, m->y, 2 * c.ffn, m->act,
-                       c.ffn);
-    CAS_TRY(linear(ctx, L.wd, m->act, ncols, full, m->y));
-    hipLaunchKernelGGL(resid_add_kernel, dim3((c.hidden + 255) / 256, ncols), dim3(256), 0, st, m->h, m->y, c.hidden,
-                       c.hidden);
+    if (full) {
+      CAS_TRY(launch_gemm_verify(ctx, L.wo.desc, L.wo.d_spec, L.wo.d_verif, m->ao, ncols, m->y));
+      hipLaunchKernelGGL(resid_add_kernel, dim3((c.hidden + 255) / 256, ncols), dim3(256), 0, st, m->h, m->y,
+                         c.hidden, c.hidden);
+      hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, L.d_g_ffn, m->xn, c.hidden, c.rms_eps);
+      CAS_TRY(launch_gemm_verify(ctx, L.wgu.desc, L.wgu.d_spec, L.wgu.d_verif, m->xn, ncols, m->y));
+      hipLaunchKernelGGL(swiglu_kernel, dim3((c.ffn + 255) / 256, ncols), dim3(256), 0, st, m->y, 2 * c.ffn, m->act,
+                         c.ffn);
+      CAS_TRY(launch_gemm_verify(ctx, L.wd.desc, L.wd.d_spec, L.wd.d_verif, m->act, ncols, m->y));
+      hipLaunchKernelGGL(resid_add_kernel, dim3((c.hidden + 255) / 256, ncols), dim3(256), 0, st, m->h, m->y,
+                         c.hidden, c.hidden);
+    } else {
+      CAS_TRY(launch_gemv_draft_fused(ctx, L.wo.desc, L.wo.d_spec, m->ao, ncols, nullptr, nullptr, 0.f, 1, m->h));
+      CAS_TRY(launch_gemv_draft_fused(ctx, L.wgu.desc, L.wgu.d_spec, m->h, ncols, nullptr, L.d_g_ffn, c.rms_eps, 2,
+                                      m->act));
+      CAS_TRY(launch_gemv_draft_fused(ctx, L.wd.desc, L.wd.d_spec, m->act, ncols, nullptr, nullptr, 0.f, 1, m->h));
+    }
   }
-  hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, m->d_g_final, m->xn, c.hidden, c.rms_eps);
-  CAS_TRY(linear(ctx, m->lm_head, m->xn, ncols, full, logits));
-  if (d_out) hipLaunchKernelGGL(argmax_kernel, dim3(ncols), dim3(1024), 0, st, logits, c.vocab, d_out);
+  if (full) {
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, m->d_g_final, m->xn, c.hidden, c.rms_eps);
+    CAS_TRY(launch_gemm_verify(ctx, m->lm_head.desc, m->lm_head.d_spec, m->lm_head.d_verif, m->xn, ncols, logits));
+  } else {
+    CAS_TRY(launch_gemv_draft_fused(ctx, m->lm_head.desc, m->lm_head.d_spec, m->h, ncols, logits, m->d_g_final,
+                                    c.rms_eps, 0, nullptr));
+  }
+  if (d_out) {
+    hipLaunchKernelGGL(argmax_part_kernel, dim3(kArgmaxSlices, ncols), dim3(256), 0, st, logits, c.vocab, m->amax_v,
+                       m->amax_i);
+    hipLaunchKernelGGL(argmax_final_kernel, dim3(ncols), dim3(64), 0, st, m->amax_v, m->amax_i, d_out);
+  }
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;
 }
@@ -190,7 +217,7 @@ static size_t carve(size_t& off, size_t bytes) {
 }
 
 struct ActLayout {
-  size_t h, xn, q, ao, act, knew, vnew, y, logits, tok, tgt, total;
+  size_t h, xn, q, ao, act, knew, vnew, y, logits, tok, tgt, amax_v, amax_i, total;
 };
 
 static ActLayout act_layout(const cas_model_cfg& c) {
@@ -209,6 +236,8 @@ static ActLayout act_layout(const cas_model_cfg& c) {
   L.logits = carve(off, nc * (size_t)c.vocab * 4);
   L.tok = carve(off, (nc + 1) * 4);
   L.tgt = carve(off, (nc + 1) * 4);
+  L.amax_v = carve(off, nc * kArgmaxSlices * 4);
+  L.amax_i = carve(off, nc * kArgmaxSlices * 4);
   L.total = off;
   return L;
 }
@@ -268,6 +297,7 @@ int cas_model_create(const cas_model_cfg* cfg, const cas_model_weights* w, void*
   m->knew = (uint16_t*)(b + L.knew); m->vnew = (uint16_t*)(b + L.vnew);
   m->y = (float*)(b + L.y); m->logits = (float*)(b + L.logits);
   m->tok = (int32_t*)(b + L.tok); m->tgt = (int32_t*)(b + L.tgt);
+  m->amax_v = (float*)(b + L.amax_v); m->amax_i = (int32_t*)(b + L.amax_i);
   *out = m;
   return CAS_OK;
 }
