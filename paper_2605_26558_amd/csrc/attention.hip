@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   float* s_l = s_m + MT * 16;                 // running sum per row
   float* s_c = s_l + MT * 16;                 // rescale factor of the current page
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int split = blockIdx.x, head = blockIdx.y;
   const int R = a.ncols * a.grp;
   const KvGeom& g = a.g;

@@ -35,17 +35,25 @@ constexpr int kXPitch = kSlabCols + 8;  // bf16 per X row in LDS
 constexpr int kGroupPitch = 36;         // 4 dump slots + 32 columns
 constexpr int kTilePitch = 148;         // 4 groups + 4 pad, keeps 8-byte alignment, spreads banks
 
-template <int T>
-__global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
+// G row groups of 16 rows per workgroup, each split over Q waves that take 2048/Q columns of
+// every slab; lane (r, j) of a wave owns 16/Q consecutive bitmap words per slab.
+template <int T, int G, int Q>
+__global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
+  constexpr int NW = G * Q;          // waves per workgroup
+  constexpr int NT = 64 * NW;        // threads
+  constexpr int WPP = 64 / Q;        // bitmap words per part and slab
+  constexpr int WPL = WPP / 4;       // words per lane and slab = decode steps per slab
+  static_assert(WPL >= 1, "at most 16 parts");
   extern __shared__ uint16_t lds[];
   uint16_t* Xs = lds;                                    // [ncols][kXPitch]
-  uint16_t* tiles = lds + (size_t)a.ncols * kXPitch;     // [4][16][kTilePitch]
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  uint16_t* tiles = lds + (size_t)a.ncols * kXPitch;     // [NW][16][kTilePitch]
+  const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int gi = wv / Q, part = wv % Q;
   uint16_t* tile = tiles + wv * 16 * kTilePitch;
-  for (int i = tid; i < 4 * 16 * kTilePitch; i += 256) tiles[i] = 0;
+  for (int i = tid; i < NW * 16 * kTilePitch; i += NT) tiles[i] = 0;
 
   const int r = lane >> 2, j = lane & 3;
-  const int row0 = blockIdx.x * 16;
+  const int row0 = (blockIdx.x * G + gi) * 16;
   const int row = min(row0 + r, a.rows - 1);
   const uint32_t* bm_row = a.bitmap + (size_t)row * a.bw;
   const uint32_t* sp_row = a.spec + (size_t)row * a.sw;
@@ -57,21 +65,21 @@ __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
   const int mi = lane & 15, mq = lane >> 4;
   const uint16_t* a_base = tile + mi * kTilePitch + 4 + 4 * mq;
   const int bcol = mi < a.ncols ? mi : 0;
-  const uint16_t* b_base = Xs + bcol * kXPitch + wv * 512 + 4 * mq;
+  const uint16_t* b_base = Xs + bcol * kXPitch + part * (WPP * 32) + 4 * mq;
 
   f32x4 C = {0.f, 0.f, 0.f, 0.f};
   uint32_t rowpre = 0;  // kept values of the row in earlier slabs
   const int nslab = (a.bw + 63) >> 6;
   const bool xvec = (a.cols & 7) == 0;  // rows of X are 16-byte aligned
 
-  // bitmap words of a slab: lane (r, j) reads words 4j..4j+3 of each quarter v
-  uint32_t mw[4][4];
+  // bitmap words of a slab: for every part v, this lane's words v*WPP + j*WPL + i
+  uint32_t mw[Q][WPL];
   auto load_bitmaps = [&](int slab) {
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      int w0 = slab * 64 + v * 16 + 4 * j;
+    for (int v = 0; v < Q; ++v) {
+      int w0 = slab * 64 + v * WPP + j * WPL;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) mw[v][i] = (w0 + i < a.bw) ? bm_row[w0 + i] : 0u;
+      for (int i = 0; i < WPL; ++i) mw[v][i] = (w0 + i < a.bw) ? bm_row[w0 + i] : 0u;
     }
   };
   load_bitmaps(0);
@@ -80,7 +88,7 @@ __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
     __syncthreads();
     // ---- stage the slab of X (bf16, zero beyond the last column)
     if (xvec) {
-      for (int i = tid; i < a.ncols * (kSlabCols / 8); i += 256) {
+      for (int i = tid; i < a.ncols * (kSlabCols / 8); i += NT) {
         int c = i / (kSlabCols / 8), o = (i - c * (kSlabCols / 8)) * 8;
         int col = slab * kSlabCols + o;
         uint4 v = make_uint4(0, 0, 0, 0);
@@ -89,41 +97,45 @@ __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
       }
     } else {
       for (int c = 0; c < a.ncols; ++c)
-        for (int i = tid; i < kSlabCols; i += 256) {
+        for (int i = tid; i < kSlabCols; i += NT) {
           int col = slab * kSlabCols + i;
           Xs[c * kXPitch + i] = col < a.cols ? a.X[(size_t)c * a.cols + col] : (uint16_t)0;
         }
     }
-    // ---- kept values of the row before this wave's quarter and before this lane's words
+    // ---- kept values of the row before this wave's part and before this lane's words
     uint32_t before = rowpre;
     int slab_total = 0, own = 0;
+    uint32_t m4[WPL];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      int cq = __popc(mw[v][0]) + __popc(mw[v][1]) + __popc(mw[v][2]) + __popc(mw[v][3]);
+    for (int v = 0; v < Q; ++v) {
+      int cq = 0;
+#pragma unroll
+      for (int i = 0; i < WPL; ++i) cq += __popc(mw[v][i]);
       int s = cq;
       s += quad_dpp<0xB1>(s);  // quad_perm [1,0,3,2]
       s += quad_dpp<0x4E>(s);  // quad_perm [2,3,0,1]
       slab_total += s;
-      if (v < wv) before += (uint32_t)s;
-      if (v == wv) own = cq;
+      if (v < part) before += (uint32_t)s;
+      if (v == part) {
+        own = cq;
+#pragma unroll
+        for (int i = 0; i < WPL; ++i) m4[i] = mw[v][i];
+      }
     }
     {
       int b0 = quad_dpp<0x00>(own), b1 = quad_dpp<0x55>(own), b2 = quad_dpp<0xAA>(own);
       before += (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
     }
     rowpre += (uint32_t)slab_total;
-    uint32_t m4[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) m4[i] = wv == 0 ? mw[0][i] : wv == 1 ? mw[1][i] : wv == 2 ? mw[2][i] : mw[3][i];
     if (slab + 1 < nslab) load_bitmaps(slab + 1);  // in flight while this slab is decoded
 
     // per word: kept / pruned masks and the positions of its first fields in the streams
-    const int word0 = slab * 64 + wv * 16 + 4 * j;
-    uint32_t pm4[4], p4[4], u4[4];
+    const int word0 = slab * 64 + part * WPP + j * WPL;
+    uint32_t pm4[WPL], p4[WPL], u4[WPL];
     {
       uint32_t p = before;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < WPL; ++i) {
         const int nvalid = a.cols - (word0 + i) * 32;
         const uint32_t valid = nvalid >= 32 ? 0xFFFFFFFFu : (nvalid <= 0 ? 0u : ((1u << nvalid) - 1u));
         pm4[i] = ~m4[i] & valid;
@@ -137,19 +149,19 @@ __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
     win[0].load(p4[0], u4[0], sp_row, lo_row, pr_row);
     __syncthreads();
 
-    static_for<0, 4>([&](auto I) {
+    static_for<0, WPL>([&](auto I) {
       constexpr int i = decltype(I)::value;
-      if constexpr (i + 1 < 4) win[(i + 1) & 1].load(p4[i + 1], u4[i + 1], sp_row, lo_row, pr_row);
+      if constexpr (i + 1 < WPL) win[(i + 1) & 1].load(p4[i + 1], u4[i + 1], sp_row, lo_row, pr_row);
       // pos == -1 (lane out of bits) lands in the dump slot in front of the group
       win[i & 1].decode(m4[i], pm4[i], [&](int pos, uint16_t v) { trow[pos] = v; });
-      // ---- tile x X: tile column 32*g + c is slab column wv*512 + (4*g + i)*32 + c
+      // ---- tile x X: tile column 32*g + c is slab column (part*WPP + g*WPL + i)*32 + c
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         const int g = kk >> 1, h = kk & 1;
         bf16x4 av = *reinterpret_cast<const bf16x4*>(a_base + g * kGroupPitch + h * 16);
-        bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + (4 * g + i) * 32 + h * 16);
+        bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + (g * WPL + i) * 32 + h * 16);
         C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, bv, C, 0, 0, 0);
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -157,21 +169,48 @@ __global__ __launch_bounds__(256) void gemm_verify_kernel(VerifyArgs a) {
     });
   }
 
-  // ---- add the four partial tiles in wave order; C[i][n]: i = 4*(lane/16) + e, n = lane%16
+  // ---- add the Q partial tiles of each row group in part order; C[i][n]: i = 4*(lane/16) + e, n = lane%16
   __syncthreads();
-  float* red = reinterpret_cast<float*>(lds);  // [4][64][4], reuses the X slab
+  float* red = reinterpret_cast<float*>(lds);  // [NW][64][4], reuses the X slab and tiles
   *reinterpret_cast<f32x4*>(red + (wv * 64 + lane) * 4) = C;
   __syncthreads();
-  if (wv == 0 && mi < a.ncols) {
-    f32x4 s = *reinterpret_cast<f32x4*>(red + lane * 4);
+  if (part == 0 && mi < a.ncols) {
+    f32x4 s = *reinterpret_cast<f32x4*>(red + (wv * 64 + lane) * 4);
 #pragma unroll
-    for (int w = 1; w < 4; ++w) s += *reinterpret_cast<f32x4*>(red + (w * 64 + lane) * 4);
+    for (int w = 1; w < Q; ++w) s += *reinterpret_cast<f32x4*>(red + ((wv + w) * 64 + lane) * 4);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       int orow = row0 + 4 * mq + e;
       if (orow < a.rows) a.Y[(size_t)mi * a.rows + orow] = s[e];
     }
   }
+}
+
+template <int G, int Q>
+static int launch_gq(cas_ctx* ctx, const VerifyArgs& a, int t) {
+  constexpr int NW = G * Q;
+  size_t lds = sizeof(uint16_t) * ((size_t)a.ncols * kXPitch + NW * 16 * kTilePitch);
+  lds = std::max(lds, sizeof(float) * NW * 64 * 4);
+  if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
+  const int groups = (a.rows + 15) / 16;
+  const int grid = (groups + G - 1) / G;
+#define CAS_LAUNCH(TV)                                                                                  \
+  case TV: {                                                                                            \
+    static size_t raised = 48 * 1024;                                                                   \
+    if (lds > raised) {                                                                                 \
+      CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemm_verify_kernel<TV, G, Q>,                       \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));          \
+      raised = lds;                                                                                     \
+    }                                                                                                   \
+    hipLaunchKernelGGL((gemm_verify_kernel<TV, G, Q>), dim3(grid), dim3(64 * NW), lds, ctx->stream, a); \
+  } break;
+  switch (t) {
+    CAS_LAUNCH(0) CAS_LAUNCH(1) CAS_LAUNCH(2) CAS_LAUNCH(3) CAS_LAUNCH(4) CAS_LAUNCH(5) CAS_LAUNCH(6) CAS_LAUNCH(7)
+    default: return CAS_EINVAL;
+  }
+#undef CAS_LAUNCH
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
 }
 
 int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const void* verif, const uint16_t* X,
@@ -185,30 +224,10 @@ int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const
   a.lo = (const uint32_t*)((const char*)verif + d.off_lo);
   a.pruned = (const uint32_t*)((const char*)verif + d.off_pruned);
   a.X = X; a.Y = Y;
-  size_t lds = sizeof(uint16_t) * ((size_t)ncols * kXPitch + 4 * 16 * kTilePitch);
-  lds = std::max(lds, sizeof(float) * 4 * 64 * 4);
-  if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
-  int grid = (int)((d.rows + 15) / 16);
   ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + d.sw + d.lw + d.pw));
-#define CAS_LAUNCH(TV)                                                                                  \
-  case TV:                                                                                              \
-    if (lds > 48 * 1024) {                                                                            \
-      static size_t raised = 48 * 1024;                                                                      \
-      if (lds > raised) {                                                                                   \
-        CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemm_verify_kernel<TV>,                                              \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));   \
-        raised = lds;                                                                                  \
-      }                                                                                                \
-    }          \
-    hipLaunchKernelGGL((gemm_verify_kernel<TV>), dim3(grid), dim3(256), lds, ctx->stream, a);           \
-    break;
-  switch (d.t) {
-    CAS_LAUNCH(0) CAS_LAUNCH(1) CAS_LAUNCH(2) CAS_LAUNCH(3) CAS_LAUNCH(4) CAS_LAUNCH(5) CAS_LAUNCH(6) CAS_LAUNCH(7)
-    default: return CAS_EINVAL;
-  }
-#undef CAS_LAUNCH
-  CAS_HIP(ctx, hipGetLastError());
-  return CAS_OK;
+  // one row group per workgroup, four waves each taking a quarter of every slab (measured
+  // faster than 8-wave workgroups in either arrangement: fewer lanes wait at the slab barriers)
+  return launch_gq<1, 4>(ctx, a, d.t);
 }
 
 }  // namespace cas

@@ -60,7 +60,8 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   const int nchunk = (a.bw + 63) >> 6;
   const int nseg = nchunk * 64;
   const int lane = tid & 63;
-  const int gw = blockIdx.x * kGemvWaves + (tid >> 6);
+  // wave-uniform values are made scalar explicitly so the row/chunk bookkeeping runs on the SALU
+  const int gw = blockIdx.x * kGemvWaves + __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nwaves = a.nwaves;  // rows are dealt round-robin to this many waves
   const bool idle = gw >= nwaves;  // still helps staging x
   const int pair = a.epi == 2;
