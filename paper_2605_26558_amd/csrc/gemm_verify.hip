@@ -36,7 +36,10 @@ constexpr int kGroupPitch = 36;         // 4 dump slots + 32 columns
 constexpr int kTilePitch = 148;         // 4 groups + 4 pad, keeps 8-byte alignment, spreads banks
 
 // G row groups of 16 rows per workgroup, each split over Q waves that take 2048/Q columns of
-// every slab; lane (r, j) of a wave owns 16/Q consecutive bitmap words per slab.
+// every slab.  At decode step i the four lanes (r, 0..3) of a row take four CONSECUTIVE bitmap
+// words, so one step reads one contiguous run of each stream per row and every cache line is
+// fetched by one step only (lines are not kept in L1 between steps: 12 waves x 16 rows x 3
+// streams are far more than it holds).
 template <int T, int G, int Q>
 __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
   constexpr int NW = G * Q;          // waves per workgroup
@@ -72,14 +75,14 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
   const int nslab = (a.bw + 63) >> 6;
   const bool xvec = (a.cols & 7) == 0;  // rows of X are 16-byte aligned
 
-  // bitmap words of a slab: for every part v, this lane's words v*WPP + j*WPL + i
+  // bitmap words of a slab: for every part v, this lane's words v*WPP + 4*i + j
   uint32_t mw[Q][WPL];
   auto load_bitmaps = [&](int slab) {
 #pragma unroll
     for (int v = 0; v < Q; ++v) {
-      int w0 = slab * 64 + v * WPP + j * WPL;
+      int w0 = slab * 64 + v * WPP + j;
 #pragma unroll
-      for (int i = 0; i < WPL; ++i) mw[v][i] = (w0 + i < a.bw) ? bm_row[w0 + i] : 0u;
+      for (int i = 0; i < WPL; ++i) mw[v][i] = (w0 + 4 * i < a.bw) ? bm_row[w0 + 4 * i] : 0u;
     }
   };
   load_bitmaps(0);
@@ -102,9 +105,9 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
           Xs[c * kXPitch + i] = col < a.cols ? a.X[(size_t)c * a.cols + col] : (uint16_t)0;
         }
     }
-    // ---- kept values of the row before this wave's part and before this lane's words
+    // ---- kept values of the row before this wave's part, then before each of this lane's words
     uint32_t before = rowpre;
-    int slab_total = 0, own = 0;
+    int slab_total = 0;
     uint32_t m4[WPL];
 #pragma unroll
     for (int v = 0; v < Q; ++v) {
@@ -117,32 +120,30 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
       slab_total += s;
       if (v < part) before += (uint32_t)s;
       if (v == part) {
-        own = cq;
 #pragma unroll
         for (int i = 0; i < WPL; ++i) m4[i] = mw[v][i];
       }
-    }
-    {
-      int b0 = quad_dpp<0x00>(own), b1 = quad_dpp<0x55>(own), b2 = quad_dpp<0xAA>(own);
-      before += (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
     }
     rowpre += (uint32_t)slab_total;
     if (slab + 1 < nslab) load_bitmaps(slab + 1);  // in flight while this slab is decoded
 
     // per word: kept / pruned masks and the positions of its first fields in the streams
-    const int word0 = slab * 64 + part * WPP + j * WPL;
+    const int word0 = slab * 64 + part * WPP + j;
     uint32_t pm4[WPL], p4[WPL], u4[WPL];
     {
-      uint32_t p = before;
+      uint32_t pstep = before;  // kept values before the four words of step i
 #pragma unroll
       for (int i = 0; i < WPL; ++i) {
-        const int nvalid = a.cols - (word0 + i) * 32;
+        const int cnt = __popc(m4[i]);
+        const int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt), b3 = quad_dpp<0xFF>(cnt);
+        const uint32_t p = pstep + (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
+        pstep += (uint32_t)(b0 + b1 + b2 + b3);
+        const int nvalid = a.cols - (word0 + 4 * i) * 32;
         const uint32_t valid = nvalid >= 32 ? 0xFFFFFFFFu : (nvalid <= 0 ? 0u : ((1u << nvalid) - 1u));
         pm4[i] = ~m4[i] & valid;
         // words past the end of the row have no fields: keep their (unused) windows in range
         p4[i] = nvalid > 0 ? p : 0u;
-        u4[i] = nvalid > 0 ? (uint32_t)(word0 + i) * 32u - p : 0u;
-        p += (uint32_t)__popc(m4[i]);
+        u4[i] = nvalid > 0 ? (uint32_t)(word0 + 4 * i) * 32u - p : 0u;
       }
     }
     WordWindows<T, true> win[2];
@@ -154,14 +155,14 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
       if constexpr (i + 1 < WPL) win[(i + 1) & 1].load(p4[i + 1], u4[i + 1], sp_row, lo_row, pr_row);
       // pos == -1 (lane out of bits) lands in the dump slot in front of the group
       win[i & 1].decode(m4[i], pm4[i], [&](int pos, uint16_t v) { trow[pos] = v; });
-      // ---- tile x X: tile column 32*g + c is slab column (part*WPP + g*WPL + i)*32 + c
+      // ---- tile x X: tile column 32*g + c is slab column (part*WPP + 4*i + g)*32 + c
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         const int g = kk >> 1, h = kk & 1;
         bf16x4 av = *reinterpret_cast<const bf16x4*>(a_base + g * kGroupPitch + h * 16);
-        bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + (g * WPL + i) * 32 + h * 16);
+        bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + (4 * i + g) * 32 + h * 16);
         C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, bv, C, 0, 0, 0);
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
