@@ -9,7 +9,9 @@
 // four words the lane walks the set bits (kept: leading bits from spec, low bits from lo) and
 // then the clear bits (pruned: verbatim word) and scatters the bf16 values into a 16 x 128
 // tile in LDS.  The tile is then multiplied with the matching 128 rows of X by eight
-// 16x16x16 bf16 MFMA operations, accumulating in fp32.  Each output column uses the same
+// 16x16x16 bf16 MFMA operations, accumulating in fp32.  Every wave stages the X columns of
+// its own part of the slab into its own LDS region, so waves never wait for each other inside
+// the column loop.  Each output column uses the same
 // sequence of operations whatever the number of columns is.  The four partial tiles of a
 // workgroup are added in wave order through LDS.
 #include "cas_device.hpp"
@@ -31,7 +33,6 @@ struct VerifyArgs {
 };
 
 constexpr int kSlabCols = 2048;
-constexpr int kXPitch = kSlabCols + 8;  // bf16 per X row in LDS
 constexpr int kGroupPitch = 36;         // 4 dump slots + 32 columns
 constexpr int kTilePitch = 148;         // 4 groups + 4 pad, keeps 8-byte alignment, spreads banks
 
@@ -47,13 +48,16 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
   constexpr int WPP = 64 / Q;        // bitmap words per part and slab
   constexpr int WPL = WPP / 4;       // words per lane and slab = decode steps per slab
   static_assert(WPL >= 1, "at most 16 parts");
+  constexpr int XQ = WPP * 32;       // X columns one wave needs per slab
+  constexpr int XQP = XQ + 8;        // row pitch of its private copy (bf16)
   extern __shared__ uint16_t lds[];
-  uint16_t* Xs = lds;                                    // [ncols][kXPitch]
-  uint16_t* tiles = lds + (size_t)a.ncols * kXPitch;     // [NW][16][kTilePitch]
+  uint16_t* tiles = lds;                                 // [NW][16][kTilePitch]
   const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int gi = wv / Q, part = wv % Q;
   uint16_t* tile = tiles + wv * 16 * kTilePitch;
+  uint16_t* Xq = lds + NW * 16 * kTilePitch + (size_t)wv * a.ncols * XQP;  // [ncols][XQP], this wave's
   for (int i = tid; i < NW * 16 * kTilePitch; i += NT) tiles[i] = 0;
+  __syncthreads();
 
   const int r = lane >> 2, j = lane & 3;
   const int row0 = (blockIdx.x * G + gi) * 16;
@@ -68,12 +72,12 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
   const int mi = lane & 15, mq = lane >> 4;
   const uint16_t* a_base = tile + mi * kTilePitch + 4 + 4 * mq;
   const int bcol = mi < a.ncols ? mi : 0;
-  const uint16_t* b_base = Xs + bcol * kXPitch + part * (WPP * 32) + 4 * mq;
+  const uint16_t* b_base = Xq + bcol * XQP + 4 * mq;
+  const bool xvec = (a.cols & 7) == 0;  // 16-byte pieces of X rows are aligned and never straddle the end
 
   f32x4 C = {0.f, 0.f, 0.f, 0.f};
   uint32_t rowpre = 0;  // kept values of the row in earlier slabs
   const int nslab = (a.bw + 63) >> 6;
-  const bool xvec = (a.cols & 7) == 0;  // rows of X are 16-byte aligned
 
   // bitmap words of a slab: for every part v, this lane's words v*WPP + 4*i + j
   uint32_t mw[Q][WPL];
@@ -88,23 +92,6 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
   load_bitmaps(0);
 
   for (int slab = 0; slab < nslab; ++slab) {
-    __syncthreads();
-    // ---- stage the slab of X (bf16, zero beyond the last column)
-    if (xvec) {
-      for (int i = tid; i < a.ncols * (kSlabCols / 8); i += NT) {
-        int c = i / (kSlabCols / 8), o = (i - c * (kSlabCols / 8)) * 8;
-        int col = slab * kSlabCols + o;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (col < a.cols) v = *reinterpret_cast<const uint4*>(a.X + (size_t)c * a.cols + col);
-        *reinterpret_cast<uint4*>(Xs + c * kXPitch + o) = v;
-      }
-    } else {
-      for (int c = 0; c < a.ncols; ++c)
-        for (int i = tid; i < kSlabCols; i += NT) {
-          int col = slab * kSlabCols + i;
-          Xs[c * kXPitch + i] = col < a.cols ? a.X[(size_t)c * a.cols + col] : (uint16_t)0;
-        }
-    }
     // ---- kept values of the row before this wave's part, then before each of this lane's words
     uint32_t before = rowpre;
     int slab_total = 0;
@@ -148,7 +135,22 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
     }
     WordWindows<T, true> win[2];
     win[0].load(p4[0], u4[0], sp_row, lo_row, pr_row);
-    __syncthreads();
+    // ---- this wave's X columns of the slab (bf16, zero beyond the last column)
+    {
+      const int col0 = slab * kSlabCols + part * XQ;
+      if (xvec) {
+        for (int i = lane; i < a.ncols * (XQ / 8); i += 64) {
+          int c = i / (XQ / 8), o = (i - c * (XQ / 8)) * 8;
+          uint4 v = make_uint4(0, 0, 0, 0);
+          if (col0 + o < a.cols) v = *reinterpret_cast<const uint4*>(a.X + (size_t)c * a.cols + col0 + o);
+          *reinterpret_cast<uint4*>(Xq + c * XQP + o) = v;
+        }
+      } else {
+        for (int c = 0; c < a.ncols; ++c)
+          for (int i = lane; i < XQ; i += 64)
+            Xq[c * XQP + i] = col0 + i < a.cols ? a.X[(size_t)c * a.cols + col0 + i] : (uint16_t)0;
+      }
+    }
 
     static_for<0, WPL>([&](auto I) {
       constexpr int i = decltype(I)::value;
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
 
   // ---- add the Q partial tiles of each row group in part order; C[i][n]: i = 4*(lane/16) + e, n = lane%16
   __syncthreads();
-  float* red = reinterpret_cast<float*>(lds);  // [NW][64][4], reuses the X slab and tiles
+  float* red = reinterpret_cast<float*>(lds);  // [NW][64][4], reuses the tiles
   *reinterpret_cast<f32x4*>(red + (wv * 64 + lane) * 4) = C;
   __syncthreads();
   if (part == 0 && mi < a.ncols) {
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
 template <int G, int Q>
 static int launch_gq(cas_ctx* ctx, const VerifyArgs& a, int t) {
   constexpr int NW = G * Q;
-  size_t lds = sizeof(uint16_t) * ((size_t)a.ncols * kXPitch + NW * 16 * kTilePitch);
+  size_t lds = sizeof(uint16_t) * (NW * 16 * kTilePitch + (size_t)NW * a.ncols * ((64 / Q) * 32 + 8));
   lds = std::max(lds, sizeof(float) * NW * 64 * 4);
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
   const int groups = (a.rows + 15) / 16;
@@ -228,6 +230,9 @@ int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const
   ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + d.sw + d.lw + d.pw));
   // one row group per workgroup, four waves each taking a quarter of every slab (measured
   // faster than 8-wave workgroups in either arrangement: fewer lanes wait at the slab barriers)
+  // few row groups: split each over eight waves so that every CU still gets several waves
+  static int q8_below = [] { const char* e = getenv("CAS_VERIFY_Q8_BELOW"); return e ? atoi(e) : 300; }();
+  if ((d.rows + 15) / 16 < q8_below) return launch_gq<1, 8>(ctx, a, d.t);
   return launch_gq<1, 4>(ctx, a, d.t);
 }
 
