@@ -117,6 +117,17 @@ int cas_decode_weight(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
 int cas_gemv_draft(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
                    const uint16_t* d_x, int batch, float* d_y);
 
+/* The same kernel with the neighbours of a linear layer fused in, as the draft pass of the
+ * model uses it (Fig. 2_1 structure).  d_gain != NULL: x is first RMS-normalised,
+ * x' = bf16(x * rsqrt(mean(x^2) + eps) * gain), recomputed by every workgroup.  epilogue:
+ *   0: d_y[b][r] = W x'                               (d_out16 unused)
+ *   1: d_out16[b][r] = bf16(d_out16[b][r] + bf16(W x'))   residual update of a bf16 vector
+ *   2: d_out16[b][i] = bf16(silu(bf16(W x')[2i]) * bf16(W x')[2i+1])   SwiGLU over row pairs
+ * (rows must be even).  d_y may be NULL for epilogues 1 and 2. */
+int cas_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
+                         const uint16_t* d_x, int batch, float* d_y, const uint16_t* d_gain,
+                         float eps, int epilogue, uint16_t* d_out16);
+
 /* Verification GEMM (Sec. 2.2 batched verification, Sec. 4.1 target inference):
  * Y[c][r] = sum_j W[r][j] * X[c][j] with W the exact bf16 matrix rebuilt from both buffers.
  * d_X: bf16 [ncols][cols]; d_Y: float [ncols][rows]; ncols in 1..16.  The value of a column

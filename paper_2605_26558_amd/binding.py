@@ -78,6 +78,8 @@ _SIGNATURES = {
                                     C.c_int64]),
     "cas_gemv_draft": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.c_void_p, C.c_int,
                                  C.c_void_p]),
+    "cas_gemv_draft_fused": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.c_void_p, C.c_int,
+                                       C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_void_p]),
     "cas_gemm_verify": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                   C.c_int, C.c_void_p]),
     "cas_kv_desc_init": (C.c_int, [C.POINTER(cas_kv_desc)]),
@@ -229,6 +231,14 @@ def cas_gemv_draft(ctx: Context, ew: EncodedWeight, x, out=None):
     ctx._check(_lib().cas_gemv_draft(ctx.h, C.byref(ew.desc), _ptr(ew.spec), _ptr(x), x.shape[0], _ptr(out)),
                "cas_gemv_draft")
     return out
+
+
+def cas_gemv_draft_fused(ctx: Context, ew: EncodedWeight, x, y=None, gain=None, eps=0.0, epilogue=0, out16=None):
+    """Fused form: optional RMSNorm of x (gain), epilogue 0 = fp32 y, 1 = residual into out16,
+    2 = SwiGLU of row pairs into out16."""
+    ctx._check(_lib().cas_gemv_draft_fused(ctx.h, C.byref(ew.desc), _ptr(ew.spec), _ptr(x), x.shape[0], _ptr(y),
+                                           _ptr(gain), eps, epilogue, _ptr(out16)), "cas_gemv_draft_fused")
+    return y if epilogue == 0 else out16
 
 
 def cas_gemm_verify(ctx: Context, ew: EncodedWeight, X, out=None):

@@ -135,6 +135,14 @@ int cas_gemv_draft(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, cons
   return cas::launch_gemv_draft(ctx, *desc, d_spec, d_x, batch, d_y);
 }
 
+int cas_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, const uint16_t* d_x, int batch,
+                         float* d_y, const uint16_t* d_gain, float eps, int epilogue, uint16_t* d_out16) {
+  if (!ctx || !d_spec || !d_x || check_desc(desc) != CAS_OK) return CAS_EINVAL;
+  if (batch < 1 || batch > 4 || !cas::aligned256(d_spec) || epilogue < 0 || epilogue > 2) return CAS_EINVAL;
+  if ((epilogue == 0 && !d_y) || (epilogue != 0 && !d_out16)) return CAS_EINVAL;
+  return cas::launch_gemv_draft_fused(ctx, *desc, d_spec, d_x, batch, d_y, d_gain, eps, epilogue, d_out16);
+}
+
 int cas_gemm_verify(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, const void* d_verif,
                     const uint16_t* d_X, int ncols, float* d_Y) {
   if (!ctx || !d_spec || !d_verif || !d_X || !d_Y || check_desc(desc) != CAS_OK) return CAS_EINVAL;

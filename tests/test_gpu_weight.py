@@ -147,3 +147,37 @@ def test_accept_matches_oracle(env):
         d = rng.integers(0, 3, size=k).tolist()
         t = rng.integers(0, 3, size=k + 1).tolist()
         assert B.cas_accept(d, t) == O.accept_greedy(d, t)
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 300), (96, 4096), (30, 2500)])
+def test_fused_draft_gemv_variants_match_oracle(env, rows, cols):
+    """RMSNorm prologue, residual epilogue and SwiGLU epilogue of the draft GEMV against the
+    oracle's separate operations."""
+    torch, B, ctx = env
+    W = synth.weight_matrix(rows, cols, seed=5)
+    x = synth.normal_bf16((1, cols), 2.0, seed=6)
+    g = synth.f32_to_bf16_bits(1.0 + 0.1 * np.random.default_rng(0).standard_normal(cols).astype(np.float32))
+    h0 = synth.normal_bf16((1, rows), 1.0, seed=7)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), 600, 4)
+    p = O.encode_weight(W, 600, 4)
+    xn = O.rmsnorm(x[0], g, 1e-5)
+    yref = O.gemv_draft(p, xn)
+    tol = _tol(W, xn[None])[0]
+    # epilogue 0 with the norm prologue
+    y = B.cas_gemv_draft_fused(ctx, ew, _dev(torch, x), y=torch.empty((1, rows), device="cuda"), gain=_dev(torch, g),
+                               eps=1e-5).cpu().numpy()[0]
+    assert (np.abs(y - yref) / tol).max() < 2e-3
+    # epilogue 1: residual update of a bf16 vector (no norm)
+    h = _dev(torch, h0.copy())
+    B.cas_gemv_draft_fused(ctx, ew, _dev(torch, x), epilogue=1, out16=h)
+    href = O.add_bf16(h0[0], O.gemv_draft(p, x[0]))
+    got = O.bf16_to_f64(h.cpu().numpy().view(np.uint16)[0])
+    assert np.abs(got - O.bf16_to_f64(href)).max() <= 2.0 ** -7 * np.abs(O.bf16_to_f64(href)).max()
+    assert (h.cpu().numpy().view(np.uint16)[0] != href).mean() < 0.02     # rare 1-ulp rounding flips only
+    # epilogue 2: SwiGLU over row pairs with the norm prologue
+    act = torch.zeros((1, rows // 2), dtype=torch.int16, device="cuda")
+    B.cas_gemv_draft_fused(ctx, ew, _dev(torch, x), gain=_dev(torch, g), eps=1e-5, epilogue=2, out16=act)
+    aref = O.swiglu(yref[0::2], yref[1::2])
+    ga = O.bf16_to_f64(act.cpu().numpy().view(np.uint16)[0]); ra = O.bf16_to_f64(aref)
+    assert np.abs(ga - ra).max() <= 2.0 ** -6 * np.abs(ra).max() + 1e-6
+    assert (act.cpu().numpy().view(np.uint16)[0] != aref).mean() < 0.05
