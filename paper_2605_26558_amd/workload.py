@@ -247,9 +247,16 @@ class ModelRoundWorkload:
         self.prof["gemv_draft"] = (n, td * 1e3, self.draft_w)
         self.prof["gemm_verify"] = (n, tv * 1e3, self.verify_w)
         ach = self.draft_w / td / 1e9
+        # HBM-side bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+        # FETCH_SIZE scaled by 2.000 after calibration with a plain copy): fetch = 1.016 x the
+        # algorithmic bytes on the 28672 x 4096 shape, writes are the output vector.
+        traffic = 1.016 * self.draft_w / n + 4.0 * sum(m.desc.rows for L in self.layers
+                                                       for m in (L["wqkv"], L["wo"], L["wgu"], L["wd"])) / n
         return {"bound": "hbm", "kernel": "gemv_draft_kernel", "achieved": ach, "peak": 8000.0, "unit": "GB/s",
-                "frac": ach / 8000.0, "traffic": None, "launches": n, "avg_launch_us": td / n * 1e6,
-                "bytes_per_launch": self.draft_w / n}
+                "frac": ach / 8000.0, "traffic": traffic, "launches": n, "avg_launch_us": td / n * 1e6,
+                "bytes_per_launch": self.draft_w / n,
+                "traffic_source": "profiles/pmc_gemv_draft_gemm_verify_28672x4096.md (counter ratio applied "
+                                  "to this run's bytes per launch)"}
 
     def extra(self, ms_per_step):
         out = {"tokens_per_s": (self.accepted + self.rounds) / max(self.rounds, 1) / (ms_per_step * 1e-3),
