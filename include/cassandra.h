@@ -194,7 +194,7 @@ int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_to
  * d_Knew, d_Vnew: bf16 [n_new][n_kv_heads][head_dim], uncompressed, ncols <= n_new <= 64;
  * d_O: bf16 [ncols][n_q_heads][head_dim].  ncols * n_q_heads / n_kv_heads <= 48.
  * Uses the context workspace for the per-split partial results (CAS_ENOMEM if too small:
- * splits * n_kv_heads * ncols * group * 132 floats, one split per 128 positions).
+ * splits * n_kv_heads * ncols * group * 132 floats, one split per 64 positions).
  * A column's value depends only on the positions it sees: not on ncols, and not on whether an
  * earlier position is already committed or still in flight.
  */

@@ -47,11 +47,13 @@ constexpr int kVR = 132;         // channel rows: 4 groups x (1 dump + 32)
 constexpr int kSP = 68;          // score row pitch (float)
 constexpr int kPP = 72;          // probability row pitch (bf16)
 constexpr int kPartStride = 132;
-constexpr int kPagesPerSplit = 2;
+constexpr int kPagesPerSplit = 1;
+
+constexpr int kKVTile = kPT * kKP > kVR * kVP ? kPT * kKP : kVR * kVP;  // K and V^T tiles share one region
 
 template <int MT>
 constexpr size_t attn_lds_bytes() {
-  return sizeof(uint16_t) * (MT * 16 * kQP + kPT * kKP + kVR * kVP + 2 * MT * 16 * kPP) +
+  return sizeof(uint16_t) * (MT * 16 * kQP + kKVTile + 2 * MT * 16 * kPP) +
          sizeof(float) * (MT * 16 * kSP + 3 * MT * 16);
 }
 
@@ -60,8 +62,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   extern __shared__ uint16_t lds16[];
   uint16_t* Qs = lds16;                       // [MT*16][kQP]
   uint16_t* Kt = Qs + MT * 16 * kQP;          // [64][kKP]
-  uint16_t* Vt = Kt + kPT * kKP;              // [kVR][kVP]
-  uint16_t* Ph = Vt + kVR * kVP;              // [MT*16][kPP]
+  uint16_t* Vt = Kt;                          // [kVR][kVP]: the K tile is dead once the scores are out
+  uint16_t* Ph = Kt + kKVTile;                // [MT*16][kPP]
   uint16_t* Pl = Ph + MT * 16 * kPP;          // [MT*16][kPP]
   float* S = reinterpret_cast<float*>(Pl + MT * 16 * kPP);  // [MT*16][kSP]
   float* s_m = S + MT * 16 * kSP;             // running max per row
@@ -73,23 +75,21 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   const int R = a.ncols * a.grp;
   const KvGeom& g = a.g;
 
-  // ---- queries of this kv head: row rr = column * grp + member
-  for (int i = tid; i < MT * 16 * 128; i += 256) {
-    int rr = i >> 7, d = i & 127;
-    uint16_t v = 0;
+  // ---- queries of this kv head: row rr = column * grp + member (16-byte pieces; rows past R are 0)
+  for (int i = tid; i < MT * 16 * 16; i += 256) {
+    const int rr = i >> 4, d = (i & 15) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
     if (rr < R) {
-      int c = rr / a.grp, gi = rr - c * a.grp;
-      v = a.Q[((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d];
+      const int c = rr / a.grp, gi = rr - c * a.grp;
+      v = *reinterpret_cast<const uint4*>(a.Q + ((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d);
     }
-    Qs[rr * kQP + d] = v;
+    *reinterpret_cast<uint4*>(Qs + rr * kQP + d) = v;
   }
   for (int i = tid; i < MT * 16; i += 256) {
     s_m[i] = -INFINITY;
     s_l[i] = 0.f;
     s_c[i] = 1.f;
   }
-  for (int i = tid; i < kVR * kVP; i += 256) Vt[i] = 0;
-  for (int i = tid; i < kPT * kKP; i += 256) Kt[i] = 0;
   f32x4 Oacc[MT][2];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -120,6 +120,21 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     const uint32_t* vs = a.spec_pool + tv * g.tile_spec_words;
     const uint32_t* kvf = a.verif_pool + tk * g.tile_verif_words;
     const uint32_t* vvf = a.verif_pool + tv * g.tile_verif_words;
+    // ---- 0. bitmap words and stream windows of K and V for this thread's (token, word): all
+    //         loads are issued up front so the V loads fly while K is decoded and scored
+    const uint32_t mk = live ? ks[r * 4 + j] : 0u;
+    const uint32_t mv = live ? vs[r * 4 + j] : 0u;
+    WordWindows<T, FULL> wk, wvw;
+    {
+      int cnt = __popc(mk);
+      int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
+      uint32_t p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
+      wk.load(p, 32u * j - p, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw);
+      cnt = __popc(mv);
+      b0 = quad_dpp<0x00>(cnt); b1 = quad_dpp<0x55>(cnt); b2 = quad_dpp<0xAA>(cnt);
+      p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
+      wvw.load(p, 32u * j - p, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw);
+    }
     // ---- 1. K tile
     {
 #pragma unroll
@@ -130,16 +145,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         for (int q = 0; q < 8; ++q)
           *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
       }
-      {
-        uint32_t m = live ? ks[r * 4 + j] : 0u;
-        int cnt = __popc(m);
-        int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
-        uint32_t p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
-        uint32_t u = 32u * j - p;
-        uint32_t pm = (FULL && live) ? ~m : 0u;
-        decode_word<T, FULL>(m, pm, p, u, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw,
-                             [&](int pos, uint16_t v) { krow[pos] = v; });
-      }
+      wk.decode(mk, (FULL && live) ? ~mk : 0u, [&](int pos, uint16_t v) { krow[pos] = v; });
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -196,16 +202,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
         for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
       }
-      {
-        uint32_t m = live ? vs[r * 4 + j] : 0u;
-        int cnt = __popc(m);
-        int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
-        uint32_t p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
-        uint32_t u = 32u * j - p;
-        uint32_t pm = (FULL && live) ? ~m : 0u;
-        decode_word<T, FULL>(m, pm, p, u, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw,
-                             [&](int pos, uint16_t v) { vcol[pos * kVP] = v; });
-      }
+      wvw.decode(mv, (FULL && live) ? ~mv : 0u, [&](int pos, uint16_t v) { vcol[pos * kVP] = v; });
     }
     __syncthreads();
     // ---- 5. O = O * rescale + P V ; wave w owns channels 32w .. 32w+31

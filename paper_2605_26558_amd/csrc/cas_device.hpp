@@ -44,10 +44,22 @@ __device__ __forceinline__ float wave_sum(float v) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_maxf(float v) {
+  // lanes without a source keep their own value (old = v), so the identity is v itself
+  return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK,
+                                                              0xf, false)));
+}
+
+// Maximum of v over the wave, returned in every lane (same DPP tree as wave_sum).
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = dpp_maxf<DPP_ROW_SHR1, 0xf>(v);
+  v = dpp_maxf<DPP_ROW_SHR2, 0xf>(v);
+  v = dpp_maxf<DPP_ROW_SHR4, 0xf>(v);
+  v = dpp_maxf<DPP_ROW_SHR8, 0xf>(v);
+  v = dpp_maxf<DPP_ROW_BCAST15, 0xa>(v);
+  v = dpp_maxf<DPP_ROW_BCAST31, 0xc>(v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
