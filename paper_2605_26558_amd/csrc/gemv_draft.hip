@@ -142,42 +142,104 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   };
 
   auto stage_x = [&]() {
-    // ---- stage x as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0
+    // ---- stage x as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0.
+    // Fast path (cols a multiple of 8, at most 2 pieces of 8 per thread): x is read once with
+    // 16-byte loads and kept in registers between the norm reduction and the LDS writes.
+    for (int sgi = tid; sgi < nseg; sgi += kGemvThreads) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) xs[sgi * 33 * NB + b] = 0.f;
+    }
+    const int npiece = (nseg * 32) >> 3;  // pieces of 8 columns, including the zero tail
+    const bool fast = (a.cols & 7) == 0 && npiece <= 2 * kGemvThreads;
     float rn[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) rn[b] = 1.f;
-    if (a.gain) {  // RMSNorm of the input vector, recomputed by every workgroup
-      __shared__ float red[NB][kGemvWaves];
+    __shared__ float red[NB][kGemvWaves];
+    auto finish_norm = [&](const float (&ss)[NB]) {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
-        float ss = 0.f;
-        for (int c = tid; c < a.cols; c += kGemvThreads) {
-          float v = bf16_to_f32(a.x[(size_t)b * a.cols + c]);
-          ss += v * v;
-        }
-        ss = wave_sum(ss);
-        if (lane == 0) red[b][tid >> 6] = ss;
+        float t = wave_sum(ss[b]);
+        if (lane == 0) red[b][tid >> 6] = t;
       }
       __syncthreads();
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
-        float ss = 0.f;
+        float t = 0.f;
 #pragma unroll
-        for (int w = 0; w < kGemvWaves; ++w) ss += red[b][w];
-        rn[b] = 1.0f / sqrtf(ss / (float)a.cols + a.eps);
+        for (int w = 0; w < kGemvWaves; ++w) t += red[b][w];
+        rn[b] = 1.0f / sqrtf(t / (float)a.cols + a.eps);
       }
-    }
-    for (int c = tid; c < nseg * 33; c += kGemvThreads) {
-      int seg = c / 33, e = c - seg * 33;
-      int col = seg * 32 + e - 1;
+    };
+    if (fast) {
+      uint4 raw[2][NB];
+      float ss[NB];
 #pragma unroll
-      for (int b = 0; b < NB; ++b) {
-        float v = 0.f;
-        if (e > 0 && col < a.cols) {
-          v = bf16_to_f32(a.x[(size_t)b * a.cols + col]);
-          if (a.gain) v = round_bf16(v * rn[b] * bf16_to_f32(a.gain[col]));
+      for (int b = 0; b < NB; ++b) ss[b] = 0.f;
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int col = (tid + k * kGemvThreads) * 8;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          raw[k][b] = make_uint4(0, 0, 0, 0);
+          if (col < a.cols) raw[k][b] = *reinterpret_cast<const uint4*>(a.x + (size_t)b * a.cols + col);
+          const uint32_t wd[4] = {raw[k][b].x, raw[k][b].y, raw[k][b].z, raw[k][b].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float lo = __uint_as_float(wd[e] << 16), hi = __uint_as_float(wd[e] & 0xFFFF0000u);
+            ss[b] += lo * lo;
+            ss[b] += hi * hi;
+          }
         }
-        xs[c * NB + b] = v;
+      }
+      if (a.gain) finish_norm(ss);
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int piece = tid + k * kGemvThreads;
+        const int col = piece * 8;
+        if (piece < npiece) {
+          uint4 gv = make_uint4(0, 0, 0, 0);
+          if (a.gain && col < a.cols) gv = *reinterpret_cast<const uint4*>(a.gain + col);
+          const uint32_t gw4[4] = {gv.x, gv.y, gv.z, gv.w};
+          float* dst = xs + ((col >> 5) * 33 + 1 + (col & 31)) * NB;
+#pragma unroll
+          for (int b = 0; b < NB; ++b) {
+            const uint32_t wd[4] = {raw[k][b].x, raw[k][b].y, raw[k][b].z, raw[k][b].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              float lo = __uint_as_float(wd[e] << 16), hi = __uint_as_float(wd[e] & 0xFFFF0000u);
+              if (a.gain) {
+                lo = round_bf16(lo * rn[b] * __uint_as_float(gw4[e] << 16));
+                hi = round_bf16(hi * rn[b] * __uint_as_float(gw4[e] & 0xFFFF0000u));
+              }
+              dst[(2 * e) * NB + b] = lo;
+              dst[(2 * e + 1) * NB + b] = hi;
+            }
+          }
+        }
+      }
+    } else {
+      if (a.gain) {
+        float ss[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          ss[b] = 0.f;
+          for (int c = tid; c < a.cols; c += kGemvThreads) {
+            float v = bf16_to_f32(a.x[(size_t)b * a.cols + c]);
+            ss[b] += v * v;
+          }
+        }
+        finish_norm(ss);
+      }
+      for (int col = tid; col < nseg * 32; col += kGemvThreads) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          float v = 0.f;
+          if (col < a.cols) {
+            v = bf16_to_f32(a.x[(size_t)b * a.cols + col]);
+            if (a.gain) v = round_bf16(v * rn[b] * bf16_to_f32(a.gain[col]));
+          }
+          xs[((col >> 5) * 33 + 1 + (col & 31)) * NB + b] = v;
+        }
       }
     }
     __syncthreads();
