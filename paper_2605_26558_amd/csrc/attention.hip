@@ -34,6 +34,14 @@ struct AttnArgs {
   const uint16_t* Knew;
   const uint16_t* Vnew;
   int n_new;
+  // fused split of the qkv projection (model path): when qkv != null the columns' q, k, v are
+  // taken from the fp32 projection output, rounded to bf16 and rotated here, and the k, v of
+  // the columns are also written to their in-flight slots for later passes and the commit
+  const float* qkv;   // [ncols][ystride]: q heads, k heads, v heads
+  int ystride, slot0; // slot0: in-flight slot of column 0 (its position is len + slot0)
+  const float* rope;  // [max_pos][64][2] cos, sin
+  uint16_t* Kslot;    // writable views of Knew / Vnew
+  uint16_t* Vslot;
   float scale;
   float* part;  // [nsplit][n_kv_heads][R][132]
   uint16_t* O;
@@ -48,12 +56,13 @@ constexpr int kSP = 68;          // score row pitch (float)
 constexpr int kPP = 72;          // probability row pitch (bf16)
 constexpr int kPartStride = 132;
 constexpr int kPagesPerSplit = 1;
+constexpr int kMaxCols = 16;     // columns of one pass whose k, v may be split from the projection here
 
 constexpr int kKVTile = kPT * kKP > kVR * kVP ? kPT * kKP : kVR * kVP;  // K and V^T tiles share one region
 
 template <int MT>
 constexpr size_t attn_lds_bytes() {
-  return sizeof(uint16_t) * (MT * 16 * kQP + kKVTile + 2 * MT * 16 * kPP) +
+  return sizeof(uint16_t) * (MT * 16 * kQP + kKVTile + 2 * MT * 16 * kPP + 2 * kMaxCols * 128) +
          sizeof(float) * (MT * 16 * kSP + 3 * MT * 16);
 }
 
@@ -69,26 +78,72 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   float* s_m = S + MT * 16 * kSP;             // running max per row
   float* s_l = s_m + MT * 16;                 // running sum per row
   float* s_c = s_l + MT * 16;                 // rescale factor of the current page
+  uint16_t* Fk = reinterpret_cast<uint16_t*>(s_c + MT * 16);  // [kMaxCols][128] k of this pass's columns
+  uint16_t* Fv = Fk + kMaxCols * 128;                          // [kMaxCols][128] v
 
   const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int split = blockIdx.x, head = blockIdx.y;
   const int R = a.ncols * a.grp;
   const KvGeom& g = a.g;
 
-  // ---- queries of this kv head: row rr = column * grp + member (16-byte pieces; rows past R are 0)
-  for (int i = tid; i < MT * 16 * 16; i += 256) {
-    const int rr = i >> 4, d = (i & 15) * 8;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (rr < R) {
-      const int c = rr / a.grp, gi = rr - c * a.grp;
-      v = *reinterpret_cast<const uint4*>(a.Q + ((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d);
+  // ---- queries of this kv head: row rr = column * grp + member; rows past R are 0
+  if (a.qkv) {
+    // pair (d, d + 64) of one query row per thread and pass; all loads are issued before use
+    float x0[MT * 4], x1[MT * 4], cc[MT * 4], sn[MT * 4];
+#pragma unroll
+    for (int it = 0; it < MT * 4; ++it) {
+      const int i = tid + it * 256, rr = i >> 6, d = i & 63;
+      x0[it] = x1[it] = cc[it] = sn[it] = 0.f;
+      if (rr < R) {
+        const int c = rr / a.grp, gi = rr - c * a.grp;
+        const float* src = a.qkv + (size_t)c * a.ystride + (size_t)(head * a.grp + gi) * 128;
+        const float2 cs = *reinterpret_cast<const float2*>(a.rope + ((size_t)(a.len + a.slot0 + c) * 64 + d) * 2);
+        x0[it] = src[d]; x1[it] = src[d + 64]; cc[it] = cs.x; sn[it] = cs.y;
+      }
     }
-    *reinterpret_cast<uint4*>(Qs + rr * kQP + d) = v;
+#pragma unroll
+    for (int it = 0; it < MT * 4; ++it) {
+      const int i = tid + it * 256, rr = i >> 6, d = i & 63;
+      const float a0 = round_bf16(x0[it]), a1 = round_bf16(x1[it]);
+      Qs[rr * kQP + d] = f32_to_bf16(a0 * cc[it] - a1 * sn[it]);
+      Qs[rr * kQP + d + 64] = f32_to_bf16(a1 * cc[it] + a0 * sn[it]);
+    }
+  } else {
+    for (int i = tid; i < MT * 16 * 16; i += 256) {  // 16-byte pieces
+      const int rr = i >> 4, d = (i & 15) * 8;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (rr < R) {
+        const int c = rr / a.grp, gi = rr - c * a.grp;
+        v = *reinterpret_cast<const uint4*>(a.Q + ((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d);
+      }
+      *reinterpret_cast<uint4*>(Qs + rr * kQP + d) = v;
+    }
   }
   for (int i = tid; i < MT * 16; i += 256) {
     s_m[i] = -INFINITY;
     s_l[i] = 0.f;
     s_c[i] = 1.f;
+  }
+  // ---- k, v of this pass's columns that fall into this workgroup's pages: split from the
+  //      projection by all threads at once (round, rotate k), staged in LDS, copied to their slots
+  if (a.qkv) {
+    const int first = a.len + a.slot0;  // position of column 0
+    const int lo = max(first, blockIdx.x * a.pages_per_split * kPT);
+    const int hi = min(a.len + a.n_new, (int)(blockIdx.x + 1) * a.pages_per_split * kPT);
+    for (int i = tid; i < (hi - lo) * 128; i += 256) {
+      const int pos = lo + (i >> 7), d = i & 127, c = pos - first;
+      const float* src = a.qkv + (size_t)c * a.ystride + (size_t)(a.n_q_heads + head) * 128;
+      const float* cs = a.rope + ((size_t)pos * 64 + (d & 63)) * 2;
+      const float x0 = round_bf16(src[d]), x1 = round_bf16(src[d ^ 64]);
+      const float sgn = d < 64 ? -1.f : 1.f;  // channel d pairs with d + 64 (d < 64) or d - 64
+      const uint16_t ko = f32_to_bf16(x0 * cs[0] + sgn * (x1 * cs[1]));
+      const uint16_t vo = f32_to_bf16(src[(size_t)g.n_kv_heads * 128 + d]);
+      Fk[c * 128 + d] = ko;
+      Fv[c * 128 + d] = vo;
+      const size_t so = ((size_t)(pos - a.len) * g.n_kv_heads + head) * 128 + d;
+      a.Kslot[so] = ko;
+      a.Vslot[so] = vo;
+    }
   }
   f32x4 Oacc[MT][2];
 #pragma unroll
@@ -140,10 +195,18 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
       for (int q = 0; q < 8; ++q) *reinterpret_cast<uint64_t*>(krow + 4 * q) = 0ull;
       if (fresh) {
-        const uint16_t* src = a.Knew + ((size_t)(pos - a.len) * g.n_kv_heads + head) * 128 + 32 * j;
+        const int slot = pos - a.len;
+        if (a.qkv && slot >= a.slot0) {  // a column of this pass: staged above
+          const uint16_t* src = Fk + (slot - a.slot0) * 128 + 32 * j;
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-          *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
+          for (int q = 0; q < 8; ++q)
+            *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
+        } else {
+          const uint16_t* src = a.Knew + ((size_t)slot * g.n_kv_heads + head) * 128 + 32 * j;
+#pragma unroll
+          for (int q = 0; q < 8; ++q)
+            *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
+        }
       }
       wk.decode(mk, (FULL && live) ? ~mk : 0u, [&](int pos, uint16_t v) { krow[pos] = v; });
     }
@@ -198,9 +261,16 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
       for (int c = 0; c < 32; ++c) vcol[c * kVP] = 0;
       if (fresh) {
-        const uint16_t* src = a.Vnew + ((size_t)(pos - a.len) * g.n_kv_heads + head) * 128 + 32 * j;
+        const int slot = pos - a.len;
+        if (a.qkv && slot >= a.slot0) {
+          const uint16_t* src = Fv + (slot - a.slot0) * 128 + 32 * j;
 #pragma unroll
-        for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
+          for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
+        } else {
+          const uint16_t* src = a.Vnew + ((size_t)slot * g.n_kv_heads + head) * 128 + 32 * j;
+#pragma unroll
+          for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
+        }
       }
       wvw.decode(mv, (FULL && live) ? ~mv : 0u, [&](int pos, uint16_t v) { vcol[pos * kVP] = v; });
     }
@@ -315,6 +385,8 @@ int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
   a.len = kv->h_len[c.seq];
   a.Q = c.Q; a.ncols = c.ncols; a.n_q_heads = c.n_q_heads; a.grp = c.n_q_heads / g.n_kv_heads;
   a.Knew = c.Knew; a.Vnew = c.Vnew; a.n_new = c.n_new;
+  a.qkv = c.qkv; a.ystride = c.ystride; a.slot0 = c.slot0; a.rope = c.rope;
+  a.Kslot = c.Kslot; a.Vslot = c.Vslot;
   a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
   a.O = c.O;
   const int R = a.ncols * a.grp;

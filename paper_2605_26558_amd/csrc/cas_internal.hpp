@@ -58,6 +58,8 @@ int launch_gemv_draft(cas_ctx*, const cas_wdesc&, const void* spec, const uint16
 int launch_gemv_draft_fused(cas_ctx*, const cas_wdesc&, const void* spec, const uint16_t* x, int batch, float* y,
                             const uint16_t* gain, float eps, int epi, uint16_t* out16);
 int launch_gemm_verify(cas_ctx*, const cas_wdesc&, const void* spec, const void* verif, const uint16_t* X, int ncols, float* Y);
+int launch_gemm_verify_fused(cas_ctx*, const cas_wdesc&, const void* spec, const void* verif, const uint16_t* X,
+                             int ncols, float* Y, int epi, uint16_t* out16);
 int launch_kv_append(cas_ctx*, cas_kv*, int layer, int seq, const uint16_t* K, const uint16_t* V, int n_tok, int pos0);
 int launch_kv_read(cas_ctx*, cas_kv*, int layer, int seq, int pos0, int n_tok, int full, uint16_t* K, uint16_t* V);
 struct AttnCall {
@@ -68,6 +70,12 @@ struct AttnCall {
   const uint16_t* Vnew;
   int n_new;
   uint16_t* O;                 // [ncols][n_q_heads][128]
+  // model path: split of the fp32 qkv projection fused in (see attention.hip); null otherwise
+  const float* qkv = nullptr;
+  int ystride = 0, slot0 = 0;
+  const float* rope = nullptr;
+  uint16_t* Kslot = nullptr;
+  uint16_t* Vslot = nullptr;
 };
 int launch_attention(cas_ctx*, cas_kv*, const AttnCall&);
 // Brackets one kernel launch with HIP events on the context stream when profiling is on.

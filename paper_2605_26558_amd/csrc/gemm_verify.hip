@@ -29,7 +29,9 @@ struct VerifyArgs {
   const uint32_t* lo;
   const uint32_t* pruned;
   const uint16_t* X;  // [ncols][cols]
-  float* Y;           // [ncols][rows]
+  float* Y;           // [ncols][rows] (epilogue 0)
+  int epi;            // 0: Y = W X;  1: h = bf16(h + bf16(W X));  2: act[i] = swiglu(rows 2i, 2i+1)
+  uint16_t* out16;    // h [ncols][rows] (epilogue 1) or act [ncols][rows/2] (epilogue 2)
 };
 
 constexpr int kSlabCols = 2048;
@@ -181,10 +183,30 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
     f32x4 s = *reinterpret_cast<f32x4*>(red + (wv * 64 + lane) * 4);
 #pragma unroll
     for (int w = 1; w < Q; ++w) s += *reinterpret_cast<f32x4*>(red + ((wv + w) * 64 + lane) * 4);
+    if (a.epi == 0) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      int orow = row0 + 4 * mq + e;
-      if (orow < a.rows) a.Y[(size_t)mi * a.rows + orow] = s[e];
+      for (int e = 0; e < 4; ++e) {
+        int orow = row0 + 4 * mq + e;
+        if (orow < a.rows) a.Y[(size_t)mi * a.rows + orow] = s[e];
+      }
+    } else if (a.epi == 1) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        int orow = row0 + 4 * mq + e;
+        if (orow < a.rows) {
+          uint16_t* hp = a.out16 + (size_t)mi * a.rows + orow;
+          *hp = f32_to_bf16(bf16_to_f32(*hp) + round_bf16(s[e]));
+        }
+      }
+    } else {  // rows come in (gate, up) pairs; a lane holds rows 4*mq .. 4*mq+3 = two pairs
+#pragma unroll
+      for (int e = 0; e < 4; e += 2) {
+        int orow = row0 + 4 * mq + e;
+        if (orow + 1 < a.rows) {
+          const float g = round_bf16(s[e]), u = round_bf16(s[e + 1]);
+          a.out16[(size_t)mi * (a.rows >> 1) + (orow >> 1)] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
+        }
+      }
     }
   }
 }
@@ -218,8 +240,15 @@ static int launch_gq(cas_ctx* ctx, const VerifyArgs& a, int t) {
 
 int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const void* verif, const uint16_t* X,
                        int ncols, float* Y) {
+  return launch_gemm_verify_fused(ctx, d, spec, verif, X, ncols, Y, 0, nullptr);
+}
+
+int launch_gemm_verify_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const void* verif,
+                             const uint16_t* X, int ncols, float* Y, int epi, uint16_t* out16) {
   if (d.rows <= 0) return CAS_OK;
+  if (epi == 2 && (d.rows & 1)) return CAS_EINVAL;
   VerifyArgs a;
+  a.epi = epi; a.out16 = out16;
   a.rows = (int)d.rows; a.cols = (int)d.cols; a.bw = d.bw; a.sw = d.sw; a.lw = d.lw; a.pw = d.pw;
   a.ncols = ncols;
   a.bitmap = (const uint32_t*)((const char*)spec + d.off_bitmap);

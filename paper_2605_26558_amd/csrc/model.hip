@@ -57,52 +57,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict
     out[(size_t)c * n + i] = f32_to_bf16(bf16_to_f32(x[i]) * r * bf16_to_f32(g[i]));
 }
 
-// Split the qkv projection: round to bf16, rotate q and k by the position angle (pairs
-// (i, i + d/2) of a head), write q to its buffer and k, v to the in-flight slots.
-__global__ __launch_bounds__(64) void qkv_post_kernel(const float* __restrict__ y, int ystride, int n_q_heads,
-                                                      int n_kv_heads, const float* __restrict__ rope, int pos0,
-                                                      int slot0, uint16_t* __restrict__ q, uint16_t* __restrict__ knew,
-                                                      uint16_t* __restrict__ vnew) {
-  const int c = blockIdx.y, hd = blockIdx.x, i = threadIdx.x;  // head index over q, k, v heads
-  const float* src = y + (size_t)c * ystride + (size_t)hd * 128;
-  const float a = round_bf16(src[i]), b = round_bf16(src[i + 64]);
-  const int kvd = n_kv_heads * 128;
-  if (hd < n_q_heads + n_kv_heads) {
-    const float cs = rope[((size_t)(pos0 + c) * 64 + i) * 2], sn = rope[((size_t)(pos0 + c) * 64 + i) * 2 + 1];
-    const uint16_t o0 = f32_to_bf16(a * cs - b * sn), o1 = f32_to_bf16(b * cs + a * sn);
-    uint16_t* dst = hd < n_q_heads ? q + ((size_t)c * n_q_heads + hd) * 128
-                                   : knew + (size_t)(slot0 + c) * kvd + (size_t)(hd - n_q_heads) * 128;
-    dst[i] = o0;
-    dst[i + 64] = o1;
-  } else {
-    uint16_t* dst = vnew + (size_t)(slot0 + c) * kvd + (size_t)(hd - n_q_heads - n_kv_heads) * 128;
-    dst[i] = f32_to_bf16(a);
-    dst[i + 64] = f32_to_bf16(b);
-  }
-}
 
-// h = bf16(h + bf16(y))
-__global__ __launch_bounds__(256) void resid_add_kernel(uint16_t* __restrict__ h, const float* __restrict__ y,
-                                                        int n, int ystride) {
-  const int c = blockIdx.y;
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < n) {
-    size_t o = (size_t)c * n + i;
-    h[o] = f32_to_bf16(bf16_to_f32(h[o]) + round_bf16(y[(size_t)c * ystride + i]));
-  }
-}
 
-// act = bf16(silu(bf16(gate)) * bf16(up)); gate of unit i at y[2i], up at y[2i+1]
-__global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ y, int ystride,
-                                                     uint16_t* __restrict__ act, int ffn) {
-  const int c = blockIdx.y;
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < ffn) {
-    const float g = round_bf16(y[(size_t)c * ystride + 2 * i]);
-    const float u = round_bf16(y[(size_t)c * ystride + 2 * i + 1]);
-    act[(size_t)c * ffn + i] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
-  }
-}
 
 // token = lowest index among the maxima of a logits row; stage 1: one candidate per slice
 constexpr int kArgmaxSlices = 64;
@@ -169,24 +125,21 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_
       CAS_TRY(launch_gemv_draft_fused(ctx, L.wqkv.desc, L.wqkv.d_spec, m->h, ncols, m->y, L.d_g_attn, c.rms_eps, 0,
                                       nullptr));
     }
-    hipLaunchKernelGGL(qkv_post_kernel, dim3(c.n_q_heads + 2 * c.n_kv_heads, ncols), dim3(64), 0, st, m->y,
-                       qd + 2 * kvd, c.n_q_heads, c.n_kv_heads, m->d_rope, pos0, slot0, m->q, kn, vn);
+    // the attention kernel splits the projection itself: bf16 rounding, rotary embedding of q and
+    // k, and the copy of this pass's k, v into their in-flight slots
     AttnCall ac;
     ac.layer = l; ac.seq = seq; ac.full = full ? 1 : 0;
     ac.Q = m->q; ac.ncols = ncols; ac.n_q_heads = c.n_q_heads;
     ac.Knew = kn; ac.Vnew = vn; ac.n_new = slot0 + ncols; ac.O = m->ao;
+    ac.qkv = m->y; ac.ystride = qd + 2 * kvd; ac.slot0 = slot0; ac.rope = m->d_rope; ac.Kslot = kn; ac.Vslot = vn;
     CAS_TRY(launch_attention(ctx, kv, ac));
     if (full) {
-      CAS_TRY(launch_gemm_verify(ctx, L.wo.desc, L.wo.d_spec, L.wo.d_verif, m->ao, ncols, m->y));
-      hipLaunchKernelGGL(resid_add_kernel, dim3((c.hidden + 255) / 256, ncols), dim3(256), 0, st, m->h, m->y,
-                         c.hidden, c.hidden);
+      // residual adds and SwiGLU ride in the epilogue of the verification GEMM
+      CAS_TRY(launch_gemm_verify_fused(ctx, L.wo.desc, L.wo.d_spec, L.wo.d_verif, m->ao, ncols, nullptr, 1, m->h));
       hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, L.d_g_ffn, m->xn, c.hidden, c.rms_eps);
-      CAS_TRY(launch_gemm_verify(ctx, L.wgu.desc, L.wgu.d_spec, L.wgu.d_verif, m->xn, ncols, m->y));
-      hipLaunchKernelGGL(swiglu_kernel, dim3((c.ffn + 255) / 256, ncols), dim3(256), 0, st, m->y, 2 * c.ffn, m->act,
-                         c.ffn);
-      CAS_TRY(launch_gemm_verify(ctx, L.wd.desc, L.wd.d_spec, L.wd.d_verif, m->act, ncols, m->y));
-      hipLaunchKernelGGL(resid_add_kernel, dim3((c.hidden + 255) / 256, ncols), dim3(256), 0, st, m->h, m->y,
-                         c.hidden, c.hidden);
+      CAS_TRY(launch_gemm_verify_fused(ctx, L.wgu.desc, L.wgu.d_spec, L.wgu.d_verif, m->xn, ncols, nullptr, 2,
+                                       m->act));
+      CAS_TRY(launch_gemm_verify_fused(ctx, L.wd.desc, L.wd.d_spec, L.wd.d_verif, m->act, ncols, nullptr, 1, m->h));
     } else {
       CAS_TRY(launch_gemv_draft_fused(ctx, L.wo.desc, L.wo.d_spec, m->ao, ncols, nullptr, nullptr, 0.f, 1, m->h));
       CAS_TRY(launch_gemv_draft_fused(ctx, L.wgu.desc, L.wgu.d_spec, m->h, ncols, nullptr, L.d_g_ffn, c.rms_eps, 2,
