@@ -317,37 +317,48 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 }
 
 // Combine the splits: o = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, rounded to bf16.
-// One workgroup per (query row, kv head); the split weights are computed once into LDS, then
-// every thread sums its channel over the splits with independent loads.
-__global__ __launch_bounds__(128) void attn_merge_kernel(AttnArgs a) {
-  extern __shared__ float sw[];  // [nsplit] weights
-  __shared__ float red[4];
-  const int rr = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
+// One workgroup per (query row, kv head): the split weights are computed once into LDS, then
+// thread (channel d, part p) sums the splits s = p, p + 4, ... with independent loads and the
+// four parts are added in part order (a fixed order: the result does not depend on timing).
+__global__ __launch_bounds__(512) void attn_merge_kernel(AttnArgs a) {
+  extern __shared__ float sw[];  // [nsplit] weights, then [4][128] partial sums
+  __shared__ float red[16];
+  const int rr = blockIdx.x, head = blockIdx.y, tid = threadIdx.x, d = tid & 127, part = tid >> 7;
   const int R = a.ncols * a.grp;
   const size_t sstride = (size_t)a.g.n_kv_heads * R * kPartStride;
   const float* base = a.part + ((size_t)head * R + rr) * kPartStride;
   float mx = -INFINITY;
-  for (int s = d; s < a.nsplit; s += 128) mx = fmaxf(mx, base[s * sstride + 128]);
+  for (int s = tid; s < a.nsplit; s += 512) mx = fmaxf(mx, base[s * sstride + 128]);
   mx = wave_max(mx);
-  if ((d & 63) == 0) red[d >> 6] = mx;
+  if ((tid & 63) == 0) red[tid >> 6] = mx;
   __syncthreads();
-  const float M = fmaxf(red[0], red[1]);
+  float M = red[0];
+#pragma unroll
+  for (int w = 1; w < 8; ++w) M = fmaxf(M, red[w]);
   float den = 0.f;
-  for (int s = d; s < a.nsplit; s += 128) {
+  for (int s = tid; s < a.nsplit; s += 512) {
     float m = base[s * sstride + 128];
     float w = (m == -INFINITY) ? 0.f : __expf(m - M);
     sw[s] = w;
     den += w * base[s * sstride + 129];
   }
   den = wave_sum(den);
-  if ((d & 63) == 0) red[2 + (d >> 6)] = den;
+  if ((tid & 63) == 0) red[8 + (tid >> 6)] = den;
   __syncthreads();
-  den = red[2] + red[3];
+  den = 0.f;
+#pragma unroll
+  for (int w = 0; w < 8; ++w) den += red[8 + w];
   float num = 0.f;
 #pragma unroll 8
-  for (int s = 0; s < a.nsplit; ++s) num += sw[s] * base[s * sstride + d];
-  const int c = rr / a.grp, gi = rr - c * a.grp;
-  a.O[((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d] = f32_to_bf16(num / den);
+  for (int s = part; s < a.nsplit; s += 4) num += sw[s] * base[s * sstride + d];
+  float* ps = sw + a.nsplit;
+  ps[part * 128 + d] = num;
+  __syncthreads();
+  if (part == 0) {
+    num = ((ps[d] + ps[128 + d]) + ps[256 + d]) + ps[384 + d];
+    const int c = rr / a.grp, gi = rr - c * a.grp;
+    a.O[((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d] = f32_to_bf16(num / den);
+  }
 }
 
 template <int MT, bool FULL>
@@ -415,7 +426,7 @@ int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
   }
   }
   if (rc != CAS_OK) return rc;
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(R, g.n_kv_heads), dim3(128), sizeof(float) * a.nsplit, ctx->stream, a);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(R, g.n_kv_heads), dim3(512), sizeof(float) * (a.nsplit + 512), ctx->stream, a);
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;
 }
