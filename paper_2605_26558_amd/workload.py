@@ -120,9 +120,14 @@ class ModelRoundWorkload:
         dims = {"wqkv": (shape.q_dim + 2 * shape.kv_dim, shape.hidden), "wo": (shape.hidden, shape.q_dim),
                 "wgu": (2 * shape.ffn, shape.hidden), "wd": (shape.hidden, shape.ffn)}
 
+        self.dense = []  # plain bf16 copies, only for the vendor-GEMV context figure
+
         def enc(r, c):
             act = torch.exp(0.5 * torch.randn(c, device="cuda", generator=gen))
-            return B.cas_encode_weight(ctx, _random_weight(torch, r, c, gen), args.keep, args.trunc, act)
+            w = _random_weight(torch, r, c, gen)
+            if getattr(args, "bf16_context", True):
+                self.dense.append(w.view(torch.bfloat16))
+            return B.cas_encode_weight(ctx, w, args.keep, args.trunc, act)
 
         def gain():
             return (1.0 + 0.1 * torch.randn(shape.hidden, device="cuda", generator=gen)).to(torch.bfloat16).view(
@@ -258,9 +263,66 @@ class ModelRoundWorkload:
                 "traffic_source": "profiles/pmc_gemv_draft_gemm_verify_28672x4096.md (counter ratio applied "
                                   "to this run's bytes per launch)"}
 
+    def _time_passes(self):
+        """Wall time of one draft pass, one verification pass (k+1 columns) and one plain decode
+        step (verification with a single column) of the whole model, by HIP events."""
+        torch, B, ctx = self.torch, self.B, self.ctx
+        tok = torch.ones(self.k + 1, dtype=torch.int32, device="cuda")
+        out = torch.empty(self.k + 1, dtype=torch.int32, device="cuda")
+
+        def timed(fn, reps=3):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        t_draft = timed(lambda: B.cas_draft_step(ctx, self.model, self.kv, 0, tok[:1], 0, out[:1]))
+        t_verify = timed(lambda: B.cas_verify_step(ctx, self.model, self.kv, 0, tok, self.k, out))
+        t_plain = timed(lambda: B.cas_verify_step(ctx, self.model, self.kv, 0, tok[:1], 0, out[:1]))
+        return t_draft, t_verify, t_plain
+
     def extra(self, ms_per_step):
+        t_draft, t_verify, t_plain = self._time_passes()
+        k = self.k
+        # context: the same linear layers as plain bf16 through the vendor GEMV (torch.mv), one pass
+        t_bf16 = None
+        if self.dense:
+            torch = self.torch
+            xs = {c: torch.randn(c, device="cuda").to(torch.bfloat16) for c in {w.shape[1] for w in self.dense}}
+
+            def chain():
+                for w in self.dense:
+                    torch.mv(w, xs[w.shape[1]])
+            chain()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                chain()
+            e1.record()
+            torch.cuda.synchronize()
+            t_bf16 = e0.elapsed_time(e1) / 3
+        # Speed model of Sec. 2.2: a round costs k t_draft + t_verify and yields accepted + 1 tokens.
+        # The acceptance of a random-init model is ~0, so the table below uses an ASSUMED per-token
+        # acceptance probability alpha (synthetic; the paper's acceptance table did not survive).
+        synth_tps = {}
+        for alpha in (0.0, 0.6, 0.8, 0.9, 1.0):
+            exp_n = float(k) if alpha == 1.0 else sum(alpha ** i for i in range(1, k + 1))
+            synth_tps[f"alpha={alpha}"] = (exp_n + 1.0) / ((k * t_draft + t_verify) * 1e-3)
         out = {"tokens_per_s": (self.accepted + self.rounds) / max(self.rounds, 1) / (ms_per_step * 1e-3),
                "accepted_per_round": self.accepted / max(self.rounds, 1),
+               "draft_pass_ms": t_draft, "verify_pass_ms": t_verify, "plain_decode_step_ms": t_plain,
+               "draft_pass_GBps": (self.draft_w + self.draft_kv) / (t_draft * 1e-3) / 1e9,
+               "verify_pass_GBps": (self.verify_w + self.verify_kv) / (t_verify * 1e-3) / 1e9,
+               "plain_decode_tokens_per_s": 1e3 / t_plain,
+               "context_vendor_bf16_gemv_pass_ms": t_bf16,
+               "context_vendor_bf16_gemv_GBps": None if t_bf16 is None else 2.0 * self.values / (t_bf16 * 1e-3) / 1e9,
+               "tokens_per_s_at_assumed_acceptance": synth_tps,
                "kernels": {}}
         for name, (n, ms, by) in self.prof.items():
             if n:
