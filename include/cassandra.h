@@ -283,6 +283,13 @@ int cas_prefill(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const int32
 int cas_accept(const int32_t* h_draft, const int32_t* h_target, int k, int32_t* n_accepted,
                int32_t* h_out);
 
+/* Rejection-sampling acceptance (Eq. 1).  Host only.  h_p[i], h_q[i]: probability of the
+ * (i+1)-th drafted token under the target and the draft model (q > 0); h_r[i]: uniform random
+ * numbers in [0, 1) supplied by the caller.  n_accepted = min({i-1 : 1 <= i <= gamma,
+ * r_i > p_i / q_i} U {gamma}); the ratio is formed in double precision. */
+int cas_accept_sampling(const double* h_p, const double* h_q, const double* h_r, int gamma,
+                        int32_t* n_accepted);
+
 #ifdef __cplusplus
 }
 #endif

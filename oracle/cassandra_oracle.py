@@ -458,6 +458,18 @@ def accept_greedy(draft, target):
     return n, [int(x) for x in draft[:n]] + [int(target[n])]
 
 
+def accept_sampling(p_target, q_draft, r):
+    """Rejection-sampling acceptance (Eq. 1): n = min({i-1 : 1 <= i <= gamma, r_i > p_i/q_i} U {gamma}),
+    with p_i, q_i the target / draft probability of the i-th drafted token and r_i uniform in
+    [0, 1).  Inputs are the three length-gamma sequences; returns n."""
+    gamma = len(r)
+    cands = [gamma]
+    for i in range(1, gamma + 1):
+        if float(r[i - 1]) > float(p_target[i - 1]) / float(q_draft[i - 1]):
+            cands.append(i - 1)
+    return min(cands)
+
+
 def prefill(model: OracleModel, prompt):
     """Fill the cache for prompt[:-1] with the target model; prompt[-1] stays pending."""
     if len(prompt) > 1:

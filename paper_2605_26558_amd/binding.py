@@ -105,6 +105,8 @@ _SIGNATURES = {
     "cas_spec_round": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int,
                                  C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "cas_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int]),
+    "cas_accept_sampling": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int,
+                                      C.POINTER(C.c_int32)]),
     "cas_accept": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32),
                              C.POINTER(C.c_int32)]),
 }
@@ -250,6 +252,16 @@ def cas_gemm_verify(ctx: Context, ew: EncodedWeight, X, out=None):
     ctx._check(_lib().cas_gemm_verify(ctx.h, C.byref(ew.desc), _ptr(ew.spec), _ptr(ew.verif), _ptr(X), X.shape[0],
                                       _ptr(out)), "cas_gemm_verify")
     return out
+
+
+def cas_accept_sampling(p, q, r):
+    g = len(r)
+    arr = lambda v: (C.c_double * max(g, 1))(*[float(x) for x in v])
+    n = C.c_int32()
+    rc = _lib().cas_accept_sampling(arr(p), arr(q), arr(r), g, C.byref(n))
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_accept_sampling")
+    return n.value
 
 
 def cas_accept(draft, target):

@@ -258,4 +258,18 @@ int cas_accept(const int32_t* h_draft, const int32_t* h_target, int k, int32_t* 
   return CAS_OK;
 }
 
+int cas_accept_sampling(const double* h_p, const double* h_q, const double* h_r, int gamma, int32_t* n_accepted) {
+  if (gamma < 0 || !n_accepted || (gamma > 0 && (!h_p || !h_q || !h_r))) return CAS_EINVAL;
+  int n = gamma;
+  for (int i = 1; i <= gamma; ++i) {
+    if (!(h_q[i - 1] > 0.0)) return CAS_EINVAL;
+    if (h_r[i - 1] > h_p[i - 1] / h_q[i - 1]) {
+      n = i - 1;
+      break;
+    }
+  }
+  *n_accepted = n;
+  return CAS_OK;
+}
+
 }  // extern "C"

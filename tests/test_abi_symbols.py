@@ -34,6 +34,13 @@ def test_host_only_calls_work_without_a_gpu():
     assert d.spec_bytes % 256 == 0 and d.off_spec % 256 == 0 and d.off_pruned % 256 == 0
     assert B.cas_accept([1, 2, 3], [1, 2, 9, 4]) == (2, [1, 2, 9])
     assert B.cas_accept([], [7]) == (0, [7])
+    import itertools
+    from oracle import cassandra_oracle as O
+    for gamma in range(0, 4):
+        for ratios in itertools.product([0.0, 0.3, 1.0, 2.5], repeat=gamma):
+            for rs in itertools.product([0.0, 0.29, 0.31, 0.99], repeat=gamma):
+                p, q = [x * 0.4 for x in ratios], [0.4] * gamma
+                assert B.cas_accept_sampling(p, q, rs) == O.accept_sampling(p, q, rs)
     import pytest
     with pytest.raises(B.CasError):
         B.cas_weight_desc(8, 8, 600, 9)

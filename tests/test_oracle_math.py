@@ -152,3 +152,20 @@ def test_cache_is_lossless_and_draft_cache_is_the_prefix():
     dk, _ = m._cache_kv(0, draft=True)
     assert (((dk ^ ck) < 16) | (dk == 0)).all()
     assert ((dk != 0).sum(axis=-1) <= 77).all()
+
+
+def test_accept_sampling_against_definition_brute_force():
+    """Eq. 1 on every combination of a small grid of ratios and random numbers: the result is the
+    index of the first rejected draft, or gamma; p = q accepts everything; p = 0 rejects at once."""
+    grid_ratio = [0.0, 0.3, 1.0, 2.5]
+    grid_r = [0.0, 0.29, 0.31, 0.99]
+    for gamma in range(0, 4):
+        for ratios in itertools.product(grid_ratio, repeat=gamma):
+            for rs in itertools.product(grid_r, repeat=gamma):
+                q = [0.4] * gamma
+                p = [x * 0.4 for x in ratios]
+                n = O.accept_sampling(p, q, rs)
+                first_rej = next((i for i in range(gamma) if rs[i] > ratios[i]), gamma)
+                assert n == first_rej
+    assert O.accept_sampling([0.2, 0.5], [0.2, 0.5], [0.999, 0.999]) == 2
+    assert O.accept_sampling([0.0, 0.5], [0.2, 0.5], [0.001, 0.0]) == 0
