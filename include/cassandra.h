@@ -192,7 +192,8 @@ int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_to
  * full = 1: cache rebuilt exactly from both pools (verification pass).
  * d_Q: bf16 [ncols][n_q_heads][head_dim] (after the rotary embedding);
  * d_Knew, d_Vnew: bf16 [n_new][n_kv_heads][head_dim], uncompressed, ncols <= n_new <= 64;
- * d_O: bf16 [ncols][n_q_heads][head_dim].  ncols * n_q_heads / n_kv_heads <= 48.
+ * d_O: bf16 [ncols][n_q_heads][head_dim].  ncols <= 16 and ncols * n_q_heads / n_kv_heads <= 80
+ * (48 when full = 0).
  * Uses the context workspace for the per-split partial results (CAS_ENOMEM if too small:
  * splits * n_kv_heads * ncols * group * 132 floats, one split per 64 positions).
  * A column's value depends only on the positions it sees: not on ncols, and not on whether an

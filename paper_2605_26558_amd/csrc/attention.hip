@@ -402,7 +402,7 @@ int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
   a.O = c.O;
   const int R = a.ncols * a.grp;
   const int MT = (R + 15) / 16;
-  if (MT < 1 || MT > 3 || c.n_new > kPT || c.n_new < c.ncols) return CAS_EINVAL;
+  if (MT < 1 || MT > (c.full ? 5 : 3) || c.n_new > kPT || c.n_new < c.ncols || c.ncols > kMaxCols) return CAS_EINVAL;
   const int pages = (a.len + a.n_new + kPT - 1) / kPT;
   if (pages > g.max_pages_per_seq) return CAS_ENOMEM;
   a.pages_per_split = kPagesPerSplit;  // fixed: a query's value must not depend on the length
@@ -418,8 +418,11 @@ int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
     const double bytes = 2.0 * g.n_kv_heads * (per_tok * a.len + 256.0 * a.n_new);
     ProfScope prof(ctx, c.full ? PROF_ATTN_VERIFY : PROF_ATTN_DRAFT, bytes);
   if (c.full) {
-    rc = MT == 1 ? launch_mt<1, true>(ctx, a, grid) : MT == 2 ? launch_mt<2, true>(ctx, a, grid)
-                                                               : launch_mt<3, true>(ctx, a, grid);
+    rc = MT == 1   ? launch_mt<1, true>(ctx, a, grid)
+         : MT == 2 ? launch_mt<2, true>(ctx, a, grid)
+         : MT == 3 ? launch_mt<3, true>(ctx, a, grid)
+         : MT == 4 ? launch_mt<4, true>(ctx, a, grid)
+                   : launch_mt<5, true>(ctx, a, grid);
   } else {
     rc = MT == 1 ? launch_mt<1, false>(ctx, a, grid) : MT == 2 ? launch_mt<2, false>(ctx, a, grid)
                                                                 : launch_mt<3, false>(ctx, a, grid);

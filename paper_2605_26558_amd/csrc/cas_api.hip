@@ -240,7 +240,7 @@ int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const 
   if (ncols < 1 || n_new < ncols || n_new > 64 || n_q_heads < kv->desc.n_kv_heads ||
       n_q_heads % kv->desc.n_kv_heads != 0)
     return CAS_EINVAL;
-  if (ncols * (n_q_heads / kv->desc.n_kv_heads) > 48) return CAS_EINVAL;
+  if (ncols * (n_q_heads / kv->desc.n_kv_heads) > (full ? 80 : 48) || ncols > 16) return CAS_EINVAL;
   cas::AttnCall c;
   c.layer = layer; c.seq = seq; c.full = full ? 1 : 0;
   c.Q = d_Q; c.ncols = ncols; c.n_q_heads = n_q_heads;

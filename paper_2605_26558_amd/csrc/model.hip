@@ -200,7 +200,7 @@ static int check_cfg(const cas_model_cfg* c) {
     return CAS_EINVAL;
   if (c->head_dim != 128) return CAS_ENOTSUP;
   if (c->n_q_heads % c->n_kv_heads != 0 || c->max_cols < 1 || c->max_cols > 16 || c->max_pos < 1) return CAS_EINVAL;
-  if (c->max_cols * (c->n_q_heads / c->n_kv_heads) > 48) return CAS_EINVAL;
+  if (c->max_cols * (c->n_q_heads / c->n_kv_heads) > 80 || c->n_q_heads / c->n_kv_heads > 48) return CAS_EINVAL;
   return CAS_OK;
 }
 

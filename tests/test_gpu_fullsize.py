@@ -17,7 +17,8 @@ def env():
     return torch, B, B.Context()
 
 
-SHAPES = [(28672, 4096), (4096, 14336), (6144, 4096), (128256, 4096)]
+SHAPES = [(28672, 4096), (4096, 14336), (6144, 4096), (128256, 4096),
+          (8192, 28672), (10240, 8192)]     # the last two: Llama-3-70B down and qkv projections
 
 
 @pytest.mark.parametrize("rows,cols", SHAPES)

@@ -138,3 +138,29 @@ def test_attention_matches_oracle(env, len_cache, ncols, n_new, full):
             o1 = _host(B.cas_attention(ctx, kv, layer, seq, True, _dev(torch, Q[c:c + 1]),
                                        _dev(torch, Kn[:vis]), _dev(torch, Vn[:vis])))
             np.testing.assert_array_equal(o1[0], out[c])
+
+
+def test_attention_llama70b_head_grouping(env):
+    """64 query heads on 8 kv heads (group of 8), 9 verification columns = 72 query rows per
+    kv head, and the matching one-column draft call."""
+    torch, B, ctx = env
+    nq, nkv = 64, 8
+    kv = B.KVCache(ctx, 1, nkv, n_pages=3, max_seqs=1, max_pages_per_seq=3)
+    L = 100
+    Kh = synth.kv_tensor(L, nkv, 128, seed=13)
+    Vh = synth.kv_tensor(L, nkv, 128, seed=14, outlier_channels=0)
+    B.cas_kv_append(ctx, kv, 0, 0, _dev(torch, Kh), _dev(torch, Vh))
+    B.cas_kv_set_len(kv, 0, L)
+    pk = O.encode_kv(Kh.reshape(-1, 128), 600, 4); pv = O.encode_kv(Vh.reshape(-1, 128), 600, 4)
+    for ncols, full in ((9, True), (1, False)):
+        Q = synth.normal_bf16((ncols, nq, 128), 0.5, seed=15)
+        Kn = synth.kv_tensor(ncols, nkv, 128, seed=16)
+        Vn = synth.kv_tensor(ncols, nkv, 128, seed=17, outlier_channels=0)
+        out = _host(B.cas_attention(ctx, kv, 0, 0, full, _dev(torch, Q), _dev(torch, Kn), _dev(torch, Vn)))
+        dec = O.decode_full if full else O.decode_draft
+        Kc = dec(pk).reshape(L, nkv, 128); Vc = dec(pv).reshape(L, nkv, 128)
+        ref = _ref_attention(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv)
+        reff = O.bf16_to_f64(ref)
+        err = np.abs(O.bf16_to_f64(out) - reff)
+        tol = _attn_tol(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv, reff)
+        assert (err <= tol).all(), float((err / tol).max())
