@@ -7,14 +7,15 @@
 // of a query therefore depends only on the tokens it sees, not on whether they are already
 // committed, nor on the number of columns or the total length.
 //
-// One workgroup handles one kv head and one split of the sequence, page by page:
+// One workgroup handles one kv head and one page (64 positions) of the sequence:
 //   1. thread (token r, word j) decodes its 32 channels of K into a 64 x 128 bf16 tile in LDS;
 //   2. each wave multiplies its 16 tokens with the query rows (grouped-query: 4 query heads x
 //      columns share the kv head) by 16x16x16 bf16 MFMA and writes the scaled scores to LDS;
-//   3. online softmax per query row (running max / sum), probabilities split into a bf16
-//      head and a bf16 remainder so the second product keeps 16 mantissa bits;
-//   4. the V tile is decoded transposed and P V accumulates in fp32 MFMA registers.
-// Partial (max, sum, output) of every split go to the workspace; a merge kernel combines them.
+//   3. softmax numerators of the page per query row (row max / sum kept for the merge),
+//      probabilities split into a bf16 head and a bf16 remainder so the second product keeps
+//      16 mantissa bits;
+//   4. the V tile is decoded transposed and P V is formed in fp32 MFMA registers.
+// Partial (max, sum, output) of every page go to the workspace; a merge kernel combines them.
 #include "cas_device.hpp"
 #include "cas_internal.hpp"
 
@@ -63,7 +64,7 @@ constexpr int kKVTile = kPT * kKP > kVR * kVP ? kPT * kKP : kVR * kVP;  // K and
 template <int MT>
 constexpr size_t attn_lds_bytes() {
   return sizeof(uint16_t) * (MT * 16 * kQP + kKVTile + 2 * MT * 16 * kPP + 2 * kMaxCols * 128) +
-         sizeof(float) * (MT * 16 * kSP + 3 * MT * 16);
+         sizeof(float) * (MT * 16 * kSP + 2 * MT * 16);
 }
 
 template <int MT, bool FULL, int T>
@@ -75,18 +76,51 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
   uint16_t* Ph = Kt + kKVTile;                // [MT*16][kPP]
   uint16_t* Pl = Ph + MT * 16 * kPP;          // [MT*16][kPP]
   float* S = reinterpret_cast<float*>(Pl + MT * 16 * kPP);  // [MT*16][kSP]
-  float* s_m = S + MT * 16 * kSP;             // running max per row
-  float* s_l = s_m + MT * 16;                 // running sum per row
-  float* s_c = s_l + MT * 16;                 // rescale factor of the current page
-  uint16_t* Fk = reinterpret_cast<uint16_t*>(s_c + MT * 16);  // [kMaxCols][128] k of this pass's columns
-  uint16_t* Fv = Fk + kMaxCols * 128;                          // [kMaxCols][128] v
+  float* s_m = S + MT * 16 * kSP;             // row maximum
+  float* s_l = s_m + MT * 16;                 // row sum of exponentials
+  uint16_t* Fk = reinterpret_cast<uint16_t*>(s_l + MT * 16);      // [kMaxCols][128] k of this pass's columns
+  uint16_t* Fv = Fk + kMaxCols * 128;                              // [kMaxCols][128] v
 
   const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int split = blockIdx.x, head = blockIdx.y;
+  const int pg = blockIdx.x, head = blockIdx.y;  // one page (64 positions) per workgroup
   const int R = a.ncols * a.grp;
   const KvGeom& g = a.g;
+  const int r = tid >> 2, j = tid & 3;           // decode role: token r of the page, word j
+  const int mi = lane & 15, mq = lane >> 4;      // MFMA role
+  uint16_t* krow = Kt + r * kKP + j * kKG + 4;
+  uint16_t* vcol = Vt + (33 * j + 1) * kVP + r;
 
-  // ---- queries of this kv head: row rr = column * grp + member; rows past R are 0
+  const int total = a.len + a.n_new;             // committed + in-flight positions
+  const int tok0 = pg * kPT;
+  const int ntok = min(kPT, total - tok0);
+  const int pos = tok0 + r;                      // position of this thread's token
+  const bool live = pos < a.len;                 // committed: decode from the cache
+  const bool fresh = !live && pos < total;       // in flight: uncompressed vector
+  const int page = a.page_row[pg];
+  const size_t tk = (((size_t)a.layer * g.n_pages + page) * 2 + 0) * g.n_kv_heads + head;
+  const size_t tv = tk + g.n_kv_heads;
+  const uint32_t* ks = a.spec_pool + tk * g.tile_spec_words;
+  const uint32_t* vs = a.spec_pool + tv * g.tile_spec_words;
+  const uint32_t* kvf = a.verif_pool + tk * g.tile_verif_words;
+  const uint32_t* vvf = a.verif_pool + tv * g.tile_verif_words;
+
+  // ---- 0. bitmap words and stream windows of K and V for this thread's (token, word): issued
+  //         first, so they are in flight while the queries are staged
+  const uint32_t mk = live ? ks[r * 4 + j] : 0u;
+  const uint32_t mv = live ? vs[r * 4 + j] : 0u;
+  WordWindows<T, FULL> wk, wvw;
+  {
+    int cnt = __popc(mk);
+    int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
+    uint32_t p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
+    wk.load(p, 32u * j - p, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw);
+    cnt = __popc(mv);
+    b0 = quad_dpp<0x00>(cnt); b1 = quad_dpp<0x55>(cnt); b2 = quad_dpp<0xAA>(cnt);
+    p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
+    wvw.load(p, 32u * j - p, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw);
+  }
+
+  // ---- 1. queries of this kv head: row rr = column * grp + member; rows past R are 0
   if (a.qkv) {
     // pair (d, d + 64) of one query row per thread and pass; all loads are issued before use
     float x0[MT * 4], x1[MT * 4], cc[MT * 4], sn[MT * 4];
@@ -108,6 +142,24 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
       Qs[rr * kQP + d] = f32_to_bf16(a0 * cc[it] - a1 * sn[it]);
       Qs[rr * kQP + d + 64] = f32_to_bf16(a1 * cc[it] + a0 * sn[it]);
     }
+    // k, v of this pass's columns that fall into this page: split from the projection by all
+    // threads at once (round, rotate k), staged in LDS, copied to their in-flight slots
+    const int first = a.len + a.slot0;  // position of column 0
+    const int lo = max(first, tok0), hi = min(total, tok0 + kPT);
+    for (int i = tid; i < (hi - lo) * 128; i += 256) {
+      const int fpos = lo + (i >> 7), d = i & 127, c = fpos - first;
+      const float* src = a.qkv + (size_t)c * a.ystride + (size_t)(a.n_q_heads + head) * 128;
+      const float* cs = a.rope + ((size_t)fpos * 64 + (d & 63)) * 2;
+      const float x0k = round_bf16(src[d]), x1k = round_bf16(src[d ^ 64]);
+      const float sgn = d < 64 ? -1.f : 1.f;  // channel d pairs with d + 64 (d < 64) or d - 64
+      const uint16_t ko = f32_to_bf16(x0k * cs[0] + sgn * (x1k * cs[1]));
+      const uint16_t vo = f32_to_bf16(src[(size_t)g.n_kv_heads * 128 + d]);
+      Fk[c * 128 + d] = ko;
+      Fv[c * 128 + d] = vo;
+      const size_t so = ((size_t)(fpos - a.len) * g.n_kv_heads + head) * 128 + d;
+      a.Kslot[so] = ko;
+      a.Vslot[so] = vo;
+    }
   } else {
     for (int i = tid; i < MT * 16 * 16; i += 256) {  // 16-byte pieces
       const int rr = i >> 4, d = (i & 15) * 8;
@@ -119,197 +171,102 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
       *reinterpret_cast<uint4*>(Qs + rr * kQP + d) = v;
     }
   }
-  for (int i = tid; i < MT * 16; i += 256) {
-    s_m[i] = -INFINITY;
-    s_l[i] = 0.f;
-    s_c[i] = 1.f;
-  }
-  // ---- k, v of this pass's columns that fall into this workgroup's pages: split from the
-  //      projection by all threads at once (round, rotate k), staged in LDS, copied to their slots
-  if (a.qkv) {
-    const int first = a.len + a.slot0;  // position of column 0
-    const int lo = max(first, blockIdx.x * a.pages_per_split * kPT);
-    const int hi = min(a.len + a.n_new, (int)(blockIdx.x + 1) * a.pages_per_split * kPT);
-    for (int i = tid; i < (hi - lo) * 128; i += 256) {
-      const int pos = lo + (i >> 7), d = i & 127, c = pos - first;
-      const float* src = a.qkv + (size_t)c * a.ystride + (size_t)(a.n_q_heads + head) * 128;
-      const float* cs = a.rope + ((size_t)pos * 64 + (d & 63)) * 2;
-      const float x0 = round_bf16(src[d]), x1 = round_bf16(src[d ^ 64]);
-      const float sgn = d < 64 ? -1.f : 1.f;  // channel d pairs with d + 64 (d < 64) or d - 64
-      const uint16_t ko = f32_to_bf16(x0 * cs[0] + sgn * (x1 * cs[1]));
-      const uint16_t vo = f32_to_bf16(src[(size_t)g.n_kv_heads * 128 + d]);
-      Fk[c * 128 + d] = ko;
-      Fv[c * 128 + d] = vo;
-      const size_t so = ((size_t)(pos - a.len) * g.n_kv_heads + head) * 128 + d;
-      a.Kslot[so] = ko;
-      a.Vslot[so] = vo;
-    }
-  }
-  f32x4 Oacc[MT][2];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    Oacc[mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-    Oacc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
   __syncthreads();
 
-  const int r = tid >> 2, j = tid & 3;           // decode role: token r of the page, word j
-  const int mi = lane & 15, mq = lane >> 4;      // MFMA role
-  uint16_t* krow = Kt + r * kKP + j * kKG + 4;
-  uint16_t* vcol = Vt + (33 * j + 1) * kVP + r;
-
-  const int page_lo = split * a.pages_per_split;
-  const int total = a.len + a.n_new;             // committed + in-flight positions
-  const int page_hi = min((total + kPT - 1) / kPT, page_lo + a.pages_per_split);
-
-  for (int pg = page_lo; pg < page_hi; ++pg) {
-    const int tok0 = pg * kPT;
-    const int ntok = min(kPT, total - tok0);
-    const int pos = tok0 + r;                      // position of this thread's token
-    const bool live = pos < a.len;                 // committed: decode from the cache
-    const bool fresh = !live && pos < total;       // in flight: copy the uncompressed vector
-    const int page = a.page_row[pg];
-    const size_t tk = (((size_t)a.layer * g.n_pages + page) * 2 + 0) * g.n_kv_heads + head;
-    const size_t tv = tk + g.n_kv_heads;
-    const uint32_t* ks = a.spec_pool + tk * g.tile_spec_words;
-    const uint32_t* vs = a.spec_pool + tv * g.tile_spec_words;
-    const uint32_t* kvf = a.verif_pool + tk * g.tile_verif_words;
-    const uint32_t* vvf = a.verif_pool + tv * g.tile_verif_words;
-    // ---- 0. bitmap words and stream windows of K and V for this thread's (token, word): all
-    //         loads are issued up front so the V loads fly while K is decoded and scored
-    const uint32_t mk = live ? ks[r * 4 + j] : 0u;
-    const uint32_t mv = live ? vs[r * 4 + j] : 0u;
-    WordWindows<T, FULL> wk, wvw;
-    {
-      int cnt = __popc(mk);
-      int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
-      uint32_t p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
-      wk.load(p, 32u * j - p, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw);
-      cnt = __popc(mv);
-      b0 = quad_dpp<0x00>(cnt); b1 = quad_dpp<0x55>(cnt); b2 = quad_dpp<0xAA>(cnt);
-      p = (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
-      wvw.load(p, 32u * j - p, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw);
+  // ---- 2. K tile: this thread's 32 channels of its token
+  {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) *reinterpret_cast<uint64_t*>(krow + 4 * q) = 0ull;
+    if (fresh) {
+      const int slot = pos - a.len;
+      const uint16_t* src = (a.qkv && slot >= a.slot0)
+                                ? Fk + (slot - a.slot0) * 128 + 32 * j
+                                : a.Knew + ((size_t)slot * g.n_kv_heads + head) * 128 + 32 * j;
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
     }
-    // ---- 1. K tile
-    {
-#pragma unroll
-      for (int q = 0; q < 8; ++q) *reinterpret_cast<uint64_t*>(krow + 4 * q) = 0ull;
-      if (fresh) {
-        const int slot = pos - a.len;
-        if (a.qkv && slot >= a.slot0) {  // a column of this pass: staged above
-          const uint16_t* src = Fk + (slot - a.slot0) * 128 + 32 * j;
-#pragma unroll
-          for (int q = 0; q < 8; ++q)
-            *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
-        } else {
-          const uint16_t* src = a.Knew + ((size_t)slot * g.n_kv_heads + head) * 128 + 32 * j;
-#pragma unroll
-          for (int q = 0; q < 8; ++q)
-            *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
-        }
-      }
-      wk.decode(mk, (FULL && live) ? ~mk : 0u, [&](int pos, uint16_t v) { krow[pos] = v; });
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    // ---- 2. scores of this wave's 16 tokens against all query rows
-    {
-      const uint16_t* b_base = Kt + (16 * wv + mi) * kKP + 4 + 4 * mq;
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        f32x4 C = {0.f, 0.f, 0.f, 0.f};
-        const uint16_t* a_base = Qs + (mt * 16 + mi) * kQP + 4 * mq;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          bf16x4 av = *reinterpret_cast<const bf16x4*>(a_base + kk * 16);
-          bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + (kk >> 1) * kKG + (kk & 1) * 16);
-          C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, bv, C, 0, 0, 0);
-        }
-        const int t = 16 * wv + mi;  // token of this lane's score column
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int rr = mt * 16 + 4 * mq + e;
-          // column c sees positions 0 .. len + n_new - ncols + c
-          const int c = rr / a.grp;
-          const bool ok = t < ntok && (tok0 + t <= total - a.ncols + c);
-          S[rr * kSP + t] = ok ? C[e] * a.scale : -INFINITY;
-        }
-      }
-    }
-    __syncthreads();
-    // ---- 3. online softmax: wave w owns rows w, w+4, ...; lane = token
-    for (int rr = wv; rr < R; rr += 4) {
-      float s = S[rr * kSP + lane];
-      float mx = wave_max(s);
-      float m_old = s_m[rr];
-      float m_new = fmaxf(m_old, mx);
-      float p = (s == -INFINITY) ? 0.f : __expf(s - m_new);
-      float sc = (m_old == -INFINITY) ? 0.f : __expf(m_old - m_new);
-      float ps = wave_sum(p);
-      uint16_t ph = f32_to_bf16(p);
-      uint16_t pl = f32_to_bf16(p - bf16_to_f32(ph));
-      Ph[rr * kPP + lane] = ph;
-      Pl[rr * kPP + lane] = pl;
-      if (lane == 0) {
-        s_m[rr] = m_new;
-        s_l[rr] = s_l[rr] * sc + ps;
-        s_c[rr] = sc;
-      }
-    }
-    // ---- 4. V tile, transposed: Vt[channel][token]
-    {
-#pragma unroll
-      for (int c = 0; c < 32; ++c) vcol[c * kVP] = 0;
-      if (fresh) {
-        const int slot = pos - a.len;
-        if (a.qkv && slot >= a.slot0) {
-          const uint16_t* src = Fv + (slot - a.slot0) * 128 + 32 * j;
-#pragma unroll
-          for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
-        } else {
-          const uint16_t* src = a.Vnew + ((size_t)slot * g.n_kv_heads + head) * 128 + 32 * j;
-#pragma unroll
-          for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
-        }
-      }
-      wvw.decode(mv, (FULL && live) ? ~mv : 0u, [&](int pos, uint16_t v) { vcol[pos * kVP] = v; });
-    }
-    __syncthreads();
-    // ---- 5. O = O * rescale + P V ; wave w owns channels 32w .. 32w+31
+    wk.decode(mk, (FULL && live) ? ~mk : 0u, [&](int bp, uint16_t v) { krow[bp] = v; });
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  // ---- 3. scores of this wave's 16 tokens against all query rows
+  {
+    const uint16_t* b_base = Kt + (16 * wv + mi) * kKP + 4 + 4 * mq;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      f32x4 scv;
+      f32x4 C = {0.f, 0.f, 0.f, 0.f};
+      const uint16_t* a_base = Qs + (mt * 16 + mi) * kQP + 4 * mq;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) scv[e] = s_c[mt * 16 + 4 * mq + e];
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        f32x4 C = Oacc[mt][nt] * scv;
-        const uint16_t* b_base = Vt + (33 * wv + 1 + nt * 16 + mi) * kVP + 4 * mq;
-        const uint16_t* ah = Ph + (mt * 16 + mi) * kPP + 4 * mq;
-        const uint16_t* al = Pl + (mt * 16 + mi) * kPP + 4 * mq;
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-          bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + kb * 16);
-          C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*reinterpret_cast<const bf16x4*>(ah + kb * 16), bv, C, 0, 0, 0);
-          C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*reinterpret_cast<const bf16x4*>(al + kb * 16), bv, C, 0, 0, 0);
-        }
-        Oacc[mt][nt] = C;
+      for (int kk = 0; kk < 8; ++kk) {
+        bf16x4 av = *reinterpret_cast<const bf16x4*>(a_base + kk * 16);
+        bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + (kk >> 1) * kKG + (kk & 1) * 16);
+        C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, bv, C, 0, 0, 0);
       }
-    }
-    __syncthreads();
-  }
-
-  // ---- partial result of this split
-  float* part = a.part + ((size_t)split * g.n_kv_heads + head) * R * kPartStride;
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+      const int t = 16 * wv + mi;  // token of this lane's score column
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        int rr = mt * 16 + 4 * mq + e;
-        if (rr < R) part[rr * kPartStride + 32 * wv + nt * 16 + mi] = Oacc[mt][nt][e];
+        const int rr = mt * 16 + 4 * mq + e;
+        // column c sees positions 0 .. len + n_new - ncols + c
+        const int c = rr / a.grp;
+        const bool ok = t < ntok && (tok0 + t <= total - a.ncols + c);
+        S[rr * kSP + t] = ok ? C[e] * a.scale : -INFINITY;
       }
+    }
+  }
+  __syncthreads();
+  // ---- 4. softmax of the page: wave w owns rows w, w+4, ...; lane = token
+  for (int rr = wv; rr < R; rr += 4) {
+    const float sc = S[rr * kSP + lane];
+    const float mx = wave_max(sc);
+    const float p = (sc == -INFINITY) ? 0.f : __expf(sc - mx);
+    const float ps = wave_sum(p);
+    const uint16_t ph = f32_to_bf16(p);
+    Ph[rr * kPP + lane] = ph;
+    Pl[rr * kPP + lane] = f32_to_bf16(p - bf16_to_f32(ph));
+    if (lane == 0) {
+      s_m[rr] = mx;
+      s_l[rr] = ps;
+    }
+  }
+  // ---- 5. V tile, transposed: Vt[channel][token]
+  {
+#pragma unroll
+    for (int c = 0; c < 32; ++c) vcol[c * kVP] = 0;
+    if (fresh) {
+      const int slot = pos - a.len;
+      const uint16_t* src = (a.qkv && slot >= a.slot0)
+                                ? Fv + (slot - a.slot0) * 128 + 32 * j
+                                : a.Vnew + ((size_t)slot * g.n_kv_heads + head) * 128 + 32 * j;
+#pragma unroll
+      for (int c = 0; c < 32; ++c) vcol[c * kVP] = src[c];
+    }
+    wvw.decode(mv, (FULL && live) ? ~mv : 0u, [&](int bp, uint16_t v) { vcol[bp * kVP] = v; });
+  }
+  __syncthreads();
+  // ---- 6. O = P V ; wave w owns channels 32w .. 32w+31; partial result of this page
+  float* part = a.part + ((size_t)pg * g.n_kv_heads + head) * R * kPartStride;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      f32x4 C = {0.f, 0.f, 0.f, 0.f};
+      const uint16_t* b_base = Vt + (33 * wv + 1 + nt * 16 + mi) * kVP + 4 * mq;
+      const uint16_t* ah = Ph + (mt * 16 + mi) * kPP + 4 * mq;
+      const uint16_t* al = Pl + (mt * 16 + mi) * kPP + 4 * mq;
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) {
+        bf16x4 bv = *reinterpret_cast<const bf16x4*>(b_base + kb * 16);
+        C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*reinterpret_cast<const bf16x4*>(ah + kb * 16), bv, C, 0, 0, 0);
+        C = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(*reinterpret_cast<const bf16x4*>(al + kb * 16), bv, C, 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int rr = mt * 16 + 4 * mq + e;
+        if (rr < R) part[rr * kPartStride + 32 * wv + nt * 16 + mi] = C[e];
+      }
+    }
+  }
   if (tid < R) {
     part[tid * kPartStride + 128] = s_m[tid];
     part[tid * kPartStride + 129] = s_l[tid];
