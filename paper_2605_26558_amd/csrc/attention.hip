@@ -357,13 +357,16 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 }
 
 // Combine the splits: o = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, rounded to bf16.
-// One workgroup per (query row, kv head): the split weights are computed once into LDS, then
-// thread (channel d, part p) sums the splits s = p, p + 4, ... with independent loads and the
-// four parts are added in part order (a fixed order: the result does not depend on timing).
+// One workgroup per (query row, kv head, half of the channels): the split weights are computed
+// once into LDS, then thread (channel d, part p) sums the splits s = p, p + 8, ... with
+// independent loads and the eight parts are added in part order (a fixed order: the result
+// does not depend on timing, nor on how many rows ride along).
+constexpr int kMergeParts = 8;
 __global__ __launch_bounds__(512) void attn_merge_kernel(AttnArgs a) {
-  extern __shared__ float sw[];  // [nsplit] weights, then [4][128] partial sums
+  extern __shared__ float sw[];  // [nsplit] weights, then [kMergeParts][64] partial sums
   __shared__ float red[16];
-  const int rr = blockIdx.x, head = blockIdx.y, tid = threadIdx.x, d = tid & 127, part = tid >> 7;
+  const int rr = blockIdx.x, head = blockIdx.y, tid = threadIdx.x;
+  const int d = blockIdx.z * 64 + (tid & 63), part = tid >> 6;
   const int R = a.ncols * a.grp;
   const size_t sstride = (size_t)a.g.n_kv_heads * R * kPartStride;
   const float* base = a.part + ((size_t)head * R + rr) * kPartStride;
@@ -390,12 +393,14 @@ __global__ __launch_bounds__(512) void attn_merge_kernel(AttnArgs a) {
   for (int w = 0; w < 8; ++w) den += red[8 + w];
   float num = 0.f;
 #pragma unroll 8
-  for (int s = part; s < a.nsplit; s += 4) num += sw[s] * base[s * sstride + d];
+  for (int s = part; s < a.nsplit; s += kMergeParts) num += sw[s] * base[s * sstride + d];
   float* ps = sw + a.nsplit;
-  ps[part * 128 + d] = num;
+  ps[part * 64 + (tid & 63)] = num;
   __syncthreads();
   if (part == 0) {
-    num = ((ps[d] + ps[128 + d]) + ps[256 + d]) + ps[384 + d];
+    num = ps[tid];
+#pragma unroll
+    for (int q = 1; q < kMergeParts; ++q) num += ps[q * 64 + tid];
     const int c = rr / a.grp, gi = rr - c * a.grp;
     a.O[((size_t)c * a.n_q_heads + head * a.grp + gi) * 128 + d] = f32_to_bf16(num / den);
   }
@@ -469,7 +474,8 @@ int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
   }
   }
   if (rc != CAS_OK) return rc;
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(R, g.n_kv_heads), dim3(512), sizeof(float) * (a.nsplit + 512), ctx->stream, a);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(R, g.n_kv_heads, 2), dim3(512), sizeof(float) * (a.nsplit + kMergeParts * 64),
+                     ctx->stream, a);
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;
 }

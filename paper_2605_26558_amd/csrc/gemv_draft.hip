@@ -141,16 +141,33 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
     }
   };
 
+  // ---- x is staged as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0.
+  // Fast path (cols a multiple of 8, at most 2 pieces of 8 per thread): x and the norm gain are
+  // read once with 16-byte loads, requested before anything else so they travel together with
+  // the first bitmap words, and stay in registers between the norm reduction and the LDS writes.
+  const int npiece = (nseg * 32) >> 3;  // pieces of 8 columns, including the zero tail
+  const bool fast = (a.cols & 7) == 0 && npiece <= 2 * kGemvThreads &&
+                    ((reinterpret_cast<uintptr_t>(a.x) | reinterpret_cast<uintptr_t>(a.gain)) & 15) == 0;
+  uint4 raw[2][NB], gv[2];
+  auto stage_load = [&]() {
+    if (!fast) return;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int col = (tid + k * kGemvThreads) * 8;
+      gv[k] = make_uint4(0, 0, 0, 0);
+      if (a.gain && col < a.cols) gv[k] = *reinterpret_cast<const uint4*>(a.gain + col);
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        raw[k][b] = make_uint4(0, 0, 0, 0);
+        if (col < a.cols) raw[k][b] = *reinterpret_cast<const uint4*>(a.x + (size_t)b * a.cols + col);
+      }
+    }
+  };
   auto stage_x = [&]() {
-    // ---- stage x as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0.
-    // Fast path (cols a multiple of 8, at most 2 pieces of 8 per thread): x is read once with
-    // 16-byte loads and kept in registers between the norm reduction and the LDS writes.
     for (int sgi = tid; sgi < nseg; sgi += kGemvThreads) {
 #pragma unroll
       for (int b = 0; b < NB; ++b) xs[sgi * 33 * NB + b] = 0.f;
     }
-    const int npiece = (nseg * 32) >> 3;  // pieces of 8 columns, including the zero tail
-    const bool fast = (a.cols & 7) == 0 && npiece <= 2 * kGemvThreads;
     float rn[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) rn[b] = 1.f;
@@ -171,35 +188,30 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
       }
     };
     if (fast) {
-      uint4 raw[2][NB];
-      float ss[NB];
-#pragma unroll
-      for (int b = 0; b < NB; ++b) ss[b] = 0.f;
-#pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        const int col = (tid + k * kGemvThreads) * 8;
+      if (a.gain) {
+        float ss[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-          raw[k][b] = make_uint4(0, 0, 0, 0);
-          if (col < a.cols) raw[k][b] = *reinterpret_cast<const uint4*>(a.x + (size_t)b * a.cols + col);
-          const uint32_t wd[4] = {raw[k][b].x, raw[k][b].y, raw[k][b].z, raw[k][b].w};
+          ss[b] = 0.f;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float lo = __uint_as_float(wd[e] << 16), hi = __uint_as_float(wd[e] & 0xFFFF0000u);
-            ss[b] += lo * lo;
-            ss[b] += hi * hi;
+          for (int k = 0; k < 2; ++k) {
+            const uint32_t wd[4] = {raw[k][b].x, raw[k][b].y, raw[k][b].z, raw[k][b].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              float lo = __uint_as_float(wd[e] << 16), hi = __uint_as_float(wd[e] & 0xFFFF0000u);
+              ss[b] += lo * lo;
+              ss[b] += hi * hi;
+            }
           }
         }
+        finish_norm(ss);
       }
-      if (a.gain) finish_norm(ss);
 #pragma unroll
       for (int k = 0; k < 2; ++k) {
         const int piece = tid + k * kGemvThreads;
         const int col = piece * 8;
         if (piece < npiece) {
-          uint4 gv = make_uint4(0, 0, 0, 0);
-          if (a.gain && col < a.cols) gv = *reinterpret_cast<const uint4*>(a.gain + col);
-          const uint32_t gw4[4] = {gv.x, gv.y, gv.z, gv.w};
+          const uint32_t gw4[4] = {gv[k].x, gv[k].y, gv[k].z, gv[k].w};
           float* dst = xs + ((col >> 5) * 33 + 1 + (col & 31)) * NB;
 #pragma unroll
           for (int b = 0; b < NB; ++b) {
@@ -246,6 +258,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   };
   Cursor cb{row_first, 0}, ci{row_first, 0}, cc{row_first, 0};
   Window<FW> w0, w1;
+  stage_load();
   if (idle) {
     stage_x();
     return;

@@ -32,33 +32,75 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
   for (int i = threadIdx.x; i < hidden; i += 256) h[(size_t)c * hidden + i] = emb[(size_t)t * hidden + i];
 }
 
-__device__ __forceinline__ float block_sum256(float v, float* red) {
-  v = wave_sum(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return red[0] + red[1] + red[2] + red[3];
-}
-
-// xn = bf16(x * rsqrt(mean(x^2) + eps) * g), one workgroup per column
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict__ h, const uint16_t* __restrict__ g,
-                                                      uint16_t* __restrict__ out, int n, float eps) {
-  __shared__ float red[4];
-  const int c = blockIdx.x;
+// xn = bf16(x * rsqrt(mean(x^2) + eps) * g), one workgroup per column.  A column of up to
+// 8192 values (a multiple of 8) is read once with 16-byte loads, together with the gain, and
+// stays in registers between the reduction and the scaling.
+constexpr int kNormThreads = 512;
+__global__ __launch_bounds__(kNormThreads) void rmsnorm_kernel(const uint16_t* __restrict__ h,
+                                                               const uint16_t* __restrict__ g,
+                                                               uint16_t* __restrict__ out, int n, float eps) {
+  __shared__ float red[kNormThreads / 64];
+  const int c = blockIdx.x, tid = threadIdx.x;
   const uint16_t* x = h + (size_t)c * n;
+  uint16_t* o = out + (size_t)c * n;
+  const bool fast = (n & 7) == 0 && n <= 2 * 8 * kNormThreads &&
+                    ((reinterpret_cast<uintptr_t>(h) | reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+  uint4 xv[2], gv[2];
   float ss = 0.f;
-  for (int i = threadIdx.x; i < n; i += 256) {
-    float v = bf16_to_f32(x[i]);
-    ss += v * v;
+  if (fast) {
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int i = (tid + k * kNormThreads) * 8;
+      xv[k] = gv[k] = make_uint4(0, 0, 0, 0);
+      if (i < n) {
+        xv[k] = *reinterpret_cast<const uint4*>(x + i);
+        gv[k] = *reinterpret_cast<const uint4*>(g + i);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const uint32_t w[4] = {xv[k].x, xv[k].y, xv[k].z, xv[k].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float lo = __uint_as_float(w[e] << 16), hi = __uint_as_float(w[e] & 0xFFFF0000u);
+        ss += lo * lo;
+        ss += hi * hi;
+      }
+    }
+  } else {
+    for (int i = tid; i < n; i += kNormThreads) {
+      const float v = bf16_to_f32(x[i]);
+      ss += v * v;
+    }
   }
-  ss = block_sum256(ss, red);
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  ss = 0.f;
+#pragma unroll
+  for (int w = 0; w < kNormThreads / 64; ++w) ss += red[w];
   const float r = 1.0f / sqrtf(ss / (float)n + eps);
-  for (int i = threadIdx.x; i < n; i += 256)
-    out[(size_t)c * n + i] = f32_to_bf16(bf16_to_f32(x[i]) * r * bf16_to_f32(g[i]));
+  if (fast) {
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int i = (tid + k * kNormThreads) * 8;
+      if (i < n) {
+        const uint32_t w[4] = {xv[k].x, xv[k].y, xv[k].z, xv[k].w};
+        const uint32_t gw[4] = {gv[k].x, gv[k].y, gv[k].z, gv[k].w};
+        uint32_t ov[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = __uint_as_float(w[e] << 16) * r * __uint_as_float(gw[e] << 16);
+          const float hi = __uint_as_float(w[e] & 0xFFFF0000u) * r * __uint_as_float(gw[e] & 0xFFFF0000u);
+          ov[e] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+        }
+        *reinterpret_cast<uint4*>(o + i) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
+      }
+    }
+  } else {
+    for (int i = tid; i < n; i += kNormThreads) o[i] = f32_to_bf16(bf16_to_f32(x[i]) * r * bf16_to_f32(g[i]));
+  }
 }
-
-
-
 
 // token = lowest index among the maxima of a logits row; stage 1: one candidate per slice
 constexpr int kArgmaxSlices = 64;
@@ -119,7 +161,7 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_
     uint16_t* vn = m->vnew + (size_t)l * c.max_cols * kvd;
     // the draft pass fuses the norms, residual adds and SwiGLU into its GEMV launches
     if (full) {
-      hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, L.d_g_attn, m->xn, c.hidden, c.rms_eps);
+      hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(kNormThreads), 0, st, m->h, L.d_g_attn, m->xn, c.hidden, c.rms_eps);
       CAS_TRY(launch_gemm_verify(ctx, L.wqkv.desc, L.wqkv.d_spec, L.wqkv.d_verif, m->xn, ncols, m->y));
     } else {
       CAS_TRY(launch_gemv_draft_fused(ctx, L.wqkv.desc, L.wqkv.d_spec, m->h, ncols, m->y, L.d_g_attn, c.rms_eps, 0,
@@ -136,7 +178,7 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_
     if (full) {
       // residual adds and SwiGLU ride in the epilogue of the verification GEMM
       CAS_TRY(launch_gemm_verify_fused(ctx, L.wo.desc, L.wo.d_spec, L.wo.d_verif, m->ao, ncols, nullptr, 1, m->h));
-      hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, L.d_g_ffn, m->xn, c.hidden, c.rms_eps);
+      hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(kNormThreads), 0, st, m->h, L.d_g_ffn, m->xn, c.hidden, c.rms_eps);
       CAS_TRY(launch_gemm_verify_fused(ctx, L.wgu.desc, L.wgu.d_spec, L.wgu.d_verif, m->xn, ncols, nullptr, 2,
                                        m->act));
       CAS_TRY(launch_gemm_verify_fused(ctx, L.wd.desc, L.wd.d_spec, L.wd.d_verif, m->act, ncols, nullptr, 1, m->h));
@@ -148,7 +190,7 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_
     }
   }
   if (full) {
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(256), 0, st, m->h, m->d_g_final, m->xn, c.hidden, c.rms_eps);
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(kNormThreads), 0, st, m->h, m->d_g_final, m->xn, c.hidden, c.rms_eps);
     CAS_TRY(launch_gemm_verify(ctx, m->lm_head.desc, m->lm_head.d_spec, m->lm_head.d_verif, m->xn, ncols, logits));
   } else {
     CAS_TRY(launch_gemv_draft_fused(ctx, m->lm_head.desc, m->lm_head.d_spec, m->h, ncols, logits, m->d_g_final,
