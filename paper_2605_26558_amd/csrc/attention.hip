@@ -362,6 +362,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 // independent loads and the eight parts are added in part order (a fixed order: the result
 // does not depend on timing, nor on how many rows ride along).
 constexpr int kMergeParts = 8;
+constexpr int kMergePre = 20;  // splits per thread whose outputs are requested before the weights exist
 __global__ __launch_bounds__(512) void attn_merge_kernel(AttnArgs a) {
   extern __shared__ float sw[];  // [nsplit] weights, then [kMergeParts][64] partial sums
   __shared__ float red[16];
@@ -370,8 +371,21 @@ __global__ __launch_bounds__(512) void attn_merge_kernel(AttnArgs a) {
   const int R = a.ncols * a.grp;
   const size_t sstride = (size_t)a.g.n_kv_heads * R * kPartStride;
   const float* base = a.part + ((size_t)head * R + rr) * kPartStride;
-  float mx = -INFINITY;
-  for (int s = tid; s < a.nsplit; s += 512) mx = fmaxf(mx, base[s * sstride + 128]);
+  // everything this thread needs from the first 512 splits goes out in one batch: its split's
+  // (max, sum) and the outputs of splits part, part + 8, ... of its channel
+  float m0 = -INFINITY, l0 = 0.f;
+  if (tid < a.nsplit) {
+    m0 = base[tid * sstride + 128];
+    l0 = base[tid * sstride + 129];
+  }
+  float o[kMergePre];
+#pragma unroll
+  for (int q = 0; q < kMergePre; ++q) {
+    const int s = part + q * kMergeParts;
+    o[q] = s < a.nsplit ? base[s * sstride + d] : 0.f;
+  }
+  float mx = m0;
+  for (int s = tid + 512; s < a.nsplit; s += 512) mx = fmaxf(mx, base[s * sstride + 128]);
   mx = wave_max(mx);
   if ((tid & 63) == 0) red[tid >> 6] = mx;
   __syncthreads();
@@ -379,7 +393,12 @@ __global__ __launch_bounds__(512) void attn_merge_kernel(AttnArgs a) {
 #pragma unroll
   for (int w = 1; w < 8; ++w) M = fmaxf(M, red[w]);
   float den = 0.f;
-  for (int s = tid; s < a.nsplit; s += 512) {
+  if (tid < a.nsplit) {
+    const float w = (m0 == -INFINITY) ? 0.f : __expf(m0 - M);
+    sw[tid] = w;
+    den = w * l0;
+  }
+  for (int s = tid + 512; s < a.nsplit; s += 512) {
     float m = base[s * sstride + 128];
     float w = (m == -INFINITY) ? 0.f : __expf(m - M);
     sw[s] = w;
@@ -392,8 +411,13 @@ __global__ __launch_bounds__(512) void attn_merge_kernel(AttnArgs a) {
 #pragma unroll
   for (int w = 0; w < 8; ++w) den += red[8 + w];
   float num = 0.f;
+#pragma unroll
+  for (int q = 0; q < kMergePre; ++q) {
+    const int s = part + q * kMergeParts;
+    if (s < a.nsplit) num += sw[s] * o[q];
+  }
 #pragma unroll 8
-  for (int s = part; s < a.nsplit; s += kMergeParts) num += sw[s] * base[s * sstride + d];
+  for (int s = part + kMergePre * kMergeParts; s < a.nsplit; s += kMergeParts) num += sw[s] * base[s * sstride + d];
   float* ps = sw + a.nsplit;
   ps[part * 64 + (tid & 63)] = num;
   __syncthreads();
