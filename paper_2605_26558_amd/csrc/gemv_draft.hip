@@ -13,6 +13,7 @@
 // 0.0, so a lane that has run out of set bits (bit position -1) multiplies by zero.
 // The (row, chunk) items of a wave run through a three-stage software pipeline: bitmap word of
 // item q+2, prefix + window loads of item q+1, arithmetic of item q.
+#include <algorithm>
 #include "cas_device.hpp"
 #include "cas_internal.hpp"
 
@@ -61,11 +62,14 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   const int nseg = nchunk * 64;
   const int lane = tid & 63;
   // wave-uniform values are made scalar explicitly so the row/chunk bookkeeping runs on the SALU
-  const int gw = blockIdx.x * kGemvWaves + __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nwaves = a.nwaves;  // rows are dealt round-robin to this many waves
-  const bool idle = gw >= nwaves;  // still helps staging x
+  // rows (row pairs) are dealt round-robin to the waves, numbered so that consecutive units go
+  // to consecutive workgroups: every workgroup, and every SIMD inside it, gets the same count
+  // within one
+  const int gw = __builtin_amdgcn_readfirstlane(tid >> 6) * gridDim.x + blockIdx.x;
+  const int nwaves = a.nwaves;
   const int pair = a.epi == 2;
   const int row_first = pair ? 2 * gw : gw;
+  const bool idle = row_first >= a.rows;  // still helps staging x
 
   auto load_bm = [&](const Cursor& c) -> uint32_t {
     int wi = c.chunk * 64 + lane;
@@ -319,13 +323,17 @@ int launch_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec, 
   a.x = x; a.y = y;
   size_t lds = sizeof(float) * (size_t)((d.bw + 63) / 64 * 64) * 33 * batch;
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
-  // every wave gets the same number of rows (within one): r rows per wave, as many waves as fit at once
-  static int waves_per_cu = [] { const char* e = getenv("CAS_GEMV_WAVES_PER_CU"); return e ? atoi(e) : 32; }();
-  const int64_t max_waves = (int64_t)ctx->num_cu * waves_per_cu;
+  // one or two workgroups per CU (two fill its 32 wave slots), whichever leaves the most
+  // loaded CU with fewer rows; all of them are resident at once
   const int64_t units = epi == 2 ? d.rows / 2 : d.rows;  // a gate/up row pair stays in one wave
-  const int64_t r = (units + max_waves - 1) / max_waves;
-  a.nwaves = (int)((units + r - 1) / r);
-  int grid = (a.nwaves + kGemvWaves - 1) / kGemvWaves;
+  int64_t best_load = 0;
+  int grid = 1;
+  for (int g = 1; g <= 2; ++g) {
+    const int64_t wgs = std::min<int64_t>((int64_t)ctx->num_cu * g, units);
+    const int64_t load = (units + wgs - 1) / wgs * g;
+    if (g == 1 || load < best_load) { best_load = load; grid = (int)wgs; }
+  }
+  a.nwaves = grid * kGemvWaves;
   ProfScope prof(ctx, PROF_GEMV_DRAFT, 4.0 * (double)d.rows * (d.bw + d.sw));
   switch (d.t) {
     case 0: return launch_t<0>(ctx, a, batch, grid, lds);
