@@ -58,7 +58,8 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
   const int gi = wv / Q, part = wv % Q;
   uint16_t* tile = tiles + wv * 16 * kTilePitch;
   uint16_t* Xq = lds + NW * 16 * kTilePitch + (size_t)wv * a.ncols * XQP;  // [ncols][XQP], this wave's
-  for (int i = tid; i < NW * 16 * kTilePitch; i += NT) tiles[i] = 0;
+  // columns past the end of a ragged row are never written by the decode: they must read as 0
+  for (int i = tid; i < NW * 16 * kTilePitch / 8; i += NT) reinterpret_cast<uint4*>(tiles)[i] = make_uint4(0, 0, 0, 0);
   __syncthreads();
 
   const int r = lane >> 2, j = lane & 3;
@@ -257,11 +258,14 @@ int launch_gemm_verify_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec,
   a.pruned = (const uint32_t*)((const char*)verif + d.off_pruned);
   a.X = X; a.Y = Y;
   ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + d.sw + d.lw + d.pw));
-  // one row group per workgroup, four waves each taking a quarter of every slab (measured
-  // faster than 8-wave workgroups in either arrangement: fewer lanes wait at the slab barriers)
-  // few row groups: split each over eight waves so that every CU still gets several waves
+  // One row group per workgroup.  Many row groups: four waves, each taking a quarter of every
+  // slab (measured faster than 8-wave workgroups: fewer lanes wait at the slab barriers).  Few
+  // row groups: eight waves so that every CU still gets several, sixteen when the rows are long
+  // (each wave then has one decode step per slab and the serial chain per workgroup halves).
   static int q8_below = [] { const char* e = getenv("CAS_VERIFY_Q8_BELOW"); return e ? atoi(e) : 300; }();
-  if ((d.rows + 15) / 16 < q8_below) return launch_gq<1, 8>(ctx, a, d.t);
+  const int groups = (int)((d.rows + 15) / 16);
+  if (groups < q8_below && d.cols >= 4 * kSlabCols) return launch_gq<1, 16>(ctx, a, d.t);
+  if (groups < q8_below) return launch_gq<1, 8>(ctx, a, d.t);
   return launch_gq<1, 4>(ctx, a, d.t);
 }
 
