@@ -262,7 +262,7 @@ int launch_gemm_verify_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec,
   // slab (measured faster than 8-wave workgroups: fewer lanes wait at the slab barriers).  Few
   // row groups: eight waves so that every CU still gets several, sixteen when the rows are long
   // (each wave then has one decode step per slab and the serial chain per workgroup halves).
-  static int q8_below = [] { const char* e = getenv("CAS_VERIFY_Q8_BELOW"); return e ? atoi(e) : 300; }();
+  constexpr int q8_below = 300;  // row groups: just over one per CU
   const int groups = (int)((d.rows + 15) / 16);
   if (groups < q8_below && d.cols >= 4 * kSlabCols) return launch_gq<1, 16>(ctx, a, d.t);
   if (groups < q8_below) return launch_gq<1, 8>(ctx, a, d.t);
