@@ -9,13 +9,17 @@
 //
 // One workgroup handles one kv head and one page (64 positions) of the sequence:
 //   1. thread (token r, word j) decodes its 32 channels of K into a 64 x 128 bf16 tile in LDS;
-//   2. each wave multiplies its 16 tokens with the query rows (grouped-query: 4 query heads x
-//      columns share the kv head) by 16x16x16 bf16 MFMA and writes the scaled scores to LDS;
-//   3. softmax numerators of the page per query row (row max / sum kept for the merge),
-//      probabilities split into a bf16 head and a bf16 remainder so the second product keeps
-//      16 mantissa bits;
-//   4. the V tile is decoded transposed and P V is formed in fp32 MFMA registers.
-// Partial (max, sum, output) of every page go to the workspace; a merge kernel combines them.
+//   2. each wave multiplies its 16 tokens with the query rows (grouped-query: the query heads
+//      of the group x columns share the kv head) by 16x16x16 bf16 MFMA; the scaled, masked
+//      scores stay in the MFMA result registers;
+//   3. softmax numerators of the page per query row: the row maximum and sum go through DPP
+//      rotations inside a wave and a few LDS words across the four waves (kept for the
+//      merge); probabilities are split into a bf16 head and a bf16 remainder, so the second
+//      product keeps 16 mantissa bits, and stored over the query tile, which is dead by then;
+//   4. the V tile is decoded transposed over the dead K tile and P V is formed in fp32 MFMA
+//      registers.
+// Partial (max, sum, output) of every page go to the workspace; a merge kernel combines them
+// in a fixed order.
 #include "cas_device.hpp"
 #include "cas_internal.hpp"
 

@@ -253,9 +253,10 @@ class ModelRoundWorkload:
         self.prof["gemm_verify"] = (n, tv * 1e3, self.verify_w)
         ach = self.draft_w / td / 1e9
         # HBM-side bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-        # FETCH_SIZE scaled by 2.000 after calibration with a plain copy): fetch = 1.016 x the
-        # algorithmic bytes on the 28672 x 4096 shape, writes are the output vector.
-        traffic = 1.016 * self.draft_w / n + 4.0 * sum(m.desc.rows for L in self.layers
+        # FETCH_SIZE scaled by 2.000 after calibration with a plain copy): fetch = 1.042 x the
+        # algorithmic bytes on the 28672 x 4096 shape; every 4-byte output is written as a 32-byte
+        # sector (neighbouring rows belong to workgroups on different XCDs).
+        traffic = 1.042 * self.draft_w / n + 32.0 * sum(m.desc.rows for L in self.layers
                                                        for m in (L["wqkv"], L["wo"], L["wgu"], L["wd"])) / n
         return {"bound": "hbm", "kernel": "gemv_draft_kernel", "achieved": ach, "peak": 8000.0, "unit": "GB/s",
                 "frac": ach / 8000.0, "traffic": traffic, "launches": n, "avg_launch_us": td / n * 1e6,
