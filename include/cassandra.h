@@ -21,6 +21,8 @@
  *     outputs are valid once the caller synchronises that stream.
  *   - bf16 tensors are passed as uint16_t bit patterns.  Device buffers must be 256-byte aligned.
  *   - One cas_ctx per host thread.
+ *   - Empty work (a matrix of 0 rows, 0 tokens to append or read) returns CAS_OK without a
+ *     launch; the data pointers of such a call may be NULL.
  */
 #ifndef CASSANDRA_H
 #define CASSANDRA_H

@@ -116,37 +116,45 @@ static int check_desc(const cas_wdesc* d) {
 
 int cas_encode_weight(cas_ctx* ctx, const uint16_t* d_W, int64_t ld, const float* d_act_norm, const cas_wdesc* desc,
                       void* d_spec, void* d_verif) {
-  if (!ctx || !d_W || !d_spec || !d_verif || check_desc(desc) != CAS_OK || ld < desc->cols) return CAS_EINVAL;
+  if (!ctx || check_desc(desc) != CAS_OK || ld < desc->cols) return CAS_EINVAL;
+  if (desc->rows == 0) return CAS_OK;  // nothing to encode; the pointers may be null
+  if (!d_W || !d_spec || !d_verif) return CAS_EINVAL;
   if (!cas::aligned256(d_spec) || !cas::aligned256(d_verif)) return CAS_EINVAL;
   return cas::launch_encode_weight(ctx, d_W, ld, d_act_norm, *desc, d_spec, d_verif);
 }
 
 int cas_decode_weight(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, const void* d_verif, uint16_t* d_out,
                       int64_t ld) {
-  if (!ctx || !d_spec || !d_out || check_desc(desc) != CAS_OK || ld < desc->cols) return CAS_EINVAL;
+  if (!ctx || check_desc(desc) != CAS_OK || ld < desc->cols) return CAS_EINVAL;
+  if (desc->rows == 0) return CAS_OK;
+  if (!d_spec || !d_out) return CAS_EINVAL;
   if (!cas::aligned256(d_spec) || !cas::aligned256(d_verif)) return CAS_EINVAL;
   return cas::launch_decode_weight(ctx, *desc, d_spec, d_verif, d_out, ld);
 }
 
 int cas_gemv_draft(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, const uint16_t* d_x, int batch,
                    float* d_y) {
-  if (!ctx || !d_spec || !d_x || !d_y || check_desc(desc) != CAS_OK) return CAS_EINVAL;
-  if (batch < 1 || batch > 4 || !cas::aligned256(d_spec)) return CAS_EINVAL;
+  if (!ctx || check_desc(desc) != CAS_OK || batch < 1 || batch > 4) return CAS_EINVAL;
+  if (desc->rows == 0) return CAS_OK;  // empty output
+  if (!d_spec || !d_x || !d_y || !cas::aligned256(d_spec)) return CAS_EINVAL;
   return cas::launch_gemv_draft(ctx, *desc, d_spec, d_x, batch, d_y);
 }
 
 int cas_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, const uint16_t* d_x, int batch,
                          float* d_y, const uint16_t* d_gain, float eps, int epilogue, uint16_t* d_out16) {
-  if (!ctx || !d_spec || !d_x || check_desc(desc) != CAS_OK) return CAS_EINVAL;
-  if (batch < 1 || batch > 4 || !cas::aligned256(d_spec) || epilogue < 0 || epilogue > 2) return CAS_EINVAL;
+  if (!ctx || check_desc(desc) != CAS_OK || batch < 1 || batch > 4 || epilogue < 0 || epilogue > 2) return CAS_EINVAL;
+  if (desc->rows == 0) return CAS_OK;
+  if (!d_spec || !d_x || !cas::aligned256(d_spec)) return CAS_EINVAL;
   if ((epilogue == 0 && !d_y) || (epilogue != 0 && !d_out16)) return CAS_EINVAL;
   return cas::launch_gemv_draft_fused(ctx, *desc, d_spec, d_x, batch, d_y, d_gain, eps, epilogue, d_out16);
 }
 
 int cas_gemm_verify(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, const void* d_verif,
                     const uint16_t* d_X, int ncols, float* d_Y) {
-  if (!ctx || !d_spec || !d_verif || !d_X || !d_Y || check_desc(desc) != CAS_OK) return CAS_EINVAL;
-  if (ncols < 1 || ncols > 16 || !cas::aligned256(d_spec) || !cas::aligned256(d_verif)) return CAS_EINVAL;
+  if (!ctx || check_desc(desc) != CAS_OK || ncols < 1 || ncols > 16) return CAS_EINVAL;
+  if (desc->rows == 0) return CAS_OK;
+  if (!d_spec || !d_verif || !d_X || !d_Y) return CAS_EINVAL;
+  if (!cas::aligned256(d_spec) || !cas::aligned256(d_verif)) return CAS_EINVAL;
   return cas::launch_gemm_verify(ctx, *desc, d_spec, d_verif, d_X, ncols, d_Y);
 }
 
@@ -208,7 +216,9 @@ static int check_seq(const cas_kv* kv, int layer, int seq) {
 }
 
 int cas_kv_append(cas_ctx* ctx, cas_kv* kv, int layer, int seq, const uint16_t* d_K, const uint16_t* d_V, int n_tok) {
-  if (!ctx || !d_K || !d_V || n_tok < 0 || check_seq(kv, layer, seq) != CAS_OK) return CAS_EINVAL;
+  if (!ctx || n_tok < 0 || check_seq(kv, layer, seq) != CAS_OK) return CAS_EINVAL;
+  if (n_tok == 0) return CAS_OK;
+  if (!d_K || !d_V) return CAS_EINVAL;
   const int64_t cap = (int64_t)kv->desc.max_pages_per_seq * kv->desc.page_tokens;
   if ((int64_t)kv->h_len[seq] + n_tok > cap) return CAS_ENOMEM;
   return cas::launch_kv_append(ctx, kv, layer, seq, d_K, d_V, n_tok, kv->h_len[seq]);
@@ -229,7 +239,9 @@ int cas_kv_len(const cas_kv* kv, int seq, int32_t* len) {
 
 int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_tok, int full, uint16_t* d_K,
                 uint16_t* d_V) {
-  if (!ctx || !d_K || !d_V || n_tok < 0 || pos0 < 0 || check_seq(kv, layer, seq) != CAS_OK) return CAS_EINVAL;
+  if (!ctx || n_tok < 0 || pos0 < 0 || check_seq(kv, layer, seq) != CAS_OK) return CAS_EINVAL;
+  if (n_tok == 0) return CAS_OK;
+  if (!d_K || !d_V) return CAS_EINVAL;
   if ((int64_t)pos0 + n_tok > (int64_t)kv->desc.max_pages_per_seq * kv->desc.page_tokens) return CAS_EINVAL;
   return cas::launch_kv_read(ctx, kv, layer, seq, pos0, n_tok, full, d_K, d_V);
 }

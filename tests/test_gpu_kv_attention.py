@@ -164,3 +164,30 @@ def test_attention_llama70b_head_grouping(env):
         err = np.abs(O.bf16_to_f64(out) - reff)
         tol = _attn_tol(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv, reff)
         assert (err <= tol).all(), float((err / tol).max())
+
+
+def test_kv_append_special_values_and_empty_append(env):
+    """Vectors holding +-0, subnormals, Inf and NaN patterns go through the online encoder bit
+    for bit like the oracle's; appending zero tokens changes nothing."""
+    torch, B, ctx = env
+    heads, ntok = 2, 9
+    kv = B.KVCache(ctx, 1, heads, n_pages=1, max_seqs=1, max_pages_per_seq=1)
+    Kh = synth.kv_tensor(ntok, heads, 128, seed=21)
+    Vh = synth.kv_tensor(ntok, heads, 128, seed=22, outlier_channels=0)
+    specials = np.array([0x0000, 0x8000, 0x0001, 0x807F, 0x7F7F, 0x7F80, 0xFF80, 0x7FC0, 0xFFFF, 0x7F81],
+                        dtype=np.uint16)
+    Kh[1, 0, 5:15] = specials
+    Vh[2, 1, 100:110] = specials
+    Kh[3, 1, :] = 0x8000                       # a vector of negative zeros: all keys equal
+    Vh[4, 0, :] = 0x7FC0                       # a vector of NaNs
+    empty = torch.empty((0, heads, 128), dtype=torch.int16, device="cuda")
+    B.cas_kv_append(ctx, kv, 0, 0, empty, empty)
+    B.cas_kv_append(ctx, kv, 0, 0, _dev(torch, Kh), _dev(torch, Vh))
+    B.cas_kv_set_len(kv, 0, ntok)
+    B.cas_kv_append(ctx, kv, 0, 0, empty, empty)
+    Kf, Vf = B.cas_kv_read(ctx, kv, 0, 0, 0, ntok, full=True)
+    np.testing.assert_array_equal(_host(Kf), Kh)
+    np.testing.assert_array_equal(_host(Vf), Vh)
+    Kd, Vd = B.cas_kv_read(ctx, kv, 0, 0, 0, ntok, full=False)
+    np.testing.assert_array_equal(_host(Kd).reshape(-1, 128), O.decode_draft(O.encode_kv(Kh.reshape(-1, 128), 600, 4)))
+    np.testing.assert_array_equal(_host(Vd).reshape(-1, 128), O.decode_draft(O.encode_kv(Vh.reshape(-1, 128), 600, 4)))

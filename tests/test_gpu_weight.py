@@ -181,3 +181,50 @@ def test_fused_draft_gemv_variants_match_oracle(env, rows, cols):
     ga = O.bf16_to_f64(act.cpu().numpy().view(np.uint16)[0]); ra = O.bf16_to_f64(aref)
     assert np.abs(ga - ra).max() <= 2.0 ** -6 * np.abs(ra).max() + 1e-6
     assert (act.cpu().numpy().view(np.uint16)[0] != aref).mean() < 0.05
+
+
+def _special_patterns(rows, cols, seed):
+    """bf16 words that exercise the selection order and the bit split: +-0, subnormals, the
+    largest finite values, +-Inf and NaNs with several payloads, among ordinary values."""
+    W = synth.weight_matrix(rows, cols, seed=seed)
+    specials = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x0080, 0x7F7F, 0xFF7F, 0x7F80, 0xFF80,
+                         0x7F81, 0x7FC0, 0xFFFF, 0x7FFF, 0x3F80, 0xBF80], dtype=np.uint16)
+    rng = np.random.Generator(np.random.Philox(seed))
+    idx = rng.integers(0, W.size, size=min(W.size, 6 * len(specials)))
+    W.reshape(-1)[idx] = np.resize(specials, idx.shape)
+    return W
+
+
+@pytest.mark.parametrize("rows,cols,keep,t,act", [(24, 200, 600, 4, True), (9, 2100, 250, 0, False),
+                                                   (12, 64, 500, 7, True)])
+def test_encode_decode_special_values_bit_exact(env, rows, cols, keep, t, act):
+    """Selection keys are the raw patterns of the scores (NaN largest, -0 == +0 by magnitude):
+    the GPU encoder must pick the same sets as the oracle for every pattern, and the exact
+    reconstruction must give back every word, NaN payloads included."""
+    torch, B, ctx = env
+    print(f"case rows={rows} cols={cols} keep={keep} t={t} act={act}", flush=True)
+    W = _special_patterns(rows, cols, seed=91 + cols)
+    a = synth.act_norm(cols, seed=3) if act else None
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t, None if a is None else torch.from_numpy(a).cuda())
+    torch.cuda.synchronize()
+    p = O.encode_weight(W, keep, t, a)
+    bm, sp, lo, pr = _regions(ew)
+    np.testing.assert_array_equal(bm, p.bitmap)
+    np.testing.assert_array_equal(sp, p.spec)
+    np.testing.assert_array_equal(lo, p.lo)
+    np.testing.assert_array_equal(pr, p.pruned)
+    np.testing.assert_array_equal(B.cas_decode_weight(ctx, ew, full=True).cpu().numpy().view(np.uint16), W)
+    np.testing.assert_array_equal(B.cas_decode_weight(ctx, ew, full=False).cpu().numpy().view(np.uint16),
+                                  O.decode_draft(p))
+
+
+def test_empty_matrix_is_accepted(env):
+    """rows = 0: the descriptor has empty streams and every call returns without launching."""
+    torch, B, ctx = env
+    W = torch.empty((0, 256), dtype=torch.int16, device="cuda")
+    ew = B.cas_encode_weight(ctx, W, 600, 4)
+    assert ew.desc.rows == 0 and ew.desc.K == O.kept_count(256, 600)
+    x = _dev(torch, synth.activations(256, 2, seed=1))
+    assert B.cas_gemv_draft(ctx, ew, x[:1].contiguous()).shape == (1, 0)
+    assert B.cas_gemm_verify(ctx, ew, x).shape == (2, 0)
+    assert B.cas_decode_weight(ctx, ew, full=True).shape == (0, 256)
