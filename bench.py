@@ -31,14 +31,21 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--k", type=int, default=6, help="draft length (config: k = 6)")
+    ap.add_argument("--model", choices=["8b", "70b"], default="8b",
+                    help="8b: the configuration the metric is quoted on; 70b: the 80-layer shape (k = 8) as context")
+    ap.add_argument("--k", type=int, default=None, help="draft length (8B config: k = 6, 70B config: k = 8)")
     ap.add_argument("--keep", type=int, default=600, help="kept fraction in 1/1000 (paper default 40 %% pruned)")
     ap.add_argument("--trunc", type=int, default=4)
-    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--layers", type=int, default=None, help="default: 32 (8b) / 80 (70b)")
     ap.add_argument("--context", type=int, default=8192, help="committed KV positions when a step starts")
     ap.add_argument("--workload", choices=["model", "linear"], default="model")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.k is None:
+        args.k = 8 if args.model == "70b" else 6
+    if args.layers is None:
+        args.layers = 80 if args.model == "70b" else 32
+    return args
 
 
 def cpu_baseline(keep, t, k):
@@ -98,7 +105,9 @@ def main():
 
     roof = wl.roofline_pass()          # HIP events around the dominant kernel's launches
     out = {
-        "metric": "draft/verify step HBM GB/s (% of peak) + batch-1 tokens/s, Llama-3-8B shape",
+        "metric": "draft/verify step HBM GB/s (% of peak) + batch-1 tokens/s, Llama-3-8B shape"
+                  if args.model == "8b" else
+                  "draft/verify step HBM GB/s (% of peak) + batch-1 tokens/s, Llama-3-70B shape (context figure)",
         "value": wl.bytes_per_step / (ms_per_step * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

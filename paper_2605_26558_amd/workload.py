@@ -110,8 +110,13 @@ class ModelRoundWorkload:
         import torch
         self.torch, self.B = torch, B
         self.k, self.ctx_len = args.k, args.context
-        shape = synth.LlamaShape("llama3-8b", 4096, args.layers, 32, 8, 128, 14336, 128256)
+        big = getattr(args, "model", "8b") == "70b"
+        if big:   # hidden 8192, 64 q / 8 kv heads, FFN 28672: ~148 GB encoded at 80 layers
+            shape = synth.LlamaShape("llama3-70b", 8192, args.layers, 64, 8, 128, 28672, 128256)
+        else:
+            shape = synth.LlamaShape("llama3-8b", 4096, args.layers, 32, 8, 128, 14336, 128256)
         self.shape = shape
+        name = "Llama-3-70B" if big else "Llama-3-8B"
         self.ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
         self.ctx = B.Context(workspace=self.ws)
         ctx = self.ctx
@@ -125,7 +130,7 @@ class ModelRoundWorkload:
         def enc(r, c):
             act = torch.exp(0.5 * torch.randn(c, device="cuda", generator=gen))
             w = _random_weight(torch, r, c, gen)
-            if getattr(args, "bf16_context", True):
+            if not big:   # the dense copies of the larger model would not fit beside the encoded ones
                 self.dense.append(w.view(torch.bfloat16))
             return B.cas_encode_weight(ctx, w, args.keep, args.trunc, act)
 
@@ -176,7 +181,7 @@ class ModelRoundWorkload:
         self.bytes_per_step = self.k * (self.draft_w + self.draft_kv) + self.verify_w + self.verify_kv
         self.pending = 1
         self.accepted, self.rounds = 0, 0
-        self.config = {"workload": f"Llama-3-8B-shaped random-init model ({shape.n_layers} layers, vocab {shape.vocab}, "
+        self.config = {"workload": f"{name}-shaped random-init model ({shape.n_layers} layers, vocab {shape.vocab}, "
                                    f"{self.values / 1e9:.2f} G encoded weights), batch 1, KV context {self.ctx_len} "
                                    f"(synthetic K/V, 4 outlier key channels per head), draft length k={self.k}, "
                                    "greedy acceptance; weights + KV in Cassandra format",
