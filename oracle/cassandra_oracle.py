@@ -12,8 +12,9 @@ patterns.  Nothing here is blocked, fused or reordered beyond the definition.
 Parity pins (tests/test_oracle_*.py): exhaustive bit-exact round trip over all
 65536 bf16 patterns, bit-prefix property of truncation, kept count, brute-force
 subset search for the selection, closed-form stream sizes, library matmul /
-attention special cases, brute-force acceptance, and speculative == plain token
-streams.  Parity unpinned: acceptance *rates* and speedups (the paper's tables
+attention special cases, brute-force acceptance, speculative == plain token
+streams, and for the unary exponent code the printed code words, a sequential
+scan, the closed-form length and an exhaustive search over code assignments.  Parity unpinned: acceptance *rates* and speedups (the paper's tables
 for them are images that did not survive, and need trained weights).
 """
 from __future__ import annotations
@@ -240,6 +241,147 @@ def encode_kv(v_u16, keep_permille: int, t: int) -> Packed:
     K = kept_count(v.shape[1], keep_permille)
     mask = select_topk(kv_scores(v), K)
     return pack(v, mask, t)
+
+
+# ----------------------------------------------------------------------------
+# Unary-coded exponents: the lossless "Cassandra-1" speculation data (Sec. 4.2
+# "Exponent Compression", decoder of Sec. 5.1 / Algorithm 1)
+# ----------------------------------------------------------------------------
+def unary_codebook(exps):
+    """Codebook of the unary code: exponents ranked by how often they occur among the kept
+    values of the tensor, the most frequent first (Sec. 4.2: more frequent exponents get
+    fewer bits).  All 256 exponents are ranked, ties by the smaller exponent, so every value
+    stays encodable.  Returns (exp_of_rank, rank_of_exp), uint8[256] each."""
+    counts = np.bincount(np.asarray(exps, dtype=np.int64).reshape(-1), minlength=256)
+    order = sorted(range(256), key=lambda e: (-int(counts[e]), e))
+    exp_of_rank = np.array(order, dtype=np.uint8)
+    rank_of_exp = np.zeros(256, dtype=np.uint8)
+    rank_of_exp[exp_of_rank] = np.arange(256, dtype=np.uint8)
+    return exp_of_rank, rank_of_exp
+
+
+def unary_encode_bits(ranks):
+    """Rank r -> r zeros followed by a one (Sec. 4.2: 1, 01, 001, ...), codes concatenated in
+    order.  Returns the bit sequence (uint8 0/1), first bit first."""
+    out = []
+    for r in np.asarray(ranks, dtype=np.int64).reshape(-1):
+        out.extend([0] * int(r))
+        out.append(1)
+    return np.array(out, dtype=np.uint8)
+
+
+def unary_decode_chunked(bits, numel: int):
+    """Decoder of Sec. 5.1: the stream is cut into 8-bit chunks; every chunk counts, for each
+    of its ones, the zeros since the previous one inside the chunk (parallel zero counter) and
+    remembers the zeros after its last one; the reorganisation step then adds to the first
+    count of a chunk the zeros that the preceding chunks left open (a chunk without a one
+    passes on what it received plus its 8 zeros).  Stops after numel codes."""
+    b = np.asarray(bits, dtype=np.uint8).reshape(-1)
+    pad = (-len(b)) % 8
+    chunks = np.concatenate([b, np.zeros(pad, dtype=np.uint8)]).reshape(-1, 8)
+    outputs, trailing = [], []
+    for ch in chunks:                      # zero counting, independent per chunk
+        cnt, outs = 0, []
+        for bit in ch:
+            if bit == 0:
+                cnt += 1
+            else:
+                outs.append(cnt)
+                cnt = 0
+        outputs.append(outs)
+        trailing.append(cnt)
+    carry = 0                              # reorganisation across chunk boundaries
+    for k, outs in enumerate(outputs):
+        if outs:
+            outs[0] += carry
+            carry = trailing[k]
+        else:
+            carry += trailing[k]
+    ranks = [r for outs in outputs for r in outs]
+    assert len(ranks) >= numel, "stream holds fewer codes than values"
+    return np.array(ranks[:numel], dtype=np.int64)
+
+
+@dataclasses.dataclass
+class PackedUnary:
+    """Speculation data with unary-coded exponents.  base holds the bitmap and the
+    verification streams (lo, pruned) unchanged; its spec stream is replaced by
+      sm[r]  : K fields of 8-t bits = sign, then the 7-t leading mantissa bits
+      ue     : for each row the K unary codes of its kept values' exponent ranks, ascending
+               column order, as a little-endian bit stream; row r occupies the words
+               ue_off[r] .. ue_off[r+1]-1 (rows start on word boundaries, zero padded)
+      exp_of_rank : the codebook."""
+    base: Packed
+    sm: np.ndarray
+    ue: np.ndarray
+    ue_off: np.ndarray
+    exp_of_rank: np.ndarray
+
+
+def _split_hi(hi, t: int):
+    """hi field (16-t bits: sign | exponent | 7-t mantissa bits) -> (sm, exponent)."""
+    mb = 7 - t
+    h = hi.astype(np.uint32)
+    exp = (h >> mb) & 0xFF
+    sm = ((h >> (mb + 8)) << mb) | (h & ((1 << mb) - 1))
+    return sm.astype(np.uint16), exp.astype(np.uint16)
+
+
+def to_unary(p: Packed) -> PackedUnary:
+    """Re-code the speculation stream of a packed matrix with unary exponents (Sec. 4.2; the
+    paper applies the exponent coding to the speculation group only, Sec. 5.1 encoder)."""
+    hi = _unpack_fields(p.spec, BF16_BITS - p.t, p.K)
+    sm, exp = _split_hi(hi, p.t)
+    exp_of_rank, rank_of_exp = unary_codebook(exp)
+    ranks = rank_of_exp[exp]
+    rows_words, off = [], [0]
+    for r in range(p.rows):
+        bits = unary_encode_bits(ranks[r])
+        nw = _words(len(bits))
+        padded = np.zeros(nw * 32, dtype=np.uint8)
+        padded[: len(bits)] = bits
+        rows_words.append(np.ascontiguousarray(np.packbits(padded, bitorder="little")).view("<u4").astype(np.uint32))
+        off.append(off[-1] + nw)
+    ue = np.concatenate(rows_words) if rows_words else np.zeros(0, dtype=np.uint32)
+    return PackedUnary(p, _pack_fields(sm, 8 - p.t, _words(p.K * (8 - p.t))), ue,
+                       np.array(off, dtype=np.uint32), exp_of_rank)
+
+
+def _hi_from_unary(u: PackedUnary):
+    p = u.base
+    mb = 7 - p.t
+    sm = _unpack_fields(u.sm, 8 - p.t, p.K).astype(np.uint32)
+    hi = np.zeros((p.rows, p.K), dtype=np.uint32)
+    for r in range(p.rows):
+        words = u.ue[int(u.ue_off[r]): int(u.ue_off[r + 1])]
+        bits = np.unpackbits(np.ascontiguousarray(words.astype("<u4")).view(np.uint8), bitorder="little")
+        exp = u.exp_of_rank[unary_decode_chunked(bits, p.K)].astype(np.uint32) if p.K else np.zeros(0, np.uint32)
+        hi[r] = ((sm[r] >> mb) << (mb + 8)) | (exp << mb) | (sm[r] & ((1 << mb) - 1))
+    return hi
+
+
+def decode_draft_unary(u: PackedUnary):
+    """Draft reconstruction from the unary-coded speculation data: identical in value to
+    decode_draft of the raw-exponent form (the exponent coding is lossless, Sec. 4.2)."""
+    p = u.base
+    out = np.zeros((p.rows, p.cols), dtype=np.uint16)
+    out[unpack_mask(p)] = (_hi_from_unary(u) << p.t).astype(np.uint16).reshape(-1)
+    return out
+
+
+def decode_full_unary(u: PackedUnary):
+    p = u.base
+    mask = unpack_mask(p)
+    lo = _unpack_fields(p.lo, p.t, p.K)
+    pr = _unpack_fields(p.pruned, 16, p.cols - p.K)
+    out = np.zeros((p.rows, p.cols), dtype=np.uint16)
+    out[mask] = ((_hi_from_unary(u) << p.t) | lo).astype(np.uint16).reshape(-1)
+    out[~mask] = pr.reshape(-1)
+    return out
+
+
+def gemv_draft_unary(u: PackedUnary, x_u16):
+    return gemv(decode_draft_unary(u), x_u16)
 
 
 # ----------------------------------------------------------------------------
