@@ -48,7 +48,8 @@ typedef struct cas_ctx cas_ctx;
 typedef struct {
   int32_t keep_permille; /* kept fraction in 1/1000 (600 = 40 % pruned); K = (keep*G+500)/1000 */
   int32_t trunc_bits;    /* t in 0..7: low mantissa bits moved to the verification data */
-  int32_t exp_mode;      /* 0 = exponent stored raw (8 bits); other values: CAS_ENOTSUP */
+  int32_t exp_mode;      /* 0 = exponent stored raw (8 bits); other values: CAS_ENOTSUP (the unary form
+                            is produced from a raw encoding by cas_unary_plan / cas_unary_encode) */
 } cas_fmt;
 
 /*
@@ -136,6 +137,58 @@ int cas_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec
  * does not depend on ncols or on the other columns. */
 int cas_gemm_verify(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
                     const void* d_verif, const uint16_t* d_X, int ncols, float* d_Y);
+
+/* ---- speculation data with unary-coded exponents (Sec. 4.2 "Exponent Compression": the
+ *      lossless configuration; decoder of Sec. 5.1, zero counting with carry across chunks) ---- */
+
+/*
+ * The unary form replaces the spec stream of an encoded matrix; bitmap and verification data
+ * stay as they are.  The exponents of the kept values are ranked by frequency over the whole
+ * matrix (most frequent first, ties to the smaller exponent, all 256 ranked) and a value of
+ * rank r is written as r zero bits followed by a one.  Unary speculation buffer (regions
+ * 256-byte aligned, 256 bytes of zeroed slack at the end):
+ *   bitmap : as in cas_wdesc                                              (bw words per row)
+ *   sm     : K fields of 8-t bits per row: sign, then the 7-t leading mantissa bits,
+ *            ascending column, little-endian bit stream                   (smw words per row)
+ *   table  : uint8 exp_of_rank[256], then uint8 rank_of_exp[256]
+ *   rowoff : uint32 [rows + 1], word index of every row's first code word in ue
+ *   ue     : per row its K code words concatenated (first bit of a code at the lower bit
+ *            position), rows padded with zeros to a word boundary       (ue_words words)
+ * Plain data; buffers can be stored verbatim.
+ */
+typedef struct {
+  cas_wdesc base;   /* the matrix this was re-coded from: rows, cols, K, t, bw, lw, pw, verification offsets */
+  int32_t smw;
+  int32_t reserved;
+  int64_t off_bitmap, off_sm, off_table, off_rowoff, off_ue; /* byte offsets in the unary speculation buffer */
+  int64_t ue_words;
+  int64_t spec_bytes;           /* size the caller must allocate for the unary speculation buffer */
+  uint8_t exp_of_rank[256];     /* the codebook (also stored in the buffer) */
+} cas_udesc;
+
+/* Measures an encoded matrix: exponent histogram of its kept values -> codebook -> size of the
+ * unary stream.  desc / d_spec: the matrix as written by cas_encode_weight (device).  Needs
+ * (rows + 512) * 4 bytes of workspace; synchronises the stream (sizes come back to the host).
+ * CAS_ENOMEM if the workspace is too small. */
+int cas_unary_plan(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, cas_udesc* out);
+
+/* Writes the unary speculation buffer d_uspec (udesc->spec_bytes bytes, 256-byte aligned,
+ * device) from the raw one.  udesc must come from cas_unary_plan on the same data.
+ * Synchronises the stream once (row offsets are summed on the host). */
+int cas_unary_encode(cas_ctx* ctx, const cas_udesc* udesc, const void* d_spec, void* d_uspec);
+
+/* Reconstruction from the unary form (test / reference path): d_verif = NULL gives the draft
+ * view (zero padding), otherwise the exact bf16 matrix.  d_out: [rows][ld] words.
+ * CAS_ENOTSUP if K bytes of exponents do not fit the LDS of a workgroup. */
+int cas_unary_decode(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, const void* d_verif,
+                     uint16_t* d_out, int64_t ld);
+
+/* Draft GEMV y = Wdraft x read from the unary speculation buffer alone (Sec. 4.1 draft
+ * inference on the Sec. 4.2 lossless format).  d_x: bf16 [cols]; d_y: float [rows].  Same values
+ * as cas_gemv_draft on the raw form up to summation order.  CAS_ENOTSUP if x and the
+ * exponents of four rows do not fit the LDS. */
+int cas_gemv_draft_unary(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, const uint16_t* d_x,
+                         float* d_y);
 
 /* ---- compressed, paged KV cache (Sec. 4.2 per-token pruning, Sec. 5.1 online encoder) ---- */
 

@@ -31,6 +31,13 @@ class cas_wdesc(C.Structure):
                 ("spec_bytes", C.c_int64), ("verif_bytes", C.c_int64)]
 
 
+class cas_udesc(C.Structure):
+    _fields_ = [("base", cas_wdesc), ("smw", C.c_int32), ("reserved", C.c_int32),
+                ("off_bitmap", C.c_int64), ("off_sm", C.c_int64), ("off_table", C.c_int64),
+                ("off_rowoff", C.c_int64), ("off_ue", C.c_int64), ("ue_words", C.c_int64),
+                ("spec_bytes", C.c_int64), ("exp_of_rank", C.c_uint8 * 256)]
+
+
 class cas_kv_desc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("page_tokens", C.c_int32), ("n_pages", C.c_int32), ("max_seqs", C.c_int32),
@@ -109,6 +116,10 @@ _SIGNATURES = {
                                       C.POINTER(C.c_int32)]),
     "cas_accept": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32),
                              C.POINTER(C.c_int32)]),
+    "cas_unary_plan": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.POINTER(cas_udesc)]),
+    "cas_unary_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p]),
+    "cas_unary_decode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
+    "cas_gemv_draft_unary": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p]),
 }
 
 
@@ -214,6 +225,49 @@ def cas_encode_weight(ctx: Context, W, keep_permille, trunc_bits, act_norm=None)
     ctx._check(_lib().cas_encode_weight(ctx.h, _ptr(W), W.stride(0), _ptr(act_norm), C.byref(d), _ptr(spec),
                                         _ptr(verif)), "cas_encode_weight")
     return EncodedWeight(d, spec, verif)
+
+
+class UnaryWeight:
+    """Unary-exponent form of an encoded matrix: descriptor, the unary speculation buffer and
+    the (shared) verification buffer."""
+
+    def __init__(self, desc, uspec, verif):
+        self.desc, self.uspec, self.verif = desc, uspec, verif
+
+
+def cas_unary_plan(ctx: Context, ew: EncodedWeight) -> cas_udesc:
+    u = cas_udesc()
+    ctx._check(_lib().cas_unary_plan(ctx.h, C.byref(ew.desc), _ptr(ew.spec), C.byref(u)), "cas_unary_plan")
+    return u
+
+
+def cas_unary_encode(ctx: Context, ew: EncodedWeight, udesc=None) -> UnaryWeight:
+    torch = ctx._torch
+    u = udesc if udesc is not None else cas_unary_plan(ctx, ew)
+    uspec = torch.empty(u.spec_bytes, dtype=torch.uint8, device=ew.spec.device)
+    ctx._check(_lib().cas_unary_encode(ctx.h, C.byref(u), _ptr(ew.spec), _ptr(uspec)), "cas_unary_encode")
+    return UnaryWeight(u, uspec, ew.verif)
+
+
+def cas_unary_decode(ctx: Context, uw: UnaryWeight, full: bool):
+    torch = ctx._torch
+    d = uw.desc.base
+    out = torch.empty((d.rows, d.cols), dtype=torch.int16, device=uw.uspec.device)
+    ctx._check(_lib().cas_unary_decode(ctx.h, C.byref(uw.desc), _ptr(uw.uspec), _ptr(uw.verif) if full else None,
+                                       _ptr(out), d.cols), "cas_unary_decode")
+    return out
+
+
+def cas_gemv_draft_unary(ctx: Context, uw: UnaryWeight, x, out=None):
+    """x: bf16 bits [cols] or [1, cols] -> float32 [rows]."""
+    torch = ctx._torch
+    d = uw.desc.base
+    assert x.numel() == d.cols and x.is_contiguous() and x.element_size() == 2
+    if out is None:
+        out = torch.empty(d.rows, dtype=torch.float32, device=x.device)
+    ctx._check(_lib().cas_gemv_draft_unary(ctx.h, C.byref(uw.desc), _ptr(uw.uspec), _ptr(x), _ptr(out)),
+               "cas_gemv_draft_unary")
+    return out
 
 
 def cas_decode_weight(ctx: Context, ew: EncodedWeight, full: bool):

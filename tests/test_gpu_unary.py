@@ -1,0 +1,112 @@
+"""GPU parity of the unary-exponent form of the speculation data (Sec. 4.2 exponent
+compression) against the oracle, through the C ABI: every region of the buffer bit for bit,
+both reconstructions, and the draft GEMV read from the unary form."""
+import numpy as np
+import pytest
+
+from oracle import cassandra_oracle as O
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2605_26558_amd import binding as B
+    ws = torch.empty(8 << 20, dtype=torch.uint8, device="cuda")
+    return torch, B, B.Context(workspace=ws)
+
+
+def _dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+
+
+def _regions(uw):
+    u, d = uw.desc, uw.desc.base
+    b = uw.uspec.cpu().numpy()
+    def words(off, n):
+        return b[off: off + 4 * n].view("<u4")
+    return (words(u.off_bitmap, d.rows * d.bw).reshape(d.rows, d.bw),
+            words(u.off_sm, d.rows * u.smw).reshape(d.rows, u.smw),
+            b[u.off_table: u.off_table + 512].copy(),
+            words(u.off_rowoff, d.rows + 1),
+            words(u.off_ue, u.ue_words))
+
+
+CASES = [
+    # rows, cols, keep, t, special values
+    (37, 77, 600, 4, False),
+    (16, 128, 600, 4, True),
+    (5, 1, 1000, 4, False),
+    (70, 4096, 600, 4, False),
+    (33, 2500, 250, 0, True),
+    (20, 300, 0, 4, False),
+    (20, 300, 1000, 7, True),
+    (9, 14336, 600, 3, False),
+    (300, 64, 500, 5, True),
+]
+
+
+def _matrix(rows, cols, special, seed):
+    W = synth.weight_matrix(rows, cols, seed=seed)
+    if special:   # rare exponents (long codes that cross several words), zeros, Inf, NaN
+        rng = np.random.Generator(np.random.Philox(seed + 1))
+        idx = rng.integers(0, W.size, size=min(W.size, 64))
+        W.reshape(-1)[idx] = rng.integers(0, 65536, size=idx.shape).astype(np.uint16)
+        W.reshape(-1)[idx[:4]] = np.array([0x7F80, 0xFFFF, 0x0001, 0x8000], dtype=np.uint16)[: len(idx[:4])]
+    return W
+
+
+@pytest.mark.parametrize("rows,cols,keep,t,special", CASES)
+def test_unary_buffer_and_reconstruction_bit_exact(env, rows, cols, keep, t, special):
+    torch, B, ctx = env
+    print(f"case rows={rows} cols={cols} keep={keep} t={t} special={special}", flush=True)
+    W = _matrix(rows, cols, special, seed=rows + cols + t)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t)
+    uw = B.cas_unary_encode(ctx, ew)
+    torch.cuda.synchronize()
+    p = O.encode_weight(W, keep, t)
+    u = O.to_unary(p)
+    assert uw.desc.ue_words == len(u.ue) and uw.desc.smw == u.sm.shape[1]
+    np.testing.assert_array_equal(np.frombuffer(bytes(uw.desc.exp_of_rank), dtype=np.uint8), u.exp_of_rank)
+    bm, sm, table, rowoff, ue = _regions(uw)
+    np.testing.assert_array_equal(bm, p.bitmap)
+    np.testing.assert_array_equal(sm, u.sm)
+    np.testing.assert_array_equal(table[:256], u.exp_of_rank)
+    np.testing.assert_array_equal(table[256:][u.exp_of_rank], np.arange(256, dtype=np.uint8))
+    np.testing.assert_array_equal(rowoff, u.ue_off)
+    np.testing.assert_array_equal(ue, u.ue)
+    full = B.cas_unary_decode(ctx, uw, full=True).cpu().numpy().view(np.uint16)
+    draft = B.cas_unary_decode(ctx, uw, full=False).cpu().numpy().view(np.uint16)
+    np.testing.assert_array_equal(full, W)
+    np.testing.assert_array_equal(draft, O.decode_draft(p))
+
+
+@pytest.mark.parametrize("rows,cols,keep,t,special", [c for c in CASES if not c[4]])
+def test_gemv_draft_unary_matches_oracle(env, rows, cols, keep, t, special):
+    torch, B, ctx = env
+    print(f"case rows={rows} cols={cols} keep={keep} t={t}", flush=True)
+    W = _matrix(rows, cols, False, seed=rows + cols + t)
+    x = synth.activations(cols, 1, seed=11)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t)
+    uw = B.cas_unary_encode(ctx, ew)
+    y = B.cas_gemv_draft_unary(ctx, uw, _dev(torch, x)).cpu().numpy()
+    ref = O.gemv_draft_unary(O.to_unary(O.encode_weight(W, keep, t)), x[0])
+    tol = np.linalg.norm(O.bf16_to_f64(W), axis=1) * np.linalg.norm(O.bf16_to_f64(x[0])) + 1e-30
+    err = np.abs(y - ref) / tol
+    assert err.max() < 2e-3          # spec bar
+    assert err.max() < 2e-5, err.max()
+    # same values as the raw-exponent kernel up to the order of the fp32 sums
+    y_raw = B.cas_gemv_draft(ctx, ew, _dev(torch, x)).cpu().numpy()[0]
+    assert (np.abs(y - y_raw) / tol).max() < 2e-5
+
+
+def test_unary_empty_matrix(env):
+    torch, B, ctx = env
+    ew = B.cas_encode_weight(ctx, torch.empty((0, 256), dtype=torch.int16, device="cuda"), 600, 4)
+    uw = B.cas_unary_encode(ctx, ew)
+    assert uw.desc.ue_words == 0
+    assert B.cas_unary_decode(ctx, uw, full=True).shape == (0, 256)
+    x = _dev(torch, synth.activations(256, 1, seed=1))
+    assert B.cas_gemv_draft_unary(ctx, uw, x).shape == (0,)
