@@ -79,12 +79,14 @@ __device__ __forceinline__ int lowest_bit(uint32_t m) {
   return r;
 }
 
-// Read a `width`-bit field at bit offset `bit` of a little-endian word stream (generic path).
+// Read a `width`-bit field (1..32 bits) at bit offset `bit` of a little-endian word stream
+// (generic path).  The word after the field's first one is always read as well and the two are
+// funnel-shifted: no 64-bit arithmetic, no divergent second load.  Every stream region ends
+// with slack, so the extra word is in bounds.
 __device__ __forceinline__ uint32_t read_field(const uint32_t* __restrict__ s, uint32_t bit, int width) {
-  uint32_t w = bit >> 5, sh = bit & 31;
-  uint64_t v = s[w];
-  if (sh + width > 32) v |= ((uint64_t)s[w + 1]) << 32;
-  return (uint32_t)(v >> sh) & ((1u << width) - 1u);
+  const uint32_t w = bit >> 5;
+  const uint32_t v = __builtin_amdgcn_alignbit(s[w + 1], s[w], bit & 31u);
+  return width >= 32 ? v : (v & ((1u << width) - 1u));
 }
 
 // Field i (compile-time) of `width` bits from a register window a[] whose bit 0 is field 0.

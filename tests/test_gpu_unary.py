@@ -45,6 +45,7 @@ CASES = [
     (20, 300, 1000, 7, True),
     (9, 14336, 600, 3, False),
     (300, 64, 500, 5, True),
+    (1400, 512, 600, 4, False),     # more workgroups than CUs
 ]
 
 
