@@ -206,41 +206,45 @@ __global__ __launch_bounds__(64 * kUnaryWaves) void gemv_draft_unary_kernel(Unar
   uint8_t* tab = lds8;                                           // exp_of_rank
   uint16_t* xs = reinterpret_cast<uint16_t*>(lds8 + 256);        // [bw * 32] bf16, zero beyond cols
   uint8_t* exps_all = lds8 + 256 + (size_t)a.bw * 64;           // [waves][kpad]
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (tid < 256) tab[tid] = a.table[tid];
   for (int c = tid; c < a.bw * 32; c += 64 * kUnaryWaves) xs[c] = c < a.cols ? x[c] : (uint16_t)0;
   __syncthreads();
-  const int row = blockIdx.x * kUnaryWaves + wv;
-  if (row >= a.rows) return;
   uint8_t* exps = exps_all + (size_t)wv * kpad;
-  const uint32_t o0 = a.rowoff[row], o1 = a.rowoff[row + 1];
-  unary_row_exponents(a.ue + o0, (int)(o1 - o0), a.K, tab, exps, lane);
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
   const int mb = 7 - a.t, SW = 8 - a.t;
-  const uint32_t* bm_row = a.u_bitmap + (size_t)row * a.bw;
-  const uint32_t* sm_row = a.u_sm + (size_t)row * a.smw;
-  float acc = 0.f;
-  int base = 0;
-  for (int w0 = 0; w0 < a.bw; w0 += 64) {
-    const int w = w0 + lane;
-    uint32_t m = w < a.bw ? bm_row[w] : 0u;
-    const int cnt = __popc(m);
-    const int incl = wave_incl_scan(cnt);
-    int e = base + incl - cnt;
-    base += __builtin_amdgcn_readlane(incl, 63);
-    while (m) {
-      const int pos = lowest_bit(m);
-      m &= m - 1u;
-      const uint32_t sm = read_field(sm_row, (uint32_t)e * SW, SW);
-      // fp32 pattern of the zero-padded bf16: sign, exponent, leading mantissa bits
-      const uint32_t bits = ((sm >> mb) << 31) | ((uint32_t)exps[e] << 23) | ((sm & ((1u << mb) - 1u)) << (16 + a.t));
-      acc = fmaf(__uint_as_float(bits), bf16_to_f32(xs[w * 32 + pos]), acc);
-      ++e;
+  // rows are dealt round-robin to all waves of the grid; a workgroup stages x once
+  for (int row = blockIdx.x * kUnaryWaves + wv; row < a.rows; row += gridDim.x * kUnaryWaves) {
+    const uint32_t o0 = a.rowoff[row], o1 = a.rowoff[row + 1];
+    unary_row_exponents(a.ue + o0, (int)(o1 - o0), a.K, tab, exps, lane);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t* bm_row = a.u_bitmap + (size_t)row * a.bw;
+    const uint32_t* sm_row = a.u_sm + (size_t)row * a.smw;
+    float acc = 0.f;
+    int base = 0;
+    for (int w0 = 0; w0 < a.bw; w0 += 64) {
+      const int w = w0 + lane;
+      uint32_t m = w < a.bw ? bm_row[w] : 0u;
+      const int cnt = __popc(m);
+      const int incl = wave_incl_scan(cnt);
+      int e = base + incl - cnt;
+      base += __builtin_amdgcn_readlane(incl, 63);
+      while (m) {
+        const int pos = lowest_bit(m);
+        m &= m - 1u;
+        const uint32_t sm = read_field(sm_row, (uint32_t)e * SW, SW);
+        // fp32 pattern of the zero-padded bf16: sign, exponent, leading mantissa bits
+        const uint32_t bits = ((sm >> mb) << 31) | ((uint32_t)exps[e] << 23) | ((sm & ((1u << mb) - 1u)) << (16 + a.t));
+        acc = fmaf(__uint_as_float(bits), bf16_to_f32(xs[w * 32 + pos]), acc);
+        ++e;
+      }
     }
+    acc = wave_sum(acc);
+    if (lane == 0) y[row] = acc;
+    // the next row overwrites exps[]: every lane must be done reading it
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   }
-  acc = wave_sum(acc);
-  if (lane == 0) y[row] = acc;
 }
 
 static UnaryArgs make_uargs(const cas_udesc& u, const void* spec_raw, void* uspec, const void* verif) {
@@ -432,7 +436,7 @@ extern "C" int cas_gemv_draft_unary(cas_ctx* ctx, const cas_udesc* udesc, const 
                                      (int)lds));
     raised = lds;
   }
-  const int grid = (int)((d.rows + kUnaryWaves - 1) / kUnaryWaves);
+  const int grid = (int)std::min<int64_t>((d.rows + kUnaryWaves - 1) / kUnaryWaves, (int64_t)ctx->num_cu * 8);
   hipLaunchKernelGGL(gemv_draft_unary_kernel, dim3(grid), dim3(64 * kUnaryWaves), lds, ctx->stream, a, d_x, d_y, kpad);
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;
