@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import cassandra_oracle as O
+import synth
 
 pytestmark = pytest.mark.gpu
 
@@ -102,3 +103,52 @@ def test_attention_at_bench_context_sampled_heads(env):
                 tol = 2e-3 * np.linalg.norm(pr) * np.linalg.norm(vv[:, h // 4, :], axis=0) + 2.0 ** -8 * np.abs(ref)
                 err = np.abs(O.bf16_to_f64(out[c, h]) - ref)
                 assert (err <= tol).all(), (ncols, c, h, float((err / tol).max()))
+
+
+@pytest.mark.parametrize("keep,t", [(600, 4), (1000, 0)])
+def test_speculative_stream_equals_plain_stream_at_8b_shape(env, keep, t):
+    """The model path at the shapes bench.py times (hidden 4096, 32 q / 8 kv heads, FFN 14336,
+    vocab 128256; two layers to keep the test short): greedy speculative decoding with k = 6
+    gives exactly the token stream of plain decoding (Sec. 2.2), across a page boundary of the
+    compressed cache.  With nothing pruned or truncated the draft model is the target model and
+    most drafts are accepted, so several positions are committed per round."""
+    print(f"case keep={keep} t={t}", flush=True)
+    torch, B, _ = env
+    from paper_2605_26558_amd.workload import _random_weight
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    ctx = B.Context(workspace=ws)
+    shape = synth.LlamaShape("llama3-8b-2l", 4096, 2, 32, 8, 128, 14336, 128256)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(77)
+    dims = {"wqkv": (shape.q_dim + 2 * shape.kv_dim, shape.hidden), "wo": (shape.hidden, shape.q_dim),
+            "wgu": (2 * shape.ffn, shape.hidden), "wd": (shape.hidden, shape.ffn)}
+    def gain():
+        return (1.0 + 0.1 * torch.randn(shape.hidden, device="cuda", generator=gen)).to(torch.bfloat16).view(torch.int16)
+    layers = []
+    for _l in range(shape.n_layers):
+        L = {n: B.cas_encode_weight(ctx, _random_weight(torch, r, c, gen), keep, t) for n, (r, c) in dims.items()}
+        L["g_attn"], L["g_ffn"] = gain(), gain()
+        layers.append(L)
+    head = B.cas_encode_weight(ctx, _random_weight(torch, shape.vocab, shape.hidden, gen), keep, t)
+    embed = torch.randn((shape.vocab, shape.hidden), device="cuda", generator=gen).to(torch.bfloat16).view(torch.int16)
+    rope = torch.from_numpy(synth.rope_table(512, shape.head_dim, shape.rope_theta)).cuda()
+    model = B.Model(ctx, shape, layers, head, embed, gain(), rope, max_cols=7)
+    kv = B.KVCache(ctx, shape.n_layers, shape.n_kv_heads, n_pages=8, max_seqs=1, max_pages_per_seq=8,
+                   keep_permille=keep, trunc_bits=t)
+    prompt = synth.token_ids(120, shape.vocab, seed=8)
+
+    def generate(k, n_new):
+        B.cas_kv_set_len(kv, 0, 0)
+        B.cas_prefill(ctx, model, kv, 0, torch.from_numpy(prompt[:-1].copy()).cuda())
+        pending, out, acc = int(prompt[-1]), [], []
+        while len(out) < n_new:
+            n, emitted = B.cas_spec_round(ctx, model, kv, 0, pending, k)
+            out.extend(emitted); acc.append(n); pending = emitted[-1]
+        return out[:n_new], acc
+
+    plain, _ = generate(0, 20)
+    spec, acc = generate(6, 20)
+    print("accepted per round", acc, flush=True)
+    assert spec == plain, (spec, plain)
+    assert all(0 <= tok < shape.vocab for tok in plain)
+    if keep == 1000 and t == 0:
+        assert sum(acc) >= len(acc)      # the fp32 draft and the MFMA target agree on most tokens
