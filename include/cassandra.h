@@ -346,6 +346,22 @@ int cas_accept(const int32_t* h_draft, const int32_t* h_target, int k, int32_t* 
 int cas_accept_sampling(const double* h_p, const double* h_q, const double* h_r, int gamma,
                         int32_t* n_accepted);
 
+/* Objective of the format search (Eq. 2): acceptance rate per bit the draft model reads,
+ *   J = alpha / (S_w (1 - w_p)(B - w_t) + S_kv (1 - kv_p)(B - kv_t)),
+ * with the kept fractions 1 - w_p, 1 - kv_p given in 1/1000.  Host only.  s_w, s_kv: numbers of
+ * weight and cached values; b_bits: width of the target model's values (16).  Writes J to
+ * *h_j.  CAS_EINVAL for a zero denominator or arguments out of range. */
+int cas_objective(double alpha, double s_w, int w_keep_permille, int w_trunc_bits, double s_kv,
+                  int kv_keep_permille, int kv_trunc_bits, int b_bits, double* h_j);
+
+/* Grid search of Sec. 7.2.2 over the weight format with the cache format fixed: h_alpha is
+ * [n_keep][n_trunc], the acceptance rate the caller measured for every pair (keep fraction
+ * h_keep_permille[i], truncation h_trunc_bits[j]).  Returns the indices of the pair with the
+ * largest J (the first one in row-major order among equals).  Host only. */
+int cas_tune_grid(const double* h_alpha, int n_keep, const int32_t* h_keep_permille, int n_trunc,
+                  const int32_t* h_trunc_bits, double s_w, double s_kv, int kv_keep_permille,
+                  int kv_trunc_bits, int b_bits, int32_t* best_keep_index, int32_t* best_trunc_index);
+
 #ifdef __cplusplus
 }
 #endif

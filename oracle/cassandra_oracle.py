@@ -612,6 +612,24 @@ def accept_sampling(p_target, q_draft, r):
     return min(cands)
 
 
+def objective_j(alpha, s_w, w_keep, w_t, s_kv, kv_keep, kv_t, b_bits=BF16_BITS):
+    """Eq. 2: acceptance rate per bit read by the draft model.  w_keep, kv_keep are the kept
+    fractions 1 - w_p, 1 - kv_p."""
+    return alpha / (s_w * w_keep * (b_bits - w_t) + s_kv * kv_keep * (b_bits - kv_t))
+
+
+def tune_grid(alpha, keeps, truncs, s_w, s_kv, kv_keep, kv_t, b_bits=BF16_BITS):
+    """Grid search of Sec. 7.2.2 over the weight format: the pair with the largest J, the first
+    one in row-major order among equals."""
+    best, arg = -1.0, None
+    for i, kp in enumerate(keeps):
+        for j, t in enumerate(truncs):
+            v = objective_j(alpha[i][j], s_w, kp, t, s_kv, kv_keep, kv_t, b_bits)
+            if v > best:
+                best, arg = v, (i, j)
+    return arg
+
+
 def prefill(model: OracleModel, prompt):
     """Fill the cache for prompt[:-1] with the target model; prompt[-1] stays pending."""
     if len(prompt) > 1:

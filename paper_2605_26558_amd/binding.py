@@ -116,6 +116,11 @@ _SIGNATURES = {
                                       C.POINTER(C.c_int32)]),
     "cas_accept": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32),
                              C.POINTER(C.c_int32)]),
+    "cas_objective": (C.c_int, [C.c_double, C.c_double, C.c_int, C.c_int, C.c_double, C.c_int, C.c_int, C.c_int,
+                                C.POINTER(C.c_double)]),
+    "cas_tune_grid": (C.c_int, [C.POINTER(C.c_double), C.c_int, C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32),
+                                C.c_double, C.c_double, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32),
+                                C.POINTER(C.c_int32)]),
     "cas_unary_plan": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.POINTER(cas_udesc)]),
     "cas_unary_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p]),
     "cas_unary_decode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
@@ -225,6 +230,29 @@ def cas_encode_weight(ctx: Context, W, keep_permille, trunc_bits, act_norm=None)
     ctx._check(_lib().cas_encode_weight(ctx.h, _ptr(W), W.stride(0), _ptr(act_norm), C.byref(d), _ptr(spec),
                                         _ptr(verif)), "cas_encode_weight")
     return EncodedWeight(d, spec, verif)
+
+
+def cas_objective(alpha, s_w, w_keep_permille, w_trunc_bits, s_kv, kv_keep_permille, kv_trunc_bits, b_bits=16):
+    j = C.c_double()
+    rc = _lib().cas_objective(alpha, s_w, w_keep_permille, w_trunc_bits, s_kv, kv_keep_permille, kv_trunc_bits, b_bits,
+                              C.byref(j))
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_objective")
+    return j.value
+
+
+def cas_tune_grid(alpha, keep_permille, trunc_bits, s_w, s_kv, kv_keep_permille, kv_trunc_bits, b_bits=16):
+    """alpha: [len(keep_permille)][len(trunc_bits)] nested sequence; returns (keep index, trunc index)."""
+    nk, nt = len(keep_permille), len(trunc_bits)
+    flat = (C.c_double * (nk * nt))(*[float(alpha[i][j]) for i in range(nk) for j in range(nt)])
+    kp = (C.c_int32 * nk)(*keep_permille)
+    tb = (C.c_int32 * nt)(*trunc_bits)
+    bi, bj = C.c_int32(), C.c_int32()
+    rc = _lib().cas_tune_grid(flat, nk, kp, nt, tb, s_w, s_kv, kv_keep_permille, kv_trunc_bits, b_bits,
+                              C.byref(bi), C.byref(bj))
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_tune_grid")
+    return bi.value, bj.value
 
 
 class UnaryWeight:

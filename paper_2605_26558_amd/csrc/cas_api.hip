@@ -284,4 +284,40 @@ int cas_accept_sampling(const double* h_p, const double* h_q, const double* h_r,
   return CAS_OK;
 }
 
+int cas_objective(double alpha, double s_w, int w_keep_permille, int w_trunc_bits, double s_kv,
+                  int kv_keep_permille, int kv_trunc_bits, int b_bits, double* h_j) {
+  if (!h_j || !(alpha >= 0.0) || !(s_w >= 0.0) || !(s_kv >= 0.0) || b_bits < 1) return CAS_EINVAL;
+  if (w_keep_permille < 0 || w_keep_permille > 1000 || kv_keep_permille < 0 || kv_keep_permille > 1000)
+    return CAS_EINVAL;
+  if (w_trunc_bits < 0 || w_trunc_bits > b_bits || kv_trunc_bits < 0 || kv_trunc_bits > b_bits) return CAS_EINVAL;
+  const double den = s_w * (w_keep_permille / 1000.0) * (double)(b_bits - w_trunc_bits) +
+                     s_kv * (kv_keep_permille / 1000.0) * (double)(b_bits - kv_trunc_bits);
+  if (!(den > 0.0)) return CAS_EINVAL;
+  *h_j = alpha / den;
+  return CAS_OK;
+}
+
+int cas_tune_grid(const double* h_alpha, int n_keep, const int32_t* h_keep_permille, int n_trunc,
+                  const int32_t* h_trunc_bits, double s_w, double s_kv, int kv_keep_permille, int kv_trunc_bits,
+                  int b_bits, int32_t* best_keep_index, int32_t* best_trunc_index) {
+  if (!h_alpha || !h_keep_permille || !h_trunc_bits || !best_keep_index || !best_trunc_index || n_keep < 1 ||
+      n_trunc < 1)
+    return CAS_EINVAL;
+  double best = -1.0;
+  for (int i = 0; i < n_keep; ++i) {
+    for (int j = 0; j < n_trunc; ++j) {
+      double v;
+      int rc = cas_objective(h_alpha[(size_t)i * n_trunc + j], s_w, h_keep_permille[i], h_trunc_bits[j], s_kv,
+                             kv_keep_permille, kv_trunc_bits, b_bits, &v);
+      if (rc != CAS_OK) return rc;
+      if (v > best) {
+        best = v;
+        *best_keep_index = i;
+        *best_trunc_index = j;
+      }
+    }
+  }
+  return CAS_OK;
+}
+
 }  // extern "C"

@@ -46,3 +46,31 @@ def test_host_only_calls_work_without_a_gpu():
         B.cas_weight_desc(8, 8, 600, 9)
     with pytest.raises(B.CasError):
         B.cas_weight_desc(8, 8, 600, 4, exp_mode=1)
+
+
+def test_objective_and_grid_search_against_oracle_and_closed_forms():
+    """Eq. 2 and the grid search of Sec. 7.2.2 (host-only entry points): the value printed
+    for the default configuration, scaling laws of the formula, and the oracle on random grids."""
+    import numpy as np
+    from oracle import cassandra_oracle as O
+    from paper_2605_26558_amd import binding as B
+    # default configuration, 4096 weights, no cache term: 4096 * 0.6 * 12 = 29491.2 bits (golden file)
+    j = B.cas_objective(1.0, 4096.0, 600, 4, 0.0, 600, 4)
+    assert abs(1.0 / j - 29491.2) < 1e-9
+    assert abs(O.objective_j(1.0, 4096.0, 0.6, 4, 0.0, 0.6, 4) - j) < 1e-18
+    # linear in alpha; halving every size doubles J; nothing truncated, nothing pruned = B bits per value
+    assert abs(B.cas_objective(0.5, 4096.0, 600, 4, 100.0, 500, 2) * 2 - B.cas_objective(1.0, 4096.0, 600, 4, 100.0, 500, 2)) < 1e-18
+    assert abs(B.cas_objective(0.7, 2048.0, 600, 4, 50.0, 500, 2) - 2 * B.cas_objective(0.7, 4096.0, 600, 4, 100.0, 500, 2)) < 1e-18
+    assert abs(1.0 / B.cas_objective(1.0, 10.0, 1000, 0, 6.0, 1000, 0) - 16 * 16.0) < 1e-12
+    rng = np.random.Generator(np.random.Philox(4))
+    keeps, truncs = [700, 600, 500, 400], [0, 1, 2, 3, 4, 5]          # the grid of Sec. 7.2.2
+    for _ in range(50):
+        alpha = rng.uniform(0.2, 0.95, size=(4, 6))
+        s_w, s_kv = float(rng.integers(1, 10**6)), float(rng.integers(0, 10**6))
+        got = B.cas_tune_grid(alpha.tolist(), keeps, truncs, s_w, s_kv, 600, 4)
+        ref = O.tune_grid(alpha, [k / 1000.0 for k in keeps], truncs, s_w, s_kv, 0.6, 4)
+        vals = np.array([[O.objective_j(alpha[i][j], s_w, keeps[i] / 1000.0, truncs[j], s_kv, 0.6, 4)
+                          for j in range(6)] for i in range(4)])
+        assert got == ref == tuple(int(v) for v in np.unravel_index(np.argmax(vals), vals.shape))
+    with __import__("pytest").raises(B.CasError):
+        B.cas_objective(1.0, 0.0, 600, 4, 0.0, 600, 4)
