@@ -53,10 +53,28 @@ struct Cursor {  // walks the (row, chunk) items of one wave in order
 constexpr int kGemvThreads = 1024;  // 16 waves share one staged copy of x
 constexpr int kGemvWaves = kGemvThreads / 64;
 
-template <int T, int NB>
+// x in LDS: fp32, or bf16 bit patterns (XH) when a batch of wide rows would not fit as fp32;
+// the staged values are bf16-representable either way, XH costs one shift per use
+template <bool XH>
+struct XStage {
+  using type = float;
+  static __device__ __forceinline__ float put(float v) { return v; }
+  static __device__ __forceinline__ float get(float v) { return v; }
+};
+template <>
+struct XStage<true> {
+  using type = uint16_t;
+  static __device__ __forceinline__ uint16_t put(float v) { return (uint16_t)(__float_as_uint(v) >> 16); }
+  static __device__ __forceinline__ float get(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+};
+
+template <int T, int NB, bool XH>
 __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   constexpr int FW = 16 - T;
-  extern __shared__ float xs[];
+  using XS = XStage<XH>;
+  using XT = typename XS::type;
+  extern __shared__ uint8_t xs_raw[];
+  XT* xs = reinterpret_cast<XT*>(xs_raw);
   const int tid = threadIdx.x;
   const int nchunk = (a.bw + 63) >> 6;
   const int nseg = nchunk * 64;
@@ -100,15 +118,15 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
 #pragma unroll
     for (int j = 0; j < FW; ++j) win[j] = __builtin_amdgcn_alignbit(w.d[j + 1], w.d[j], w.sh);
     uint32_t m = w.m;
-    const float* xb = xs + ((c.chunk * 64 + lane) * 33 + 1) * NB;
+    const XT* xb = xs + ((c.chunk * 64 + lane) * 33 + 1) * NB;
     auto step = [&](auto I) {
       constexpr int i = decltype(I)::value;
       int pos = lowest_bit(m);
       m &= m - 1u;
       float f = __uint_as_float(field_top<FW, i>(win));
-      const float* xp = xb + pos * NB;
+      const XT* xp = xb + pos * NB;
 #pragma unroll
-      for (int b = 0; b < NB; ++b) acc[b] = fmaf(f, xp[b], acc[b]);
+      for (int b = 0; b < NB; ++b) acc[b] = fmaf(f, XS::get(xp[b]), acc[b]);
     };
     // the first 16 set bits unconditionally, then pairs until every lane has run out
     static_for<0, 16>(step);
@@ -170,7 +188,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   auto stage_x = [&]() {
     for (int sgi = tid; sgi < nseg; sgi += kGemvThreads) {
 #pragma unroll
-      for (int b = 0; b < NB; ++b) xs[sgi * 33 * NB + b] = 0.f;
+      for (int b = 0; b < NB; ++b) xs[sgi * 33 * NB + b] = XS::put(0.f);
     }
     float rn[NB];
 #pragma unroll
@@ -216,7 +234,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
         const int col = piece * 8;
         if (piece < npiece) {
           const uint32_t gw4[4] = {gv[k].x, gv[k].y, gv[k].z, gv[k].w};
-          float* dst = xs + ((col >> 5) * 33 + 1 + (col & 31)) * NB;
+          XT* dst = xs + ((col >> 5) * 33 + 1 + (col & 31)) * NB;
 #pragma unroll
           for (int b = 0; b < NB; ++b) {
             const uint32_t wd[4] = {raw[k][b].x, raw[k][b].y, raw[k][b].z, raw[k][b].w};
@@ -227,8 +245,8 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
                 lo = round_bf16(lo * rn[b] * __uint_as_float(gw4[e] << 16));
                 hi = round_bf16(hi * rn[b] * __uint_as_float(gw4[e] & 0xFFFF0000u));
               }
-              dst[(2 * e) * NB + b] = lo;
-              dst[(2 * e + 1) * NB + b] = hi;
+              dst[(2 * e) * NB + b] = XS::put(lo);
+              dst[(2 * e + 1) * NB + b] = XS::put(hi);
             }
           }
         }
@@ -254,7 +272,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
             v = bf16_to_f32(a.x[(size_t)b * a.cols + col]);
             if (a.gain) v = round_bf16(v * rn[b] * bf16_to_f32(a.gain[col]));
           }
-          xs[((col >> 5) * 33 + 1 + (col & 31)) * NB + b] = v;
+          xs[((col >> 5) * 33 + 1 + (col & 31)) * NB + b] = XS::put(v);
         }
       }
     }
@@ -283,20 +301,20 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   }
 }
 
-template <int T>
+template <int T, bool XH>
 static int launch_t(cas_ctx* ctx, const GemvArgs& a, int batch, int grid, size_t lds) {
 #define CAS_LAUNCH(NBV)                                                                                      \
   do {                                                                                                       \
-    static size_t raised = 48 * 1024;                                                                              \
-    if (lds > raised) {                                                                        \
-      CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_kernel<T, NBV>,                               \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));           \
+    static size_t raised = 48 * 1024;                                                                        \
+    if (lds > raised) {                                                                                      \
+      CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_kernel<T, NBV, XH>,                           \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));               \
       raised = lds;                                                                                          \
     }                                                                                                        \
-    hipLaunchKernelGGL((gemv_draft_kernel<T, NBV>), dim3(grid), dim3(kGemvThreads), lds, ctx->stream, a);             \
+    hipLaunchKernelGGL((gemv_draft_kernel<T, NBV, XH>), dim3(grid), dim3(kGemvThreads), lds, ctx->stream, a); \
   } while (0)
   switch (batch) {
-    case 1: CAS_LAUNCH(1); break;
+    case 1: if constexpr (XH) return CAS_EINVAL; else CAS_LAUNCH(1); break;  // one column always fits as fp32
     case 2: CAS_LAUNCH(2); break;
     case 3: CAS_LAUNCH(3); break;
     case 4: CAS_LAUNCH(4); break;
@@ -321,7 +339,10 @@ int launch_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec, 
   a.bitmap = (const uint32_t*)((const char*)spec + d.off_bitmap);
   a.spec = (const uint32_t*)((const char*)spec + d.off_spec);
   a.x = x; a.y = y;
+  // x as fp32 when it fits the LDS, else (a batch of wide rows) as bf16
   size_t lds = sizeof(float) * (size_t)((d.bw + 63) / 64 * 64) * 33 * batch;
+  const bool xh = lds > (size_t)ctx->lds_max && batch > 1;
+  if (xh) lds /= 2;
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
   // one or two workgroups per CU (two fill its 32 wave slots), whichever leaves the most
   // loaded CU with fewer rows; all of them are resident at once
@@ -335,16 +356,11 @@ int launch_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec, 
   }
   a.nwaves = grid * kGemvWaves;
   ProfScope prof(ctx, PROF_GEMV_DRAFT, 4.0 * (double)d.rows * (d.bw + d.sw));
+#define CAS_T(TV) case TV: return xh ? launch_t<TV, true>(ctx, a, batch, grid, lds) : launch_t<TV, false>(ctx, a, batch, grid, lds);
   switch (d.t) {
-    case 0: return launch_t<0>(ctx, a, batch, grid, lds);
-    case 1: return launch_t<1>(ctx, a, batch, grid, lds);
-    case 2: return launch_t<2>(ctx, a, batch, grid, lds);
-    case 3: return launch_t<3>(ctx, a, batch, grid, lds);
-    case 4: return launch_t<4>(ctx, a, batch, grid, lds);
-    case 5: return launch_t<5>(ctx, a, batch, grid, lds);
-    case 6: return launch_t<6>(ctx, a, batch, grid, lds);
-    case 7: return launch_t<7>(ctx, a, batch, grid, lds);
+    CAS_T(0) CAS_T(1) CAS_T(2) CAS_T(3) CAS_T(4) CAS_T(5) CAS_T(6) CAS_T(7)
   }
+#undef CAS_T
   return CAS_EINVAL;
 }
 

@@ -76,7 +76,7 @@ def _tol(W, X):
 
 
 @pytest.mark.parametrize("rows,cols,keep,t,act", CASES)
-@pytest.mark.parametrize("batch", [1, 3])
+@pytest.mark.parametrize("batch", [1, 3, 4])
 def test_gemv_draft_matches_oracle(env, rows, cols, keep, t, act, batch):
     torch, B, ctx = env
     print(f"case rows={rows} cols={cols} keep={keep} t={t} batch={batch}", flush=True)
