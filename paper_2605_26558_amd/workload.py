@@ -292,6 +292,38 @@ class ModelRoundWorkload:
         t_plain = timed(lambda: B.cas_verify_step(ctx, self.model, self.kv, 0, tok[:1], 0, out[:1]))
         return t_draft, t_verify, t_plain
 
+    def _forced_rounds(self, alpha, rounds=48, seed=11):
+        """Tokens/s of whole rounds (k draft passes, verification, read-back of the targets,
+        commit with the online KV encoder) when the number of accepted drafts is FORCED by a
+        seeded Bernoulli(alpha) schedule instead of comparing tokens: synthetic acceptance,
+        real work (the random-init model itself accepts nothing)."""
+        import time
+        import numpy as np
+        torch, B, ctx, k = self.torch, self.B, self.ctx, self.k
+        rng = np.random.Generator(np.random.Philox(seed))
+        tok = torch.ones(k + 1, dtype=torch.int32, device="cuda")
+        out = torch.empty(k + 1, dtype=torch.int32, device="cuda")
+
+        def one_round():
+            for i in range(k):
+                B.cas_draft_step(ctx, self.model, self.kv, 0, tok[i:i + 1], i, out[i:i + 1])
+            B.cas_verify_step(ctx, self.model, self.kv, 0, tok, k, out)
+            out.cpu()                                   # the host needs the target tokens to accept
+            draws = rng.random(k) < alpha
+            n = k if draws.all() else int(np.argmin(draws))
+            B.cas_commit(ctx, self.model, self.kv, 0, n)
+            return n + 1
+
+        one_round()
+        B.cas_kv_set_len(self.kv, 0, self.ctx_len)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        tokens = sum(one_round() for _ in range(rounds))
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        B.cas_kv_set_len(self.kv, 0, self.ctx_len)
+        return {"tokens_per_s": tokens / dt, "tokens_per_round": tokens / rounds, "rounds": rounds}
+
     def extra(self, ms_per_step):
         t_draft, t_verify, t_plain = self._time_passes()
         k = self.k
@@ -329,6 +361,8 @@ class ModelRoundWorkload:
                "context_vendor_bf16_gemv_pass_ms": t_bf16,
                "context_vendor_bf16_gemv_GBps": None if t_bf16 is None else 2.0 * self.values / (t_bf16 * 1e-3) / 1e9,
                "tokens_per_s_at_assumed_acceptance": synth_tps,
+               "tokens_per_s_forced_acceptance_schedule": {f"alpha={a}": self._forced_rounds(a)
+                                                           for a in (0.6, 0.8, 1.0)},
                "kernels": {}}
         for name, (n, ms, by) in self.prof.items():
             if n:
