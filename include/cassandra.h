@@ -269,6 +269,8 @@ typedef struct {
   int32_t max_cols; /* largest k+1 (1..16); also the number of in-flight K/V slots per layer */
   int32_t max_pos;  /* rows of the rotary table */
   float rms_eps;
+  int32_t max_seqs; /* sequences that may have positions in flight at once (0 means 1): every
+                       one owns max_cols in-flight K/V slots per layer; sequence ids are < max_seqs */
 } cas_model_cfg;
 
 /* One encoded linear layer: layout + the two device buffers (caller-owned). */
@@ -319,6 +321,19 @@ int cas_draft_step(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const in
 int cas_verify_step(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const int32_t* d_tokens,
                     int k, int32_t* d_target, float* d_logits);
 
+/* The same passes for several sequences at once (low-batch serving, Sec. 1): the linear
+ * layers read their weights once for all columns, attention runs per sequence over its own
+ * cache.  h_seqs: n_seqs distinct sequence ids (host).  Draft: one column per sequence, n_seqs
+ * in 1..4, h_slots[i] = in-flight slot of sequence i's token, d_tokens_in / d_tokens_out:
+ * int32 [n_seqs] (device).  Verification: h_k[i] drafts of sequence i, i.e. h_k[i] + 1 columns;
+ * the columns of all sequences, sequence after sequence, are d_tokens / d_target (device);
+ * their total is at most max_cols.  Every sequence gets exactly the values the one-sequence
+ * calls give it.  Accept and cas_commit stay per sequence. */
+int cas_draft_step_multi(cas_ctx* ctx, cas_model* model, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
+                         const int32_t* h_slots, const int32_t* d_tokens_in, int32_t* d_tokens_out);
+int cas_verify_step_multi(cas_ctx* ctx, cas_model* model, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
+                          const int32_t* h_k, const int32_t* d_tokens, int32_t* d_target);
+
 /* After acceptance: format and append the target K/V of the pending token and the n_accepted
  * accepted drafts (slots 0..n_accepted) to every layer of the cache, advance the length by
  * n_accepted + 1, drop the remaining slots. */
@@ -329,6 +344,13 @@ int cas_commit(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, int n_accept
  * tokens.  h_out receives n_accepted + 1 tokens; the last one is the next pending token. */
 int cas_spec_round(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, int32_t pending, int k,
                    int32_t* h_out, int32_t* n_accepted);
+
+/* One speculative round for n_seqs sequences at once (1..4, (k + 1) * n_seqs <= max_cols):
+ * k multi-sequence draft passes, one multi-sequence verification pass, greedy acceptance and
+ * commit per sequence.  h_pending: the pending token of every sequence; h_out: [n_seqs][k+1],
+ * row s receives the h_n_accepted[s] + 1 tokens emitted for sequence s. */
+int cas_spec_round_multi(cas_ctx* ctx, cas_model* model, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
+                         const int32_t* h_pending, int k, int32_t* h_out, int32_t* h_n_accepted);
 
 /* Prefill (functional): runs n prompt tokens through the target path in chunks of max_cols
  * columns and commits all of them.  d_tokens: int32 [n] on the device. */

@@ -50,7 +50,7 @@ class cas_kv_desc(C.Structure):
 class cas_model_cfg(C.Structure):
     _fields_ = [("hidden", C.c_int32), ("n_layers", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32),
-                ("max_cols", C.c_int32), ("max_pos", C.c_int32), ("rms_eps", C.c_float)]
+                ("max_cols", C.c_int32), ("max_pos", C.c_int32), ("rms_eps", C.c_float), ("max_seqs", C.c_int32)]
 
 
 class cas_tensor(C.Structure):
@@ -109,8 +109,14 @@ _SIGNATURES = {
     "cas_verify_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
                                   C.c_void_p]),
     "cas_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
+    "cas_draft_step_multi": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]),
+    "cas_verify_step_multi": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]),
     "cas_spec_round": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int,
                                  C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "cas_spec_round_multi": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "cas_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int]),
     "cas_accept_sampling": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int,
                                       C.POINTER(C.c_int32)]),
@@ -451,12 +457,12 @@ class Model:
     g_attn, g_ffn; lm_head: EncodedWeight; embed, g_final: bf16-bit tensors; rope: float32
     tensor [max_pos, 64, 2]."""
 
-    def __init__(self, ctx: Context, shape, layers, lm_head, embed, g_final, rope, max_cols):
+    def __init__(self, ctx: Context, shape, layers, lm_head, embed, g_final, rope, max_cols, max_seqs=1):
         torch = ctx._torch
         self.ctx, self.shape = ctx, shape
         self._keep = (layers, lm_head, embed, g_final, rope)
         cfg = cas_model_cfg(shape.hidden, len(layers), shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
-                            shape.ffn, shape.vocab, max_cols, rope.shape[0], shape.rms_eps)
+                            shape.ffn, shape.vocab, max_cols, rope.shape[0], shape.rms_eps, max_seqs)
         self.cfg = cfg
         nbytes = C.c_size_t()
         rc = _lib().cas_model_act_bytes(C.byref(cfg), C.byref(nbytes))
@@ -496,6 +502,18 @@ def cas_verify_step(ctx, model: Model, kv: KVCache, seq, tokens, k, target, logi
                "cas_verify_step")
 
 
+def cas_draft_step_multi(ctx, model: Model, kv: KVCache, seqs, slots, tokens_in, tokens_out):
+    n = len(seqs)
+    ctx._check(_lib().cas_draft_step_multi(ctx.h, model.h, kv.h, n, (C.c_int32 * n)(*seqs), (C.c_int32 * n)(*slots),
+                                           _ptr(tokens_in), _ptr(tokens_out)), "cas_draft_step_multi")
+
+
+def cas_verify_step_multi(ctx, model: Model, kv: KVCache, seqs, ks, tokens, target):
+    n = len(seqs)
+    ctx._check(_lib().cas_verify_step_multi(ctx.h, model.h, kv.h, n, (C.c_int32 * n)(*seqs), (C.c_int32 * n)(*ks),
+                                            _ptr(tokens), _ptr(target)), "cas_verify_step_multi")
+
+
 def cas_commit(ctx, model: Model, kv: KVCache, seq, n_accepted):
     ctx._check(_lib().cas_commit(ctx.h, model.h, kv.h, seq, n_accepted), "cas_commit")
 
@@ -505,6 +523,17 @@ def cas_spec_round(ctx, model: Model, kv: KVCache, seq, pending, k):
     n = C.c_int32()
     ctx._check(_lib().cas_spec_round(ctx.h, model.h, kv.h, seq, int(pending), k, out, C.byref(n)), "cas_spec_round")
     return n.value, [out[i] for i in range(n.value + 1)]
+
+
+def cas_spec_round_multi(ctx, model: Model, kv: KVCache, seqs, pending, k):
+    """Returns a list of (n_accepted, emitted tokens) per sequence."""
+    n = len(seqs)
+    out = (C.c_int32 * (n * (k + 1)))()
+    acc = (C.c_int32 * n)()
+    ctx._check(_lib().cas_spec_round_multi(ctx.h, model.h, kv.h, n, (C.c_int32 * n)(*seqs),
+                                           (C.c_int32 * n)(*[int(p) for p in pending]), k, out, acc),
+               "cas_spec_round_multi")
+    return [(acc[s], [out[s * (k + 1) + i] for i in range(acc[s] + 1)]) for s in range(n)]
 
 
 def cas_prefill(ctx, model: Model, kv: KVCache, seq, tokens):

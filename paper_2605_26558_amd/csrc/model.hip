@@ -138,27 +138,48 @@ __global__ __launch_bounds__(64) void argmax_final_kernel(const float* __restric
   if (threadIdx.x == 0) out[c] = idx == 0x7FFFFFFF ? 0 : idx;
 }
 
+// tokens [steps][n_seqs] -> [n_seqs][steps]
+__global__ void transpose_tokens_kernel(const int32_t* __restrict__ in, int32_t* __restrict__ out, int steps, int n_seqs) {
+  const int i = threadIdx.x;
+  if (i < steps * n_seqs) out[(i % n_seqs) * steps + i / n_seqs] = in[i];
+}
+
 #define CAS_TRY(expr)            \
   do {                           \
     int rc__ = (expr);           \
     if (rc__ != CAS_OK) return rc__; \
   } while (0)
 
-// Runs `ncols` columns (token ids on the device) through the model.  slot0: index of the
-// first column among the in-flight positions of the sequence (its position is len + slot0).
-static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_tokens, int ncols, bool full,
-                   int slot0, int32_t* d_out, float* d_logits) {
+// A run of consecutive columns that belong to one sequence.  slot0: index of the run's first
+// column among the in-flight positions of the sequence (its position is len + slot0).
+struct ColGroup {
+  int seq, ncols, slot0;
+};
+
+static int model_seqs(const cas_model_cfg& c) { return c.max_seqs > 0 ? c.max_seqs : 1; }
+
+// Runs the columns of `ng` groups (token ids on the device, group after group) through the
+// model in one pass: the linear layers see all columns at once, attention runs per sequence.
+static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, int ng, const int32_t* d_tokens,
+                   bool full, int32_t* d_out, float* d_logits) {
   const cas_model_cfg& c = m->cfg;
   const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
-  const int pos0 = kv->h_len[seq] + slot0;
-  if (pos0 + ncols > c.max_pos || slot0 + ncols > c.max_cols) return CAS_EINVAL;
+  int ncols = 0;
+  for (int i = 0; i < ng; ++i) {
+    const ColGroup& g = grp[i];
+    if (g.seq < 0 || g.seq >= kv->desc.max_seqs || g.seq >= model_seqs(c) || g.ncols < 1 || g.slot0 < 0)
+      return CAS_EINVAL;
+    if (kv->h_len[g.seq] + g.slot0 + g.ncols > c.max_pos || g.slot0 + g.ncols > c.max_cols) return CAS_EINVAL;
+    for (int j = 0; j < i; ++j)
+      if (grp[j].seq == g.seq) return CAS_EINVAL;  // one run per sequence and pass
+    ncols += g.ncols;
+  }
+  if (ncols < 1 || ncols > c.max_cols || (!full && ncols > 4)) return CAS_EINVAL;
   hipStream_t st = ctx->stream;
   float* logits = d_logits ? d_logits : m->logits;
   hipLaunchKernelGGL(embed_kernel, dim3(ncols), dim3(256), 0, st, d_tokens, m->d_embed, m->h, c.hidden, c.vocab);
   for (int l = 0; l < c.n_layers; ++l) {
     const cas_layer_weights& L = m->layers[l];
-    uint16_t* kn = m->knew + (size_t)l * c.max_cols * kvd;
-    uint16_t* vn = m->vnew + (size_t)l * c.max_cols * kvd;
     // the draft pass fuses the norms, residual adds and SwiGLU into its GEMV launches
     if (full) {
       hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(kNormThreads), 0, st, m->h, L.d_g_attn, m->xn, c.hidden, c.rms_eps);
@@ -169,12 +190,18 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_
     }
     // the attention kernel splits the projection itself: bf16 rounding, rotary embedding of q and
     // k, and the copy of this pass's k, v into their in-flight slots
-    AttnCall ac;
-    ac.layer = l; ac.seq = seq; ac.full = full ? 1 : 0;
-    ac.Q = m->q; ac.ncols = ncols; ac.n_q_heads = c.n_q_heads;
-    ac.Knew = kn; ac.Vnew = vn; ac.n_new = slot0 + ncols; ac.O = m->ao;
-    ac.qkv = m->y; ac.ystride = qd + 2 * kvd; ac.slot0 = slot0; ac.rope = m->d_rope; ac.Kslot = kn; ac.Vslot = vn;
-    CAS_TRY(launch_attention(ctx, kv, ac));
+    for (int i = 0, c0 = 0; i < ng; c0 += grp[i].ncols, ++i) {
+      const ColGroup& g = grp[i];
+      const size_t slots = ((size_t)g.seq * c.n_layers + l) * c.max_cols * kvd;  // in-flight K/V of (sequence, layer)
+      AttnCall ac;
+      ac.layer = l; ac.seq = g.seq; ac.full = full ? 1 : 0;
+      ac.Q = m->q; ac.ncols = g.ncols; ac.n_q_heads = c.n_q_heads;
+      ac.Knew = m->knew + slots; ac.Vnew = m->vnew + slots; ac.n_new = g.slot0 + g.ncols;
+      ac.O = m->ao + (size_t)c0 * qd;
+      ac.qkv = m->y + (size_t)c0 * (qd + 2 * kvd); ac.ystride = qd + 2 * kvd; ac.slot0 = g.slot0; ac.rope = m->d_rope;
+      ac.Kslot = m->knew + slots; ac.Vslot = m->vnew + slots;
+      CAS_TRY(launch_attention(ctx, kv, ac));
+    }
     if (full) {
       // residual adds and SwiGLU ride in the epilogue of the verification GEMM
       CAS_TRY(launch_gemm_verify_fused(ctx, L.wo.desc, L.wo.d_spec, L.wo.d_verif, m->ao, ncols, nullptr, 1, m->h));
@@ -225,11 +252,11 @@ static ActLayout act_layout(const cas_model_cfg& c) {
   L.q = carve(off, nc * qd * 2);
   L.ao = carve(off, nc * qd * 2);
   L.act = carve(off, nc * c.ffn * 2);
-  L.knew = carve(off, (size_t)c.n_layers * nc * kvd * 2);
-  L.vnew = carve(off, (size_t)c.n_layers * nc * kvd * 2);
+  L.knew = carve(off, (size_t)model_seqs(c) * c.n_layers * nc * kvd * 2);
+  L.vnew = carve(off, (size_t)model_seqs(c) * c.n_layers * nc * kvd * 2);
   L.y = carve(off, nc * ymax * 4);
   L.logits = carve(off, nc * (size_t)c.vocab * 4);
-  L.tok = carve(off, (nc + 1) * 4);
+  L.tok = carve(off, (2 * nc + 2) * 4);  // draft tokens step-major, then the same sequence-major
   L.tgt = carve(off, (nc + 1) * 4);
   L.amax_v = carve(off, nc * kArgmaxSlices * 4);
   L.amax_i = carve(off, nc * kArgmaxSlices * 4);
@@ -242,6 +269,7 @@ static int check_cfg(const cas_model_cfg* c) {
     return CAS_EINVAL;
   if (c->head_dim != 128) return CAS_ENOTSUP;
   if (c->n_q_heads % c->n_kv_heads != 0 || c->max_cols < 1 || c->max_cols > 16 || c->max_pos < 1) return CAS_EINVAL;
+  if (c->max_seqs < 0 || c->max_seqs > 64) return CAS_EINVAL;
   if (c->max_cols * (c->n_q_heads / c->n_kv_heads) > 80 || c->n_q_heads / c->n_kv_heads > 48) return CAS_EINVAL;
   return CAS_OK;
 }
@@ -303,7 +331,7 @@ int cas_model_destroy(cas_model* m) {
 }
 
 static int check_step(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq) {
-  if (!ctx || !m || !kv || seq < 0 || seq >= kv->desc.max_seqs) return CAS_EINVAL;
+  if (!ctx || !m || !kv || seq < 0 || seq >= kv->desc.max_seqs || seq >= cas::model_seqs(m->cfg)) return CAS_EINVAL;
   if (kv->desc.n_layers != m->cfg.n_layers || kv->desc.n_kv_heads != m->cfg.n_kv_heads) return CAS_EINVAL;
   return CAS_OK;
 }
@@ -311,13 +339,37 @@ static int check_step(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq) {
 int cas_draft_step(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_token_in, int slot,
                    int32_t* d_token_out, float* d_logits) {
   if (check_step(ctx, m, kv, seq) != CAS_OK || !d_token_in || !d_token_out || slot < 0) return CAS_EINVAL;
-  return cas::forward(ctx, m, kv, seq, d_token_in, 1, false, slot, d_token_out, d_logits);
+  const cas::ColGroup g{seq, 1, slot};
+  return cas::forward(ctx, m, kv, &g, 1, d_token_in, false, d_token_out, d_logits);
 }
 
 int cas_verify_step(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_tokens, int k,
                     int32_t* d_target, float* d_logits) {
   if (check_step(ctx, m, kv, seq) != CAS_OK || !d_tokens || k < 0) return CAS_EINVAL;
-  return cas::forward(ctx, m, kv, seq, d_tokens, k + 1, true, 0, d_target, d_logits);
+  const cas::ColGroup g{seq, k + 1, 0};
+  return cas::forward(ctx, m, kv, &g, 1, d_tokens, true, d_target, d_logits);
+}
+
+int cas_draft_step_multi(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
+                         const int32_t* h_slots, const int32_t* d_tokens_in, int32_t* d_tokens_out) {
+  if (!ctx || !m || !kv || n_seqs < 1 || n_seqs > 4 || !h_seqs || !h_slots || !d_tokens_in || !d_tokens_out)
+    return CAS_EINVAL;
+  if (kv->desc.n_layers != m->cfg.n_layers || kv->desc.n_kv_heads != m->cfg.n_kv_heads) return CAS_EINVAL;
+  cas::ColGroup g[4];
+  for (int i = 0; i < n_seqs; ++i) g[i] = cas::ColGroup{h_seqs[i], 1, h_slots[i]};
+  return cas::forward(ctx, m, kv, g, n_seqs, d_tokens_in, false, d_tokens_out, nullptr);
+}
+
+int cas_verify_step_multi(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
+                          const int32_t* h_k, const int32_t* d_tokens, int32_t* d_target) {
+  if (!ctx || !m || !kv || n_seqs < 1 || n_seqs > 16 || !h_seqs || !h_k || !d_tokens || !d_target) return CAS_EINVAL;
+  if (kv->desc.n_layers != m->cfg.n_layers || kv->desc.n_kv_heads != m->cfg.n_kv_heads) return CAS_EINVAL;
+  cas::ColGroup g[16];
+  for (int i = 0; i < n_seqs; ++i) {
+    if (h_k[i] < 0) return CAS_EINVAL;
+    g[i] = cas::ColGroup{h_seqs[i], h_k[i] + 1, 0};
+  }
+  return cas::forward(ctx, m, kv, g, n_seqs, d_tokens, true, d_target, nullptr);
 }
 
 int cas_commit(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int n_accepted) {
@@ -327,8 +379,8 @@ int cas_commit(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int n_accepted) 
   const int64_t cap = (int64_t)kv->desc.max_pages_per_seq * kv->desc.page_tokens;
   if ((int64_t)kv->h_len[seq] + n > cap) return CAS_ENOMEM;
   for (int l = 0; l < c.n_layers; ++l) {
-    int rc = cas::launch_kv_append(ctx, kv, l, seq, m->knew + (size_t)l * c.max_cols * kvd,
-                                   m->vnew + (size_t)l * c.max_cols * kvd, n, kv->h_len[seq]);
+    const size_t slots = ((size_t)seq * c.n_layers + l) * c.max_cols * kvd;
+    int rc = cas::launch_kv_append(ctx, kv, l, seq, m->knew + slots, m->vnew + slots, n, kv->h_len[seq]);
     if (rc != CAS_OK) return rc;
   }
   kv->h_len[seq] += n;
@@ -341,10 +393,12 @@ int cas_spec_round(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int32_t pend
     return CAS_EINVAL;
   CAS_HIP(ctx, hipMemcpyAsync(m->tok, &pending, sizeof(int32_t), hipMemcpyHostToDevice, ctx->stream));
   for (int i = 0; i < k; ++i) {
-    int rc = cas::forward(ctx, m, kv, seq, m->tok + i, 1, false, i, m->tok + i + 1, nullptr);
+    const cas::ColGroup g{seq, 1, i};
+    int rc = cas::forward(ctx, m, kv, &g, 1, m->tok + i, false, m->tok + i + 1, nullptr);
     if (rc != CAS_OK) return rc;
   }
-  int rc = cas::forward(ctx, m, kv, seq, m->tok, k + 1, true, 0, m->tgt, nullptr);
+  const cas::ColGroup gv{seq, k + 1, 0};
+  int rc = cas::forward(ctx, m, kv, &gv, 1, m->tok, true, m->tgt, nullptr);
   if (rc != CAS_OK) return rc;
   int32_t h_tok[17], h_tgt[17];
   CAS_HIP(ctx, hipMemcpyAsync(h_tok, m->tok, sizeof(int32_t) * (k + 1), hipMemcpyDeviceToHost, ctx->stream));
@@ -355,11 +409,45 @@ int cas_spec_round(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int32_t pend
   return cas_commit(ctx, m, kv, seq, *n_accepted);
 }
 
+int cas_spec_round_multi(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
+                         const int32_t* h_pending, int k, int32_t* h_out, int32_t* h_n_accepted) {
+  if (!ctx || !m || !kv || n_seqs < 1 || n_seqs > 4 || !h_seqs || !h_pending || !h_out || !h_n_accepted || k < 0)
+    return CAS_EINVAL;
+  const int steps = k + 1, total = steps * n_seqs;
+  if (total > m->cfg.max_cols) return CAS_EINVAL;
+  if (kv->desc.n_layers != m->cfg.n_layers || kv->desc.n_kv_heads != m->cfg.n_kv_heads) return CAS_EINVAL;
+  int32_t* step_major = m->tok;                      // [steps][n_seqs]
+  int32_t* seq_major = m->tok + m->cfg.max_cols + 1;  // [n_seqs][steps]
+  CAS_HIP(ctx, hipMemcpyAsync(step_major, h_pending, sizeof(int32_t) * n_seqs, hipMemcpyHostToDevice, ctx->stream));
+  cas::ColGroup g[4];
+  for (int i = 0; i < k; ++i) {
+    for (int s = 0; s < n_seqs; ++s) g[s] = cas::ColGroup{h_seqs[s], 1, i};
+    int rc = cas::forward(ctx, m, kv, g, n_seqs, step_major + i * n_seqs, false, step_major + (i + 1) * n_seqs, nullptr);
+    if (rc != CAS_OK) return rc;
+  }
+  hipLaunchKernelGGL(cas::transpose_tokens_kernel, dim3(1), dim3(64), 0, ctx->stream, step_major, seq_major, steps, n_seqs);
+  for (int s = 0; s < n_seqs; ++s) g[s] = cas::ColGroup{h_seqs[s], steps, 0};
+  int rc = cas::forward(ctx, m, kv, g, n_seqs, seq_major, true, m->tgt, nullptr);
+  if (rc != CAS_OK) return rc;
+  int32_t h_tok[16], h_tgt[16];
+  CAS_HIP(ctx, hipMemcpyAsync(h_tok, seq_major, sizeof(int32_t) * total, hipMemcpyDeviceToHost, ctx->stream));
+  CAS_HIP(ctx, hipMemcpyAsync(h_tgt, m->tgt, sizeof(int32_t) * total, hipMemcpyDeviceToHost, ctx->stream));
+  CAS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  for (int s = 0; s < n_seqs; ++s) {
+    rc = cas_accept(h_tok + s * steps + 1, h_tgt + s * steps, k, h_n_accepted + s, h_out + s * steps);
+    if (rc != CAS_OK) return rc;
+    rc = cas_commit(ctx, m, kv, h_seqs[s], h_n_accepted[s]);
+    if (rc != CAS_OK) return rc;
+  }
+  return CAS_OK;
+}
+
 int cas_prefill(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_tokens, int n) {
   if (check_step(ctx, m, kv, seq) != CAS_OK || !d_tokens || n < 0) return CAS_EINVAL;
   for (int done = 0; done < n;) {
     const int nc = std::min(n - done, (int)m->cfg.max_cols);
-    int rc = cas::forward(ctx, m, kv, seq, d_tokens + done, nc, true, 0, nullptr, nullptr);
+    const cas::ColGroup g{seq, nc, 0};
+    int rc = cas::forward(ctx, m, kv, &g, 1, d_tokens + done, true, nullptr, nullptr);
     if (rc != CAS_OK) return rc;
     rc = cas_commit(ctx, m, kv, seq, nc - 1);
     if (rc != CAS_OK) return rc;

@@ -165,3 +165,95 @@ def test_gpu_stream_against_oracle_teacher_forced(env):
         pending = want
     print("excused near-ties:", excused, flush=True)
     assert excused <= 2
+
+
+def test_multi_sequence_passes_equal_single_sequence_passes(env):
+    """Draft and verification passes over several sequences at once give every sequence exactly
+    the tokens, and after the commit exactly the cache contents, of the one-sequence calls:
+    a column's value never depends on what rides along."""
+    torch, B, ctx = env
+    keep, t, k, nseq = 600, 4, 3, 3
+    weights = synth.model_weights(SHAPE, seed=4)
+    layers = []
+    for lw in weights["layers"]:
+        L = {n: B.cas_encode_weight(ctx, _dev(torch, lw[n]), keep, t) for n in ("wqkv", "wo", "wgu", "wd")}
+        L["g_attn"], L["g_ffn"] = _dev(torch, lw["g_attn"]), _dev(torch, lw["g_ffn"])
+        layers.append(L)
+    head = B.cas_encode_weight(ctx, _dev(torch, weights["lm_head"]), keep, t)
+    rope = torch.from_numpy(synth.rope_table(MAX_POS, SHAPE.head_dim, SHAPE.rope_theta)).cuda()
+    model = B.Model(ctx, SHAPE, layers, head, _dev(torch, weights["embed"]), _dev(torch, weights["g_final"]), rope,
+                    max_cols=12, max_seqs=nseq)
+    def cache():
+        return B.KVCache(ctx, SHAPE.n_layers, SHAPE.n_kv_heads, n_pages=2 * nseq, max_seqs=nseq, max_pages_per_seq=2,
+                         keep_permille=keep, trunc_bits=t)
+    kv_a, kv_b = cache(), cache()
+    prompts = [synth.token_ids(n, SHAPE.vocab, seed=20 + n) for n in (10, 37, 70)]
+    for kv in (kv_a, kv_b):
+        for s, p in enumerate(prompts):
+            B.cas_prefill(ctx, model, kv, s, torch.from_numpy(p[:-1].copy()).cuda())
+    # one sequence at a time
+    single = []
+    for s, p in enumerate(prompts):
+        tok = torch.zeros(k + 1, dtype=torch.int32, device="cuda"); tok[0] = int(p[-1])
+        tgt = torch.zeros(k + 1, dtype=torch.int32, device="cuda")
+        for i in range(k):
+            B.cas_draft_step(ctx, model, kv_a, s, tok[i:i + 1], i, tok[i + 1:i + 2])
+        B.cas_verify_step(ctx, model, kv_a, s, tok, k, tgt)
+        B.cas_commit(ctx, model, kv_a, s, 2)
+        single.append((tok.cpu().numpy().copy(), tgt.cpu().numpy().copy()))
+    # all sequences per pass
+    toks = torch.zeros((k + 1, nseq), dtype=torch.int32, device="cuda")
+    toks[0] = torch.tensor([int(p[-1]) for p in prompts], dtype=torch.int32)
+    for i in range(k):
+        B.cas_draft_step_multi(ctx, model, kv_b, list(range(nseq)), [i] * nseq, toks[i], toks[i + 1])
+    cols = toks.t().contiguous().reshape(-1)                 # sequence after sequence
+    tgt = torch.zeros(nseq * (k + 1), dtype=torch.int32, device="cuda")
+    B.cas_verify_step_multi(ctx, model, kv_b, list(range(nseq)), [k] * nseq, cols, tgt)
+    for s in range(nseq):
+        B.cas_commit(ctx, model, kv_b, s, 2)
+    cols_h, tgt_h = cols.cpu().numpy().reshape(nseq, k + 1), tgt.cpu().numpy().reshape(nseq, k + 1)
+    for s in range(nseq):
+        np.testing.assert_array_equal(cols_h[s], single[s][0])
+        np.testing.assert_array_equal(tgt_h[s], single[s][1])
+        n = B.cas_kv_len(kv_a, s)
+        assert n == B.cas_kv_len(kv_b, s) == len(prompts[s]) - 1 + 3
+        for layer in range(SHAPE.n_layers):
+            Ka, Va = B.cas_kv_read(ctx, kv_a, layer, s, 0, n, full=True)
+            Kb, Vb = B.cas_kv_read(ctx, kv_b, layer, s, 0, n, full=True)
+            assert torch.equal(Ka, Kb) and torch.equal(Va, Vb)
+
+
+def test_multi_sequence_round_equals_single_sequence_rounds(env):
+    """cas_spec_round_multi emits, sequence by sequence, the stream cas_spec_round emits."""
+    torch, B, ctx = env
+    keep, t, k, nseq = 600, 4, 3, 3
+    weights = synth.model_weights(SHAPE, seed=2)
+    model, _ = gpu_model(torch, B, ctx, weights, keep, t, max_cols=12)
+    # same weights, room for three sequences
+    layers, head, embed, g_final, rope = model._keep
+    model = B.Model(ctx, SHAPE, layers, head, embed, g_final, rope, max_cols=12, max_seqs=nseq)
+    def cache():
+        return B.KVCache(ctx, SHAPE.n_layers, SHAPE.n_kv_heads, n_pages=2 * nseq, max_seqs=nseq, max_pages_per_seq=2,
+                         keep_permille=keep, trunc_bits=t)
+    kv_a, kv_b = cache(), cache()
+    prompts = [synth.token_ids(n, SHAPE.vocab, seed=40 + n) for n in (5, 20, 33)]
+    for kv in (kv_a, kv_b):
+        for s, p in enumerate(prompts):
+            B.cas_prefill(ctx, model, kv, s, torch.from_numpy(p[:-1].copy()).cuda())
+    rounds = 5
+    single = []
+    for s, p in enumerate(prompts):
+        pending, out = int(p[-1]), []
+        for _ in range(rounds):
+            n, emitted = B.cas_spec_round(ctx, model, kv_a, s, pending, k)
+            out.append((n, emitted)); pending = emitted[-1]
+        single.append(out)
+    pending = [int(p[-1]) for p in prompts]
+    multi = [[] for _ in range(nseq)]
+    for _ in range(rounds):
+        res = B.cas_spec_round_multi(ctx, model, kv_b, list(range(nseq)), pending, k)
+        for s, (n, emitted) in enumerate(res):
+            multi[s].append((n, emitted)); pending[s] = emitted[-1]
+    assert multi == single
+    for s in range(nseq):
+        assert B.cas_kv_len(kv_a, s) == B.cas_kv_len(kv_b, s)
