@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--trunc", type=int, default=4)
     ap.add_argument("--layers", type=int, default=None, help="default: 32 (8b) / 80 (70b)")
     ap.add_argument("--context", type=int, default=8192, help="committed KV positions when a step starts")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="sequences decoded together (1..4, batch * (k + 1) <= 16); 1 is the configuration of the metric")
     ap.add_argument("--workload", choices=["model", "linear"], default="model")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()

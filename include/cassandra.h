@@ -116,8 +116,9 @@ int cas_decode_weight(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
 
 /* Draft GEMV (Sec. 4.1 draft inference): y[b][r] = sum_c Wdraft[r][c] * x[b][c], fp32
  * accumulation, reading only the speculation buffer.  d_x: bf16 [batch][cols];
- * d_y: float [batch][rows]; batch in 1..4.  x is held in LDS (fp32, or bf16 for a batch of wide
- * rows): CAS_ENOTSUP if 66 * ceil(cols / 32) * batch bytes exceed the LDS of a workgroup. */
+ * d_y: float [batch][rows]; batch in 1..4.  x is held in LDS (fp32 for one column, bf16 for a
+ * batch): CAS_ENOTSUP if it does not fit (132 bytes per 32 columns for one column, 66 per column
+ * of a batch). */
 int cas_gemv_draft(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
                    const uint16_t* d_x, int batch, float* d_y);
 

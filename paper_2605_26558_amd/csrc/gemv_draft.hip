@@ -53,8 +53,9 @@ struct Cursor {  // walks the (row, chunk) items of one wave in order
 constexpr int kGemvThreads = 1024;  // 16 waves share one staged copy of x
 constexpr int kGemvWaves = kGemvThreads / 64;
 
-// x in LDS: fp32, or bf16 bit patterns (XH) when a batch of wide rows would not fit as fp32;
-// the staged values are bf16-representable either way, XH costs one shift per use
+// x in LDS: fp32 for one column; bf16 bit patterns (XH) for a batch, whose gathers of NB
+// values per kept weight would otherwise saturate the LDS (measured 2.4x slower at NB = 4).
+// The staged values are bf16-representable either way; XH costs one shift per use.
 template <bool XH>
 struct XStage {
   using type = float;
@@ -68,9 +69,10 @@ struct XStage<true> {
   static __device__ __forceinline__ float get(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 };
 
-template <int T, int NB, bool XH>
+template <int T, int NB>
 __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   constexpr int FW = 16 - T;
+  constexpr bool XH = NB > 1;
   using XS = XStage<XH>;
   using XT = typename XS::type;
   extern __shared__ uint8_t xs_raw[];
@@ -301,20 +303,20 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   }
 }
 
-template <int T, bool XH>
+template <int T>
 static int launch_t(cas_ctx* ctx, const GemvArgs& a, int batch, int grid, size_t lds) {
 #define CAS_LAUNCH(NBV)                                                                                      \
   do {                                                                                                       \
     static size_t raised = 48 * 1024;                                                                        \
     if (lds > raised) {                                                                                      \
-      CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_kernel<T, NBV, XH>,                           \
+      CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_kernel<T, NBV>,                           \
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));               \
       raised = lds;                                                                                          \
     }                                                                                                        \
-    hipLaunchKernelGGL((gemv_draft_kernel<T, NBV, XH>), dim3(grid), dim3(kGemvThreads), lds, ctx->stream, a); \
+    hipLaunchKernelGGL((gemv_draft_kernel<T, NBV>), dim3(grid), dim3(kGemvThreads), lds, ctx->stream, a); \
   } while (0)
   switch (batch) {
-    case 1: if constexpr (XH) return CAS_EINVAL; else CAS_LAUNCH(1); break;  // one column always fits as fp32
+    case 1: CAS_LAUNCH(1); break;
     case 2: CAS_LAUNCH(2); break;
     case 3: CAS_LAUNCH(3); break;
     case 4: CAS_LAUNCH(4); break;
@@ -339,10 +341,8 @@ int launch_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec, 
   a.bitmap = (const uint32_t*)((const char*)spec + d.off_bitmap);
   a.spec = (const uint32_t*)((const char*)spec + d.off_spec);
   a.x = x; a.y = y;
-  // x as fp32 when it fits the LDS, else (a batch of wide rows) as bf16
-  size_t lds = sizeof(float) * (size_t)((d.bw + 63) / 64 * 64) * 33 * batch;
-  const bool xh = lds > (size_t)ctx->lds_max && batch > 1;
-  if (xh) lds /= 2;
+  // x: fp32 for one column, bf16 for a batch (see XStage)
+  const size_t lds = (batch > 1 ? sizeof(uint16_t) : sizeof(float)) * (size_t)((d.bw + 63) / 64 * 64) * 33 * batch;
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
   // one or two workgroups per CU (two fill its 32 wave slots), whichever leaves the most
   // loaded CU with fewer rows; all of them are resident at once
@@ -356,7 +356,7 @@ int launch_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec, 
   }
   a.nwaves = grid * kGemvWaves;
   ProfScope prof(ctx, PROF_GEMV_DRAFT, 4.0 * (double)d.rows * (d.bw + d.sw));
-#define CAS_T(TV) case TV: return xh ? launch_t<TV, true>(ctx, a, batch, grid, lds) : launch_t<TV, false>(ctx, a, batch, grid, lds);
+#define CAS_T(TV) case TV: return launch_t<TV>(ctx, a, batch, grid, lds);
   switch (d.t) {
     CAS_T(0) CAS_T(1) CAS_T(2) CAS_T(3) CAS_T(4) CAS_T(5) CAS_T(6) CAS_T(7)
   }

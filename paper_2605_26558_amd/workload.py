@@ -110,6 +110,9 @@ class ModelRoundWorkload:
         import torch
         self.torch, self.B = torch, B
         self.k, self.ctx_len = args.k, args.context
+        self.batch = max(1, int(getattr(args, "batch", 1)))
+        if self.batch > 4 or self.batch * (self.k + 1) > 16:
+            raise SystemExit("--batch: at most 4 sequences and batch * (k + 1) <= 16 columns per verification pass")
         big = getattr(args, "model", "8b") == "70b"
         if big:   # hidden 8192, 64 q / 8 kv heads, FFN 28672: ~148 GB encoded at 80 layers
             shape = synth.LlamaShape("llama3-70b", 8192, args.layers, 64, 8, 128, 28672, 128256)
@@ -149,9 +152,11 @@ class ModelRoundWorkload:
         max_pos = self.ctx_len + 1024
         rope = torch.from_numpy(synth.rope_table(max_pos, shape.head_dim, shape.rope_theta)).cuda()
         self.layers, self.head, self.g_final = layers, head, gain()
-        self.model = B.Model(ctx, shape, layers, head, embed, self.g_final, rope, max_cols=self.k + 1)
+        nb = self.batch
+        self.model = B.Model(ctx, shape, layers, head, embed, self.g_final, rope, max_cols=nb * (self.k + 1),
+                             max_seqs=nb)
         pages = (max_pos + 63) // 64
-        self.kv = B.KVCache(ctx, shape.n_layers, shape.n_kv_heads, n_pages=pages, max_seqs=1,
+        self.kv = B.KVCache(ctx, shape.n_layers, shape.n_kv_heads, n_pages=pages * nb, max_seqs=nb,
                             max_pages_per_seq=pages, keep_permille=args.keep, trunc_bits=args.trunc)
         # synthetic cache contents
         chunk = 1024
@@ -160,14 +165,16 @@ class ModelRoundWorkload:
             done = 0
             while done < self.ctx_len:
                 n = min(chunk, self.ctx_len - done)
-                K = torch.randn((n, shape.n_kv_heads, 128), device="cuda", generator=gen)
-                K[:, :, out_idx] *= 10.0
-                V = torch.randn((n, shape.n_kv_heads, 128), device="cuda", generator=gen)
-                B.cas_kv_set_len(self.kv, 0, done)
-                B.cas_kv_append(ctx, self.kv, layer, 0, K.to(torch.bfloat16).view(torch.int16).contiguous(),
-                                V.to(torch.bfloat16).view(torch.int16).contiguous())
+                for seq in range(nb):
+                    K = torch.randn((n, shape.n_kv_heads, 128), device="cuda", generator=gen)
+                    K[:, :, out_idx] *= 10.0
+                    V = torch.randn((n, shape.n_kv_heads, 128), device="cuda", generator=gen)
+                    B.cas_kv_set_len(self.kv, seq, done)
+                    B.cas_kv_append(ctx, self.kv, layer, seq, K.to(torch.bfloat16).view(torch.int16).contiguous(),
+                                    V.to(torch.bfloat16).view(torch.int16).contiguous())
                 done += n
-        B.cas_kv_set_len(self.kv, 0, self.ctx_len)
+        for seq in range(nb):
+            B.cas_kv_set_len(self.kv, seq, self.ctx_len)
         torch.cuda.synchronize()
         mats = [L[n] for L in layers for n in dims] + [head]
         self.draft_w = sum(m.desc.rows * (m.desc.bw + m.desc.sw) * 4 for m in mats)
@@ -178,30 +185,39 @@ class ModelRoundWorkload:
         self.draft_kv = per_tok_draft * self.ctx_len
         self.verify_kv = per_tok_full * self.ctx_len
         self.values = sum(m.desc.rows * m.desc.cols for m in mats)
+        # a pass reads the weights once for all sequences and every sequence's cache
+        self.draft_kv *= nb
+        self.verify_kv *= nb
         self.bytes_per_step = self.k * (self.draft_w + self.draft_kv) + self.verify_w + self.verify_kv
-        self.pending = 1
+        self.pending = [1] * nb
         self.accepted, self.rounds = 0, 0
         self.config = {"workload": f"{name}-shaped random-init model ({shape.n_layers} layers, vocab {shape.vocab}, "
-                                   f"{self.values / 1e9:.2f} G encoded weights), batch 1, KV context {self.ctx_len} "
+                                   f"{self.values / 1e9:.2f} G encoded weights), batch {nb}, KV context {self.ctx_len} "
                                    f"(synthetic K/V, 4 outlier key channels per head), draft length k={self.k}, "
                                    "greedy acceptance; weights + KV in Cassandra format",
                        "keep_permille": args.keep, "trunc_bits": args.trunc, "k": self.k, "context": self.ctx_len,
                        "step": "one speculative round: k draft passes + verify(k+1) + accept + commit"}
 
     def step(self):
-        n, out = self.B.cas_spec_round(self.ctx, self.model, self.kv, 0, self.pending, self.k)
-        self.pending = out[-1]
-        self.accepted += n
+        B, nb = self.B, self.batch
+        if nb == 1:
+            res = [B.cas_spec_round(self.ctx, self.model, self.kv, 0, self.pending[0], self.k)]
+        else:
+            res = B.cas_spec_round_multi(self.ctx, self.model, self.kv, list(range(nb)), self.pending, self.k)
+        for seq, (n, out) in enumerate(res):
+            self.pending[seq] = out[-1]
+            self.accepted += n
+            # keep the context length fixed across steps (roll the committed tokens back)
+            B.cas_kv_set_len(self.kv, seq, self.ctx_len)
         self.rounds += 1
-        # keep the context length fixed across steps (roll the committed tokens back)
-        self.B.cas_kv_set_len(self.kv, 0, self.ctx_len)
 
     def _chain_buffers(self):
         torch, shape = self.torch, self.shape
         z = lambda n, c=1: torch.zeros((c, n), dtype=torch.int16, device="cuda")
-        return {"h": z(shape.hidden), "ao": z(shape.q_dim), "act": z(shape.ffn),
-                "y": torch.empty((self.k + 1, max(shape.vocab, 2 * shape.ffn)), dtype=torch.float32, device="cuda"),
-                "X": {c: torch.randn((self.k + 1, c), device="cuda").to(torch.bfloat16).view(torch.int16)
+        nb, nv = self.batch, self.batch * (self.k + 1)
+        return {"h": z(shape.hidden, nb), "ao": z(shape.q_dim, nb), "act": z(shape.ffn, nb),
+                "y": torch.empty((nv, max(shape.vocab, 2 * shape.ffn)), dtype=torch.float32, device="cuda"),
+                "X": {c: torch.randn((nv, c), device="cuda").to(torch.bfloat16).view(torch.int16)
                       for c in (shape.hidden, shape.q_dim, shape.ffn)}}
 
     def _draft_gemv_chain(self, buf):
@@ -210,11 +226,11 @@ class ModelRoundWorkload:
         B, ctx, eps = self.B, self.ctx, self.shape.rms_eps
         h, ao, act, y = buf["h"], buf["ao"], buf["act"], buf["y"]
         for L in self.layers:
-            B.cas_gemv_draft_fused(ctx, L["wqkv"], h, y=y[:1], gain=L["g_attn"], eps=eps, epilogue=0)
+            B.cas_gemv_draft_fused(ctx, L["wqkv"], h, y=y[:self.batch], gain=L["g_attn"], eps=eps, epilogue=0)
             B.cas_gemv_draft_fused(ctx, L["wo"], ao, epilogue=1, out16=h)
             B.cas_gemv_draft_fused(ctx, L["wgu"], h, gain=L["g_ffn"], eps=eps, epilogue=2, out16=act)
             B.cas_gemv_draft_fused(ctx, L["wd"], act, epilogue=1, out16=h)
-        B.cas_gemv_draft_fused(ctx, self.head, h, y=y[:1], gain=self.g_final, eps=eps, epilogue=0)
+        B.cas_gemv_draft_fused(ctx, self.head, h, y=y[:self.batch], gain=self.g_final, eps=eps, epilogue=0)
 
     def _verify_gemm_chain(self, buf):
         B, ctx, X, y = self.B, self.ctx, buf["X"], buf["y"]
@@ -273,8 +289,10 @@ class ModelRoundWorkload:
         """Wall time of one draft pass, one verification pass (k+1 columns) and one plain decode
         step (verification with a single column) of the whole model, by HIP events."""
         torch, B, ctx = self.torch, self.B, self.ctx
-        tok = torch.ones(self.k + 1, dtype=torch.int32, device="cuda")
-        out = torch.empty(self.k + 1, dtype=torch.int32, device="cuda")
+        nb, k = self.batch, self.k
+        seqs = list(range(nb))
+        tok = torch.ones(nb * (k + 1), dtype=torch.int32, device="cuda")
+        out = torch.empty(nb * (k + 1), dtype=torch.int32, device="cuda")
 
         def timed(fn, reps=3):
             fn()
@@ -287,9 +305,9 @@ class ModelRoundWorkload:
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / reps
 
-        t_draft = timed(lambda: B.cas_draft_step(ctx, self.model, self.kv, 0, tok[:1], 0, out[:1]))
-        t_verify = timed(lambda: B.cas_verify_step(ctx, self.model, self.kv, 0, tok, self.k, out))
-        t_plain = timed(lambda: B.cas_verify_step(ctx, self.model, self.kv, 0, tok[:1], 0, out[:1]))
+        t_draft = timed(lambda: B.cas_draft_step_multi(ctx, self.model, self.kv, seqs, [0] * nb, tok[:nb], out[:nb]))
+        t_verify = timed(lambda: B.cas_verify_step_multi(ctx, self.model, self.kv, seqs, [k] * nb, tok, out))
+        t_plain = timed(lambda: B.cas_verify_step_multi(ctx, self.model, self.kv, seqs, [0] * nb, tok[:nb], out[:nb]))
         return t_draft, t_verify, t_plain
 
     def _forced_rounds(self, alpha, rounds=48, seed=11):
@@ -299,29 +317,37 @@ class ModelRoundWorkload:
         real work (the random-init model itself accepts nothing)."""
         import time
         import numpy as np
-        torch, B, ctx, k = self.torch, self.B, self.ctx, self.k
+        torch, B, ctx, k, nb = self.torch, self.B, self.ctx, self.k, self.batch
+        seqs = list(range(nb))
         rng = np.random.Generator(np.random.Philox(seed))
-        tok = torch.ones(k + 1, dtype=torch.int32, device="cuda")
-        out = torch.empty(k + 1, dtype=torch.int32, device="cuda")
+        tok = torch.ones(nb * (k + 1), dtype=torch.int32, device="cuda")
+        out = torch.empty(nb * (k + 1), dtype=torch.int32, device="cuda")
 
         def one_round():
             for i in range(k):
-                B.cas_draft_step(ctx, self.model, self.kv, 0, tok[i:i + 1], i, out[i:i + 1])
-            B.cas_verify_step(ctx, self.model, self.kv, 0, tok, k, out)
+                B.cas_draft_step_multi(ctx, self.model, self.kv, seqs, [i] * nb, tok[:nb], out[:nb])
+            B.cas_verify_step_multi(ctx, self.model, self.kv, seqs, [k] * nb, tok, out)
             out.cpu()                                   # the host needs the target tokens to accept
-            draws = rng.random(k) < alpha
-            n = k if draws.all() else int(np.argmin(draws))
-            B.cas_commit(ctx, self.model, self.kv, 0, n)
-            return n + 1
+            emitted = 0
+            for seq in seqs:
+                draws = rng.random(k) < alpha
+                n = k if draws.all() else int(np.argmin(draws))
+                B.cas_commit(ctx, self.model, self.kv, seq, n)
+                emitted += n + 1
+            return emitted
+
+        def reset():
+            for seq in seqs:
+                B.cas_kv_set_len(self.kv, seq, self.ctx_len)
 
         one_round()
-        B.cas_kv_set_len(self.kv, 0, self.ctx_len)
+        reset()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         tokens = sum(one_round() for _ in range(rounds))
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        B.cas_kv_set_len(self.kv, 0, self.ctx_len)
+        reset()
         return {"tokens_per_s": tokens / dt, "tokens_per_round": tokens / rounds, "rounds": rounds}
 
     def extra(self, ms_per_step):
@@ -351,13 +377,13 @@ class ModelRoundWorkload:
         synth_tps = {}
         for alpha in (0.0, 0.6, 0.8, 0.9, 1.0):
             exp_n = float(k) if alpha == 1.0 else sum(alpha ** i for i in range(1, k + 1))
-            synth_tps[f"alpha={alpha}"] = (exp_n + 1.0) / ((k * t_draft + t_verify) * 1e-3)
-        out = {"tokens_per_s": (self.accepted + self.rounds) / max(self.rounds, 1) / (ms_per_step * 1e-3),
+            synth_tps[f"alpha={alpha}"] = self.batch * (exp_n + 1.0) / ((k * t_draft + t_verify) * 1e-3)
+        out = {"tokens_per_s": (self.accepted + self.rounds * self.batch) / max(self.rounds, 1) / (ms_per_step * 1e-3),
                "accepted_per_round": self.accepted / max(self.rounds, 1),
                "draft_pass_ms": t_draft, "verify_pass_ms": t_verify, "plain_decode_step_ms": t_plain,
                "draft_pass_GBps": (self.draft_w + self.draft_kv) / (t_draft * 1e-3) / 1e9,
                "verify_pass_GBps": (self.verify_w + self.verify_kv) / (t_verify * 1e-3) / 1e9,
-               "plain_decode_tokens_per_s": 1e3 / t_plain,
+               "plain_decode_tokens_per_s": self.batch * 1e3 / t_plain,
                "context_vendor_bf16_gemv_pass_ms": t_bf16,
                "context_vendor_bf16_gemv_GBps": None if t_bf16 is None else 2.0 * self.values / (t_bf16 * 1e-3) / 1e9,
                "tokens_per_s_at_assumed_acceptance": synth_tps,
