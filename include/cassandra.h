@@ -327,9 +327,10 @@ int cas_verify_step(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const i
  * cache.  h_seqs: n_seqs distinct sequence ids (host).  Draft: one column per sequence, n_seqs
  * in 1..4, h_slots[i] = in-flight slot of sequence i's token, d_tokens_in / d_tokens_out:
  * int32 [n_seqs] (device).  Verification: h_k[i] drafts of sequence i, i.e. h_k[i] + 1 columns;
- * the columns of all sequences, sequence after sequence, are d_tokens / d_target (device);
- * their total is at most max_cols.  Every sequence gets exactly the values the one-sequence
- * calls give it.  Accept and cas_commit stay per sequence. */
+ * the columns of all sequences, sequence after sequence, are d_tokens / d_target (device).
+ * Sequences share a pass while their columns fit max_cols; further sequences go into further
+ * passes (each reads the weights again).  Every sequence gets exactly the values the
+ * one-sequence calls give it.  Accept and cas_commit stay per sequence. */
 int cas_draft_step_multi(cas_ctx* ctx, cas_model* model, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
                          const int32_t* h_slots, const int32_t* d_tokens_in, int32_t* d_tokens_out);
 int cas_verify_step_multi(cas_ctx* ctx, cas_model* model, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
@@ -346,7 +347,7 @@ int cas_commit(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, int n_accept
 int cas_spec_round(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, int32_t pending, int k,
                    int32_t* h_out, int32_t* n_accepted);
 
-/* One speculative round for n_seqs sequences at once (1..4, (k + 1) * n_seqs <= max_cols):
+/* One speculative round for n_seqs sequences at once (1..4, k + 1 <= max_cols):
  * k multi-sequence draft passes, one multi-sequence verification pass, greedy acceptance and
  * commit per sequence.  h_pending: the pending token of every sequence; h_out: [n_seqs][k+1],
  * row s receives the h_n_accepted[s] + 1 tokens emitted for sequence s. */

@@ -256,8 +256,9 @@ static ActLayout act_layout(const cas_model_cfg& c) {
   L.vnew = carve(off, (size_t)model_seqs(c) * c.n_layers * nc * kvd * 2);
   L.y = carve(off, nc * ymax * 4);
   L.logits = carve(off, nc * (size_t)c.vocab * 4);
-  L.tok = carve(off, (2 * nc + 2) * 4);  // draft tokens step-major, then the same sequence-major
-  L.tgt = carve(off, (nc + 1) * 4);
+  L.tok = carve(off, 8 * nc * 4);        // draft tokens of up to 4 sequences step-major, then sequence-major
+
+  L.tgt = carve(off, 4 * nc * 4);
   L.amax_v = carve(off, nc * kArgmaxSlices * 4);
   L.amax_i = carve(off, nc * kArgmaxSlices * 4);
   L.total = off;
@@ -360,16 +361,35 @@ int cas_draft_step_multi(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, con
   return cas::forward(ctx, m, kv, g, n_seqs, d_tokens_in, false, d_tokens_out, nullptr);
 }
 
+// Verification columns of several sequences: sequences are taken in order, as many per pass as
+// fit max_cols columns (a pass reads every weight once; a column's value does not depend on
+// how the sequences are split over passes).
+static int verify_groups(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, const int32_t* h_seqs, const int32_t* h_k,
+                         const int32_t* d_tokens, int32_t* d_target) {
+  cas::ColGroup g[16];
+  for (int s = 0, off = 0; s < n_seqs;) {
+    int ng = 0, cols = 0;
+    while (s + ng < n_seqs && ng < 16 && cols + h_k[s + ng] + 1 <= m->cfg.max_cols) {
+      g[ng] = cas::ColGroup{h_seqs[s + ng], h_k[s + ng] + 1, 0};
+      cols += h_k[s + ng] + 1;
+      ++ng;
+    }
+    if (ng == 0) return CAS_EINVAL;  // one sequence alone exceeds max_cols
+    int rc = cas::forward(ctx, m, kv, g, ng, d_tokens + off, true, d_target + off, nullptr);
+    if (rc != CAS_OK) return rc;
+    s += ng;
+    off += cols;
+  }
+  return CAS_OK;
+}
+
 int cas_verify_step_multi(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
                           const int32_t* h_k, const int32_t* d_tokens, int32_t* d_target) {
   if (!ctx || !m || !kv || n_seqs < 1 || n_seqs > 16 || !h_seqs || !h_k || !d_tokens || !d_target) return CAS_EINVAL;
   if (kv->desc.n_layers != m->cfg.n_layers || kv->desc.n_kv_heads != m->cfg.n_kv_heads) return CAS_EINVAL;
-  cas::ColGroup g[16];
-  for (int i = 0; i < n_seqs; ++i) {
+  for (int i = 0; i < n_seqs; ++i)
     if (h_k[i] < 0) return CAS_EINVAL;
-    g[i] = cas::ColGroup{h_seqs[i], h_k[i] + 1, 0};
-  }
-  return cas::forward(ctx, m, kv, g, n_seqs, d_tokens, true, d_target, nullptr);
+  return verify_groups(ctx, m, kv, n_seqs, h_seqs, h_k, d_tokens, d_target);
 }
 
 int cas_commit(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int n_accepted) {
@@ -414,10 +434,10 @@ int cas_spec_round_multi(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, con
   if (!ctx || !m || !kv || n_seqs < 1 || n_seqs > 4 || !h_seqs || !h_pending || !h_out || !h_n_accepted || k < 0)
     return CAS_EINVAL;
   const int steps = k + 1, total = steps * n_seqs;
-  if (total > m->cfg.max_cols) return CAS_EINVAL;
+  if (steps > m->cfg.max_cols) return CAS_EINVAL;
   if (kv->desc.n_layers != m->cfg.n_layers || kv->desc.n_kv_heads != m->cfg.n_kv_heads) return CAS_EINVAL;
   int32_t* step_major = m->tok;                      // [steps][n_seqs]
-  int32_t* seq_major = m->tok + m->cfg.max_cols + 1;  // [n_seqs][steps]
+  int32_t* seq_major = m->tok + 4 * m->cfg.max_cols;   // [n_seqs][steps]
   CAS_HIP(ctx, hipMemcpyAsync(step_major, h_pending, sizeof(int32_t) * n_seqs, hipMemcpyHostToDevice, ctx->stream));
   cas::ColGroup g[4];
   for (int i = 0; i < k; ++i) {
@@ -425,11 +445,13 @@ int cas_spec_round_multi(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, con
     int rc = cas::forward(ctx, m, kv, g, n_seqs, step_major + i * n_seqs, false, step_major + (i + 1) * n_seqs, nullptr);
     if (rc != CAS_OK) return rc;
   }
-  hipLaunchKernelGGL(cas::transpose_tokens_kernel, dim3(1), dim3(64), 0, ctx->stream, step_major, seq_major, steps, n_seqs);
-  for (int s = 0; s < n_seqs; ++s) g[s] = cas::ColGroup{h_seqs[s], steps, 0};
-  int rc = cas::forward(ctx, m, kv, g, n_seqs, seq_major, true, m->tgt, nullptr);
+  hipLaunchKernelGGL(cas::transpose_tokens_kernel, dim3(1), dim3(64), 0, ctx->stream, step_major, seq_major, steps,
+                     n_seqs);  // total <= 4 * 16 = 64 threads
+  int32_t h_k[4];
+  for (int s = 0; s < n_seqs; ++s) h_k[s] = k;
+  int rc = verify_groups(ctx, m, kv, n_seqs, h_seqs, h_k, seq_major, m->tgt);
   if (rc != CAS_OK) return rc;
-  int32_t h_tok[16], h_tgt[16];
+  int32_t h_tok[64], h_tgt[64];
   CAS_HIP(ctx, hipMemcpyAsync(h_tok, seq_major, sizeof(int32_t) * total, hipMemcpyDeviceToHost, ctx->stream));
   CAS_HIP(ctx, hipMemcpyAsync(h_tgt, m->tgt, sizeof(int32_t) * total, hipMemcpyDeviceToHost, ctx->stream));
   CAS_HIP(ctx, hipStreamSynchronize(ctx->stream));

@@ -111,8 +111,8 @@ class ModelRoundWorkload:
         self.torch, self.B = torch, B
         self.k, self.ctx_len = args.k, args.context
         self.batch = max(1, int(getattr(args, "batch", 1)))
-        if self.batch > 4 or self.batch * (self.k + 1) > 16:
-            raise SystemExit("--batch: at most 4 sequences and batch * (k + 1) <= 16 columns per verification pass")
+        if self.batch > 4:
+            raise SystemExit("--batch: at most 4 sequences")
         big = getattr(args, "model", "8b") == "70b"
         if big:   # hidden 8192, 64 q / 8 kv heads, FFN 28672: ~148 GB encoded at 80 layers
             shape = synth.LlamaShape("llama3-70b", 8192, args.layers, 64, 8, 128, 28672, 128256)
@@ -153,8 +153,9 @@ class ModelRoundWorkload:
         rope = torch.from_numpy(synth.rope_table(max_pos, shape.head_dim, shape.rope_theta)).cuda()
         self.layers, self.head, self.g_final = layers, head, gain()
         nb = self.batch
-        self.model = B.Model(ctx, shape, layers, head, embed, self.g_final, rope, max_cols=nb * (self.k + 1),
-                             max_seqs=nb)
+        # 16 columns per verification pass at most; more sequences x drafts take a second pass
+        self.model = B.Model(ctx, shape, layers, head, embed, self.g_final, rope,
+                             max_cols=min(16, nb * (self.k + 1)), max_seqs=nb)
         pages = (max_pos + 63) // 64
         self.kv = B.KVCache(ctx, shape.n_layers, shape.n_kv_heads, n_pages=pages * nb, max_seqs=nb,
                             max_pages_per_seq=pages, keep_permille=args.keep, trunc_bits=args.trunc)
@@ -185,9 +186,12 @@ class ModelRoundWorkload:
         self.draft_kv = per_tok_draft * self.ctx_len
         self.verify_kv = per_tok_full * self.ctx_len
         self.values = sum(m.desc.rows * m.desc.cols for m in mats)
-        # a pass reads the weights once for all sequences and every sequence's cache
+        # a pass reads the weights once for all sequences and every sequence's cache; the
+        # verification columns go into passes of at most 16 columns
+        per_pass = max(1, min(nb, 16 // (self.k + 1)))
         self.draft_kv *= nb
         self.verify_kv *= nb
+        self.verify_w *= (nb + per_pass - 1) // per_pass
         self.bytes_per_step = self.k * (self.draft_w + self.draft_kv) + self.verify_w + self.verify_kv
         self.pending = [1] * nb
         self.accepted, self.rounds = 0, 0
@@ -214,7 +218,7 @@ class ModelRoundWorkload:
     def _chain_buffers(self):
         torch, shape = self.torch, self.shape
         z = lambda n, c=1: torch.zeros((c, n), dtype=torch.int16, device="cuda")
-        nb, nv = self.batch, self.batch * (self.k + 1)
+        nb, nv = self.batch, min(16, self.batch * (self.k + 1))
         return {"h": z(shape.hidden, nb), "ao": z(shape.q_dim, nb), "act": z(shape.ffn, nb),
                 "y": torch.empty((nv, max(shape.vocab, 2 * shape.ffn)), dtype=torch.float32, device="cuda"),
                 "X": {c: torch.randn((nv, c), device="cuda").to(torch.bfloat16).view(torch.int16)

@@ -223,15 +223,18 @@ def test_multi_sequence_passes_equal_single_sequence_passes(env):
             assert torch.equal(Ka, Kb) and torch.equal(Va, Vb)
 
 
-def test_multi_sequence_round_equals_single_sequence_rounds(env):
-    """cas_spec_round_multi emits, sequence by sequence, the stream cas_spec_round emits."""
+@pytest.mark.parametrize("max_cols", [12, 8, 4])
+def test_multi_sequence_round_equals_single_sequence_rounds(env, max_cols):
+    """cas_spec_round_multi emits, sequence by sequence, the stream cas_spec_round emits, also
+    when the verification columns of the three sequences need two or three passes."""
     torch, B, ctx = env
+    print(f"case max_cols={max_cols}", flush=True)
     keep, t, k, nseq = 600, 4, 3, 3
     weights = synth.model_weights(SHAPE, seed=2)
     model, _ = gpu_model(torch, B, ctx, weights, keep, t, max_cols=12)
     # same weights, room for three sequences
     layers, head, embed, g_final, rope = model._keep
-    model = B.Model(ctx, SHAPE, layers, head, embed, g_final, rope, max_cols=12, max_seqs=nseq)
+    model = B.Model(ctx, SHAPE, layers, head, embed, g_final, rope, max_cols=max_cols, max_seqs=nseq)
     def cache():
         return B.KVCache(ctx, SHAPE.n_layers, SHAPE.n_kv_heads, n_pages=2 * nseq, max_seqs=nseq, max_pages_per_seq=2,
                          keep_permille=keep, trunc_bits=t)
