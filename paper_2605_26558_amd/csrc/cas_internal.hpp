@@ -61,6 +61,10 @@ int launch_gemm_verify(cas_ctx*, const cas_wdesc&, const void* spec, const void*
 int launch_gemm_verify_fused(cas_ctx*, const cas_wdesc&, const void* spec, const void* verif, const uint16_t* X,
                              int ncols, float* Y, int epi, uint16_t* out16);
 int launch_kv_append(cas_ctx*, cas_kv*, int layer, int seq, const uint16_t* K, const uint16_t* V, int n_tok, int pos0);
+// the same for n_layers consecutive layers in one launch; the vectors of layer layer0 + i start
+// i * layer_stride values after K / V
+int launch_kv_append_layers(cas_ctx*, cas_kv*, int layer0, int n_layers, size_t layer_stride, int seq,
+                            const uint16_t* K, const uint16_t* V, int n_tok, int pos0);
 int launch_kv_read(cas_ctx*, cas_kv*, int layer, int seq, int pos0, int n_tok, int full, uint16_t* K, uint16_t* V);
 struct AttnCall {
   int layer, seq, full;        // full: 0 = speculation data only (draft), 1 = exact reconstruction

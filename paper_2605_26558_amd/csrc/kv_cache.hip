@@ -13,13 +13,16 @@ namespace cas {
 // the K-th largest key is found bit by bit with wave ballots and "key >= threshold" keeps
 // exactly K values with ties going to the lower column.
 __global__ __launch_bounds__(64) void kv_append_kernel(KvGeom g, uint32_t* spec_pool, uint32_t* verif_pool,
-                                                       const int32_t* __restrict__ page_row, int layer, int pos0,
+                                                       const int32_t* __restrict__ page_row, int layer0, int pos0,
                                                        const uint16_t* __restrict__ Kn,
-                                                       const uint16_t* __restrict__ Vn) {
+                                                       const uint16_t* __restrict__ Vn, size_t layer_stride) {
   __shared__ uint32_t stage[3 * 64 + 8];  // sw + lw + pw <= 16*128/32 = 64 words (+ rounding)
   const int lane = threadIdx.x;
-  const int tok = blockIdx.x, head = blockIdx.y, kv = blockIdx.z;
-  const uint16_t* src = (kv ? Vn : Kn) + ((size_t)tok * g.n_kv_heads + head) * 128;
+  // grid.z = 2 * (layers of this launch): the vectors of layer layer0 + i start i * layer_stride
+  // values after those of layer0
+  const int tok = blockIdx.x, head = blockIdx.y, kv = blockIdx.z & 1, layer = layer0 + (blockIdx.z >> 1);
+  const uint16_t* src = (kv ? Vn : Kn) + (size_t)(blockIdx.z >> 1) * layer_stride +
+                        ((size_t)tok * g.n_kv_heads + head) * 128;
   const uint32_t v0 = src[lane], v1 = src[lane + 64];
   const uint32_t key0 = ((v0 & 0x7FFFu) << 7) | (uint32_t)(127 - lane);
   const uint32_t key1 = ((v1 & 0x7FFFu) << 7) | (uint32_t)(63 - lane);
@@ -113,11 +116,17 @@ __global__ __launch_bounds__(128) void kv_read_kernel(KvGeom g, const uint32_t* 
 
 int launch_kv_append(cas_ctx* ctx, cas_kv* kv, int layer, int seq, const uint16_t* K, const uint16_t* V, int n_tok,
                      int pos0) {
-  if (n_tok <= 0) return CAS_OK;
+  return launch_kv_append_layers(ctx, kv, layer, 1, 0, seq, K, V, n_tok, pos0);
+}
+
+int launch_kv_append_layers(cas_ctx* ctx, cas_kv* kv, int layer0, int n_layers, size_t layer_stride, int seq,
+                            const uint16_t* K, const uint16_t* V, int n_tok, int pos0) {
+  if (n_tok <= 0 || n_layers <= 0) return CAS_OK;
   const KvGeom& g = kv->geom;
-  dim3 grid(n_tok, g.n_kv_heads, 2);
+  dim3 grid(n_tok, g.n_kv_heads, 2 * n_layers);
   hipLaunchKernelGGL(kv_append_kernel, grid, dim3(64), 0, ctx->stream, g, (uint32_t*)kv->d_spec,
-                     (uint32_t*)kv->d_verif, kv->d_page_table + (size_t)seq * g.max_pages_per_seq, layer, pos0, K, V);
+                     (uint32_t*)kv->d_verif, kv->d_page_table + (size_t)seq * g.max_pages_per_seq, layer0, pos0, K, V,
+                     layer_stride);
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;
 }

@@ -398,11 +398,11 @@ int cas_commit(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int n_accepted) 
   const int kvd = c.n_kv_heads * c.head_dim, n = n_accepted + 1;
   const int64_t cap = (int64_t)kv->desc.max_pages_per_seq * kv->desc.page_tokens;
   if ((int64_t)kv->h_len[seq] + n > cap) return CAS_ENOMEM;
-  for (int l = 0; l < c.n_layers; ++l) {
-    const size_t slots = ((size_t)seq * c.n_layers + l) * c.max_cols * kvd;
-    int rc = cas::launch_kv_append(ctx, kv, l, seq, m->knew + slots, m->vnew + slots, n, kv->h_len[seq]);
-    if (rc != CAS_OK) return rc;
-  }
+  // all layers in one launch: the slots of a sequence are [layer][max_cols][kv heads * 128]
+  const size_t slots = (size_t)seq * c.n_layers * c.max_cols * kvd;
+  int rc = cas::launch_kv_append_layers(ctx, kv, 0, c.n_layers, (size_t)c.max_cols * kvd, seq, m->knew + slots,
+                                        m->vnew + slots, n, kv->h_len[seq]);
+  if (rc != CAS_OK) return rc;
   kv->h_len[seq] += n;
   return CAS_OK;
 }
