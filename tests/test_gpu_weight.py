@@ -183,6 +183,31 @@ def test_fused_draft_gemv_variants_match_oracle(env, rows, cols):
     assert (act.cpu().numpy().view(np.uint16)[0] != aref).mean() < 0.05
 
 
+@pytest.mark.parametrize("rows,cols,batch", [(96, 4096, 4), (40, 14336, 3), (64, 300, 2)])
+def test_fused_draft_gemv_batch_equals_single_columns(env, rows, cols, batch):
+    """Every column of a batched fused call (norm prologue; fp32, residual and SwiGLU epilogues)
+    has exactly the bits of the one-column call: sequences decoded together do not influence
+    each other.  (One column stages x as fp32, a batch as bf16: the staged values are
+    bf16-representable, so nothing changes.)"""
+    torch, B, ctx = env
+    W = synth.weight_matrix(rows, cols, seed=9)
+    X = _dev(torch, synth.normal_bf16((batch, cols), 2.0, seed=10))
+    g = _dev(torch, synth.f32_to_bf16_bits(1.0 + 0.1 * np.random.default_rng(1).standard_normal(cols).astype(np.float32)))
+    H0 = _dev(torch, synth.normal_bf16((batch, rows), 1.0, seed=12))
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), 600, 4)
+    yb = B.cas_gemv_draft_fused(ctx, ew, X, y=torch.empty((batch, rows), device="cuda"), gain=g, eps=1e-5)
+    hb = H0.clone(); B.cas_gemv_draft_fused(ctx, ew, X, epilogue=1, out16=hb)
+    ab = torch.zeros((batch, rows // 2), dtype=torch.int16, device="cuda")
+    B.cas_gemv_draft_fused(ctx, ew, X, gain=g, eps=1e-5, epilogue=2, out16=ab)
+    for b in range(batch):
+        x1 = X[b:b + 1].contiguous()
+        y1 = B.cas_gemv_draft_fused(ctx, ew, x1, y=torch.empty((1, rows), device="cuda"), gain=g, eps=1e-5)
+        h1 = H0[b:b + 1].clone(); B.cas_gemv_draft_fused(ctx, ew, x1, epilogue=1, out16=h1)
+        a1 = torch.zeros((1, rows // 2), dtype=torch.int16, device="cuda")
+        B.cas_gemv_draft_fused(ctx, ew, x1, gain=g, eps=1e-5, epilogue=2, out16=a1)
+        assert torch.equal(yb[b:b + 1], y1) and torch.equal(hb[b:b + 1], h1) and torch.equal(ab[b:b + 1], a1)
+
+
 def _special_patterns(rows, cols, seed):
     """bf16 words that exercise the selection order and the bit split: +-0, subnormals, the
     largest finite values, +-Inf and NaNs with several payloads, among ordinary values."""
