@@ -14,7 +14,11 @@ Parity pins (tests/test_oracle_*.py): exhaustive bit-exact round trip over all
 subset search for the selection, closed-form stream sizes, library matmul /
 attention special cases, brute-force acceptance, speculative == plain token
 streams, and for the unary exponent code the printed code words, a sequential
-scan, the closed-form length and an exhaustive search over code assignments.  Parity unpinned: acceptance *rates* and speedups (the paper's tables
+scan, the closed-form length and an exhaustive search over code assignments; for the
+shared-exponent form the conversion restated as real arithmetic, the lossless special case,
+the error bound of one unit of the block's last place and hand-worked blocks.  Parity unpinned:
+block size, magnitude width and rounding of the shared-exponent form (the paper fixes none of
+them; the reading taken is stated at the functions); acceptance *rates* and speedups (the paper's tables
 for them are images that did not survive, and need trained weights).
 """
 from __future__ import annotations
@@ -382,6 +386,147 @@ def decode_full_unary(u: PackedUnary):
 
 def gemv_draft_unary(u: PackedUnary, x_u16):
     return gemv(decode_draft_unary(u), x_u16)
+
+
+# ----------------------------------------------------------------------------
+# Shared-exponent (MX) form of the speculation group (Sec. 4.2 "Exponent Compression",
+# first approach; decoder #N of Sec. 5.1; the lossy configuration, Cassandra-2)
+# ----------------------------------------------------------------------------
+MX_BLOCK = 32   # consecutive columns of a row that share one exponent
+MX_MAG_BITS = 8  # the bf16 significand with its hidden bit written out
+
+
+def _bf16_parts(w_u16):
+    """(sign, effective exponent, 8-bit significand): value = (-1)^s * sig * 2^(e - 134).
+    Subnormals and zeros have no hidden bit and exponent 1."""
+    w = np.asarray(w_u16, dtype=np.uint16).astype(np.int64)
+    exp = (w >> 7) & 0xFF
+    frac = w & 0x7F
+    return w >> 15, np.maximum(exp, 1), np.where(exp > 0, 0x80 | frac, frac)
+
+
+def mx_shared_exponents(w_u16, mask):
+    """Shared exponent of every block of MX_BLOCK columns: the largest exponent among its
+    kept values (0 for a block without kept values).  [rows, ceil(cols/32)] uint8."""
+    w = np.asarray(w_u16, dtype=np.uint16)
+    rows, cols = w.shape
+    nb = (cols + MX_BLOCK - 1) // MX_BLOCK
+    _, e, _ = _bf16_parts(w)
+    ek = np.zeros((rows, nb * MX_BLOCK), dtype=np.int64)
+    ek[:, :cols] = np.where(mask, e, 0)
+    return ek.reshape(rows, nb, MX_BLOCK).max(axis=2).astype(np.uint8)
+
+
+def mx_magnitudes(w_u16, mask, sexp):
+    """Sign and 8-bit magnitude of every kept value against its block's exponent: the
+    significand shifted right by the exponent difference, low bits dropped (no rounding,
+    as for the mantissa truncation of Sec. 4.2).  Entries outside the mask are 0."""
+    w = np.asarray(w_u16, dtype=np.uint16)
+    cols = w.shape[1]
+    s, e, sig = _bf16_parts(w)
+    E = np.repeat(sexp.astype(np.int64), MX_BLOCK, axis=1)[:, :cols]
+    shift = np.clip(E - e, 0, MX_MAG_BITS)
+    mag = np.where(mask, sig >> shift, 0)
+    return np.where(mask, s, 0).astype(np.uint16), mag.astype(np.uint16)
+
+
+def mx_to_bf16(sign, E, mag):
+    """Decoder #N of Sec. 5.1 for one value: count the leading zeros of the magnitude, shift
+    them out, subtract the count from the shared exponent.  The result is exactly
+    (-1)^s * mag * 2^(E - 134), always a bf16 value (subnormal when the exponent runs out)."""
+    sign, E, mag = int(sign), int(E), int(mag)
+    if mag == 0:
+        return sign << 15
+    lz = MX_MAG_BITS - mag.bit_length()
+    e = E - lz
+    if e >= 1:
+        return (sign << 15) | (e << 7) | ((mag << lz) & 0x7F)
+    return (sign << 15) | (mag << (E - 1))
+
+
+@dataclasses.dataclass
+class PackedMX:
+    """Shared-exponent form of a packed matrix.  base supplies bitmap and pruned stream;
+      sexp[r, b] : shared exponent of block b (the 32 columns of bitmap word b)
+      field[r]   : K fields of 9-t bits = sign, then the 8-t leading magnitude bits
+      lo[r]      : K fields of t bits, the dropped magnitude bits (verification data)."""
+    base: Packed
+    sexp: np.ndarray
+    field: np.ndarray
+    lo: np.ndarray
+
+
+def to_mx(p: Packed) -> PackedMX:
+    """Exponent sharing first, truncation second (the order Sec. 4.2 states): the kept
+    values of a packed matrix -> shared exponents, sign+magnitude split at t bits."""
+    mask = unpack_mask(p)
+    w = decode_full(p)
+    sexp = mx_shared_exponents(w, mask)
+    s, mag = mx_magnitudes(w, mask, sexp)
+    sk = s[mask].reshape(p.rows, p.K).astype(np.uint32)
+    mk = mag[mask].reshape(p.rows, p.K).astype(np.uint32)
+    hb = MX_MAG_BITS - p.t
+    field = (sk << hb) | (mk >> p.t)
+    lo = mk & ((1 << p.t) - 1)
+    return PackedMX(p, sexp, _pack_fields(field, hb + 1, _words(p.K * (hb + 1))),
+                    _pack_fields(lo, p.t, _words(p.K * p.t)))
+
+
+def _decode_mx(m: PackedMX, full: bool):
+    p = m.base
+    hb = MX_MAG_BITS - p.t
+    mask = unpack_mask(p)
+    field = _unpack_fields(m.field, hb + 1, p.K).astype(np.int64)
+    lo = _unpack_fields(m.lo, p.t, p.K).astype(np.int64)
+    out = np.zeros((p.rows, p.cols), dtype=np.uint16)
+    if full:
+        out[~mask] = _unpack_fields(p.pruned, 16, p.cols - p.K).reshape(-1)
+    for r in range(p.rows):
+        cols_kept = np.nonzero(mask[r])[0]
+        for e, c in enumerate(cols_kept):
+            mag = (field[r, e] & ((1 << hb) - 1)) << p.t
+            if full:
+                mag |= lo[r, e]
+            out[r, c] = mx_to_bf16(field[r, e] >> hb, m.sexp[r, c // MX_BLOCK], mag)
+    return out
+
+
+def decode_draft_mx(m: PackedMX):
+    """Draft view of the shared-exponent form: leading magnitude bits only, pruned
+    positions +0 (zero padding, Sec. 4.1)."""
+    return _decode_mx(m, False)
+
+
+def decode_full_mx(m: PackedMX):
+    """Target view: all magnitude bits, pruned values merged back unchanged.  Equals the
+    shared-exponent conversion of the kept values, not the original matrix (Sec. 4.2: this
+    configuration trades accuracy for size)."""
+    return _decode_mx(m, True)
+
+
+def mx_convert(w_u16, mask):
+    """The conversion stated as arithmetic on real numbers: per block, scale 2^(E - 134)
+    with E the largest kept exponent; every kept finite value becomes the scale times the
+    integer part of |value| / scale, sign kept.  Other entries pass through."""
+    w = np.asarray(w_u16, dtype=np.uint16)
+    rows, cols = w.shape
+    out = w.copy()
+    v = bf16_to_f64(w)
+    for r in range(rows):
+        for b0 in range(0, cols, MX_BLOCK):
+            idx = b0 + np.nonzero(mask[r, b0:b0 + MX_BLOCK])[0]
+            if idx.size == 0:
+                continue
+            amax = np.abs(v[r, idx]).max()
+            E = max(int(math.floor(math.log2(amax))) + 127, 1) if amax > 0 else 1
+            scale = math.ldexp(1.0, E - 134)
+            q = np.floor(np.abs(v[r, idx]) / scale) * scale
+            out[r, idx] = f64_to_bf16(np.copysign(q, v[r, idx]))
+    return out
+
+
+def gemv_draft_mx(m: PackedMX, x_u16):
+    return gemv(decode_draft_mx(m), x_u16)
 
 
 # ----------------------------------------------------------------------------
