@@ -192,6 +192,54 @@ int cas_unary_decode(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, 
 int cas_gemv_draft_unary(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, const uint16_t* d_x,
                          float* d_y);
 
+/* ---- speculation data with shared exponents (Sec. 4.2 "Exponent Compression", the MX
+ *      approach: the lossy, smaller configuration; decoder of Sec. 5.1, leading-zero count
+ *      and shift against the shared exponent) ---- */
+
+/*
+ * The shared-exponent form is written from an encoded matrix and keeps its selection.  The
+ * paper fixes neither block size, magnitude width nor rounding; this library takes: a block
+ * is the 32 columns of one bitmap word; its exponent E is the largest exponent field among
+ * the block's kept values (fields 0 and 1 both count as 1; 0 for a block without kept
+ * values); a kept value becomes sign + 8-bit magnitude = its significand with the hidden bit
+ * written out, shifted right by (E - its exponent), low bits dropped, so that
+ * value' = (-1)^sign * magnitude * 2^(E - 134).  Truncation then splits the magnitude: the
+ * 8-t leading bits go to the speculation buffer, the t low bits to the verification buffer.
+ * Pruned values stay as they are.  Non-finite values are treated as numbers with exponent 255.
+ *   MX speculation buffer : bitmap (bw words per row) | sexp (uint8 per bitmap word, ew bytes
+ *                           per row, ew = bw rounded up to 4) | field (K fields of 9-t bits:
+ *                           sign above the magnitude bits, ascending column; fw words per row)
+ *   MX verification buffer: lo (K fields of t bits; lw words per row) | pruned (as cas_wdesc)
+ * Regions are 256-byte aligned and followed by 256 bytes of slack.  Plain data.
+ */
+typedef struct {
+  cas_wdesc base;   /* the matrix this was written from: rows, cols, K, t, bw, lw, pw */
+  int32_t fw, ew;
+  int64_t off_bitmap, off_sexp, off_field;  /* byte offsets in the MX speculation buffer */
+  int64_t off_lo, off_pruned;               /* byte offsets in the MX verification buffer */
+  int64_t spec_bytes, verif_bytes;          /* sizes the caller must allocate */
+} cas_mxdesc;
+
+/* Layout of the shared-exponent form of *desc (host only, no device work). */
+int cas_mx_plan(const cas_wdesc* desc, cas_mxdesc* out);
+
+/* Writes both MX buffers (device, 256-byte aligned, sizes from the descriptor) from the raw
+ * encoding d_spec / d_verif of the same matrix.  Stream-ordered, no synchronisation. */
+int cas_mx_encode(cas_ctx* ctx, const cas_mxdesc* mx, const void* d_spec, const void* d_verif,
+                  void* d_mxspec, void* d_mxverif);
+
+/* Reconstruction: d_mxverif = NULL gives the draft view (leading magnitude bits, pruned
+ * positions +0), otherwise the converted matrix (all magnitude bits, pruned values merged
+ * back).  d_out: [rows][ld] bf16 words. */
+int cas_mx_decode(cas_ctx* ctx, const cas_mxdesc* mx, const void* d_mxspec, const void* d_mxverif,
+                  uint16_t* d_out, int64_t ld);
+
+/* Draft GEMV y = Wdraft x from the MX speculation buffer alone (Sec. 4.1 draft inference on
+ * the shared-exponent format).  d_x: bf16 [cols]; d_y: float [rows].  CAS_ENOTSUP if x does
+ * not fit the LDS. */
+int cas_gemv_draft_mx(cas_ctx* ctx, const cas_mxdesc* mx, const void* d_mxspec, const uint16_t* d_x,
+                      float* d_y);
+
 /* ---- compressed, paged KV cache (Sec. 4.2 per-token pruning, Sec. 5.1 online encoder) ---- */
 
 /*

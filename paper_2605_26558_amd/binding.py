@@ -57,6 +57,13 @@ class cas_tensor(C.Structure):
     _fields_ = [("desc", cas_wdesc), ("d_spec", C.c_void_p), ("d_verif", C.c_void_p)]
 
 
+class cas_mxdesc(C.Structure):
+    _fields_ = [("base", cas_wdesc), ("fw", C.c_int32), ("ew", C.c_int32),
+                ("off_bitmap", C.c_int64), ("off_sexp", C.c_int64), ("off_field", C.c_int64),
+                ("off_lo", C.c_int64), ("off_pruned", C.c_int64),
+                ("spec_bytes", C.c_int64), ("verif_bytes", C.c_int64)]
+
+
 class cas_layer_weights(C.Structure):
     _fields_ = [("wqkv", cas_tensor), ("wo", cas_tensor), ("wgu", cas_tensor), ("wd", cas_tensor),
                 ("d_g_attn", C.c_void_p), ("d_g_ffn", C.c_void_p)]
@@ -131,6 +138,10 @@ _SIGNATURES = {
     "cas_unary_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p]),
     "cas_unary_decode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
     "cas_gemv_draft_unary": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p]),
+    "cas_mx_plan": (C.c_int, [C.POINTER(cas_wdesc), C.POINTER(cas_mxdesc)]),
+    "cas_mx_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "cas_mx_decode": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
+    "cas_gemv_draft_mx": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p]),
 }
 
 
@@ -301,6 +312,52 @@ def cas_gemv_draft_unary(ctx: Context, uw: UnaryWeight, x, out=None):
         out = torch.empty(d.rows, dtype=torch.float32, device=x.device)
     ctx._check(_lib().cas_gemv_draft_unary(ctx.h, C.byref(uw.desc), _ptr(uw.uspec), _ptr(x), _ptr(out)),
                "cas_gemv_draft_unary")
+    return out
+
+
+class MxWeight:
+    """Shared-exponent form of an encoded matrix: descriptor and its two buffers."""
+
+    def __init__(self, desc, spec, verif):
+        self.desc, self.spec, self.verif = desc, spec, verif
+
+
+def cas_mx_plan(desc: cas_wdesc) -> cas_mxdesc:
+    m = cas_mxdesc()
+    rc = _lib().cas_mx_plan(C.byref(desc), C.byref(m))
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_mx_plan")
+    return m
+
+
+def cas_mx_encode(ctx: Context, ew: EncodedWeight) -> MxWeight:
+    torch = ctx._torch
+    m = cas_mx_plan(ew.desc)
+    spec = torch.empty(m.spec_bytes, dtype=torch.uint8, device=ew.spec.device)
+    verif = torch.empty(m.verif_bytes, dtype=torch.uint8, device=ew.spec.device)
+    ctx._check(_lib().cas_mx_encode(ctx.h, C.byref(m), _ptr(ew.spec), _ptr(ew.verif), _ptr(spec), _ptr(verif)),
+               "cas_mx_encode")
+    return MxWeight(m, spec, verif)
+
+
+def cas_mx_decode(ctx: Context, mw: MxWeight, full: bool):
+    torch = ctx._torch
+    d = mw.desc.base
+    out = torch.empty((d.rows, d.cols), dtype=torch.int16, device=mw.spec.device)
+    ctx._check(_lib().cas_mx_decode(ctx.h, C.byref(mw.desc), _ptr(mw.spec), _ptr(mw.verif) if full else None,
+                                    _ptr(out), d.cols), "cas_mx_decode")
+    return out
+
+
+def cas_gemv_draft_mx(ctx: Context, mw: MxWeight, x, out=None):
+    """x: bf16 bits [cols] or [1, cols] -> float32 [rows]."""
+    torch = ctx._torch
+    d = mw.desc.base
+    assert x.numel() == d.cols and x.is_contiguous() and x.element_size() == 2
+    if out is None:
+        out = torch.empty(d.rows, dtype=torch.float32, device=x.device)
+    ctx._check(_lib().cas_gemv_draft_mx(ctx.h, C.byref(mw.desc), _ptr(mw.spec), _ptr(x), _ptr(out)),
+               "cas_gemv_draft_mx")
     return out
 
 

@@ -1,6 +1,6 @@
 """Small driver for hardware-counter runs (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE): one plain
 device-to-device copy of known size (the calibration kernel) followed by draft-GEMV,
-verify-GEMM and unary draft-GEMV launches on Llama-3-8B gate/up shaped matrices (28672 x 4096, paper-default
+verify-GEMM, unary and shared-exponent draft-GEMV launches on Llama-3-8B gate/up shaped matrices (28672 x 4096, paper-default
 format).  Prints the algorithmic bytes of each launch so counter readings can be compared."""
 import os
 import sys
@@ -37,6 +37,10 @@ def main():
     for _ in range(3):
         for u in umats:
             B.cas_gemv_draft_unary(ctx, u, x1, yu)
+    xmats = [B.cas_mx_encode(ctx, m) for m in mats]        # shared-exponent form of the same matrices
+    for _ in range(3):
+        for xm in xmats:
+            B.cas_gemv_draft_mx(ctx, xm, x1, yu)
     torch.cuda.synchronize()
     d = mats[0].desc
     print("copy_bytes_read", src.numel() * 4, "copy_bytes_written", src.numel() * 4)
@@ -44,6 +48,8 @@ def main():
     print("gemm_verify_algorithmic_bytes", rows * (d.bw + d.sw + d.lw + d.pw) * 4)
     u = umats[0].desc
     print("gemv_draft_unary_algorithmic_bytes", rows * (d.bw + u.smw) * 4 + (u.ue_words + rows + 1) * 4)
+    xd = xmats[0].desc
+    print("gemv_draft_mx_algorithmic_bytes", rows * (d.bw * 4 + d.bw + xd.fw * 4))
 
 
 if __name__ == "__main__":

@@ -41,6 +41,11 @@ def test_host_only_calls_work_without_a_gpu():
             for rs in itertools.product([0.0, 0.29, 0.31, 0.99], repeat=gamma):
                 p, q = [x * 0.4 for x in ratios], [0.4] * gamma
                 assert B.cas_accept_sampling(p, q, rs) == O.accept_sampling(p, q, rs)
+    # layout of the shared-exponent form: 9-t bits per kept value, one exponent byte per bitmap word
+    m = B.cas_mx_plan(d)
+    assert (m.fw, m.ew) == ((2458 * 5 + 31) // 32, 128)
+    assert m.off_sexp % 256 == 0 and m.off_field % 256 == 0 and m.off_pruned % 256 == 0
+    assert m.spec_bytes >= m.off_field + 4096 * m.fw * 4 and m.verif_bytes >= m.off_pruned + 4096 * d.pw * 4
     import pytest
     with pytest.raises(B.CasError):
         B.cas_weight_desc(8, 8, 600, 9)
