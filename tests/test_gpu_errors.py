@@ -1,0 +1,93 @@
+"""Error behaviour of the C ABI as the header states it: requests outside the limits come back
+as an error code from the host-side checks, before any kernel is launched."""
+import copy
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2605_26558_amd import binding as B
+    return torch, B, B.Context()
+
+
+def _dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+
+
+def _code(B, fn):
+    with pytest.raises(B.CasError) as e:
+        fn()
+    return e.value.code
+
+
+def test_linear_entry_points_reject_what_they_cannot_do(env):
+    torch, B, ctx = env
+    lib = B._lib()
+    ew = B.cas_encode_weight(ctx, _dev(torch, synth.weight_matrix(32, 256, seed=1)), 600, 4)
+    X = _dev(torch, synth.activations(256, 17, seed=2))
+    y = torch.empty((17, 32), device="cuda")
+    # batch and column limits
+    assert lib.cas_gemv_draft(ctx.h, C.byref(ew.desc), B._ptr(ew.spec), B._ptr(X), 5, B._ptr(y)) == B.CAS_EINVAL
+    assert lib.cas_gemv_draft(ctx.h, C.byref(ew.desc), B._ptr(ew.spec), B._ptr(X), 0, B._ptr(y)) == B.CAS_EINVAL
+    assert lib.cas_gemm_verify(ctx.h, C.byref(ew.desc), B._ptr(ew.spec), B._ptr(ew.verif), B._ptr(X), 17,
+                               B._ptr(y)) == B.CAS_EINVAL
+    # a speculation buffer that is not 256-byte aligned, a missing buffer
+    off = C.c_void_p(ew.spec.data_ptr() + 64)
+    assert lib.cas_gemv_draft(ctx.h, C.byref(ew.desc), off, B._ptr(X), 1, B._ptr(y)) == B.CAS_EINVAL
+    assert lib.cas_gemm_verify(ctx.h, C.byref(ew.desc), B._ptr(ew.spec), None, B._ptr(X), 1, B._ptr(y)) == B.CAS_EINVAL
+    # a descriptor whose stream widths do not belong to its shape
+    bad = copy.copy(ew.desc)
+    bad.sw += 1
+    assert lib.cas_gemv_draft(ctx.h, C.byref(bad), B._ptr(ew.spec), B._ptr(X), 1, B._ptr(y)) == B.CAS_EINVAL
+    # the valid call still works afterwards
+    assert B.cas_gemv_draft(ctx, ew, X[:1].contiguous()).shape == (1, 32)
+
+
+def test_rows_too_long_for_the_lds_are_not_supported(env):
+    torch, B, ctx = env
+    cols = 49152           # 48 K fp32 activations + segment padding exceed one workgroup's LDS
+    W = torch.zeros((2, cols), dtype=torch.int16, device="cuda")
+    ew = B.cas_encode_weight(ctx, W, 600, 4)
+    x = torch.zeros((1, cols), dtype=torch.int16, device="cuda")
+    assert _code(B, lambda: B.cas_gemv_draft(ctx, ew, x)) == B.CAS_ENOTSUP
+    mw = B.cas_mx_encode(ctx, ew)
+    assert _code(B, lambda: B.cas_gemv_draft_mx(ctx, mw, x)) == B.CAS_ENOTSUP
+
+
+def test_shared_exponent_descriptor_is_checked(env):
+    torch, B, ctx = env
+    lib = B._lib()
+    ew = B.cas_encode_weight(ctx, _dev(torch, synth.weight_matrix(8, 96, seed=3)), 600, 4)
+    mw = B.cas_mx_encode(ctx, ew)
+    x = _dev(torch, synth.activations(96, 1, seed=4))
+    y = torch.empty(8, device="cuda")
+    bad = copy.copy(mw.desc)
+    bad.off_field += 256
+    assert lib.cas_gemv_draft_mx(ctx.h, C.byref(bad), B._ptr(mw.spec), B._ptr(x), B._ptr(y)) == B.CAS_EINVAL
+    assert lib.cas_mx_decode(ctx.h, C.byref(mw.desc), B._ptr(mw.spec), None, B._ptr(y), 95) == B.CAS_EINVAL  # ld < cols
+    with pytest.raises(B.CasError):
+        d = copy.copy(ew.desc); d.t = 9
+        B.cas_mx_plan(d)
+
+
+def test_attention_limits(env):
+    torch, B, ctx = env
+    kv = B.KVCache(ctx, 1, 2, n_pages=2, max_seqs=1, max_pages_per_seq=2)
+    z = lambda *s: torch.zeros(s, dtype=torch.int16, device="cuda")
+    # 17 columns; a head count that is no multiple of the kv heads; fewer in-flight vectors than columns
+    assert _code(B, lambda: B.cas_attention(ctx, kv, 0, 0, True, z(17, 2, 128), z(17, 2, 128), z(17, 2, 128))) == B.CAS_EINVAL
+    assert _code(B, lambda: B.cas_attention(ctx, kv, 0, 0, True, z(1, 3, 128), z(1, 2, 128), z(1, 2, 128))) == B.CAS_EINVAL
+    assert _code(B, lambda: B.cas_attention(ctx, kv, 0, 0, False, z(2, 2, 128), z(1, 2, 128), z(1, 2, 128))) == B.CAS_EINVAL
+    # layer and sequence out of range
+    assert _code(B, lambda: B.cas_attention(ctx, kv, 1, 0, False, z(1, 2, 128), z(1, 2, 128), z(1, 2, 128))) == B.CAS_EINVAL
+    assert _code(B, lambda: B.cas_attention(ctx, kv, 0, 1, False, z(1, 2, 128), z(1, 2, 128), z(1, 2, 128))) == B.CAS_EINVAL
+    # appending past the pages a sequence may hold
+    assert _code(B, lambda: B.cas_kv_append(ctx, kv, 0, 0, z(129, 2, 128), z(129, 2, 128))) == B.CAS_ENOMEM
