@@ -135,7 +135,7 @@ int cas_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec
 
 /* Verification GEMM (Sec. 2.2 batched verification, Sec. 4.1 target inference):
  * Y[c][r] = sum_j W[r][j] * X[c][j] with W the exact bf16 matrix rebuilt from both buffers.
- * d_X: bf16 [ncols][cols]; d_Y: float [ncols][rows]; ncols in 1..16.  The value of a column
+ * d_X: bf16 [ncols][cols]; d_Y: float [ncols][rows]; ncols in 1..32.  The value of a column
  * does not depend on ncols or on the other columns. */
 int cas_gemm_verify(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
                     const void* d_verif, const uint16_t* d_X, int ncols, float* d_Y);
@@ -315,7 +315,9 @@ int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const 
  * -> residual; final RMSNorm and output head; greedy token = lowest index among the maxima. */
 typedef struct {
   int32_t hidden, n_layers, n_q_heads, n_kv_heads, head_dim /* 128 */, ffn, vocab;
-  int32_t max_cols; /* largest k+1 (1..16); also the number of in-flight K/V slots per layer */
+  int32_t max_cols; /* columns one pass may carry (1..32); also the number of in-flight K/V slots per
+                       sequence and layer.  One sequence contributes at most 16 columns to a pass, and
+                       at most 80 / (n_q_heads / n_kv_heads). */
   int32_t max_pos;  /* rows of the rotary table */
   float rms_eps;
   int32_t max_seqs; /* sequences that may have positions in flight at once (0 means 1): every
@@ -402,8 +404,8 @@ int cas_spec_round(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, int32_t 
 int cas_spec_round_multi(cas_ctx* ctx, cas_model* model, cas_kv* kv, int n_seqs, const int32_t* h_seqs,
                          const int32_t* h_pending, int k, int32_t* h_out, int32_t* h_n_accepted);
 
-/* Prefill (functional): runs n prompt tokens through the target path in chunks of max_cols
- * columns and commits all of them.  d_tokens: int32 [n] on the device. */
+/* Prefill (functional): runs n prompt tokens through the target path in chunks of as many
+ * columns as one sequence may bring to a pass (see max_cols) and commits all of them.  d_tokens: int32 [n] on the device. */
 int cas_prefill(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const int32_t* d_tokens, int n);
 
 /* Greedy acceptance (Sec. 2.2).  Host only, no side effects.  h_draft: k drafted tokens;

@@ -151,7 +151,7 @@ int cas_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec
 
 int cas_gemm_verify(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec, const void* d_verif,
                     const uint16_t* d_X, int ncols, float* d_Y) {
-  if (!ctx || check_desc(desc) != CAS_OK || ncols < 1 || ncols > 16) return CAS_EINVAL;
+  if (!ctx || check_desc(desc) != CAS_OK || ncols < 1 || ncols > 32) return CAS_EINVAL;
   if (desc->rows == 0) return CAS_OK;
   if (!d_spec || !d_verif || !d_X || !d_Y) return CAS_EINVAL;
   if (!cas::aligned256(d_spec) || !cas::aligned256(d_verif)) return CAS_EINVAL;

@@ -159,6 +159,12 @@ struct ColGroup {
 static int model_seqs(const cas_model_cfg& c) { return c.max_seqs > 0 ? c.max_seqs : 1; }
 
 // Runs the columns of `ng` groups (token ids on the device, group after group) through the
+
+// columns one sequence may contribute to a pass: what one attention call takes
+static int seq_cols_max(const cas_model_cfg& c) {
+  return std::min({(int)c.max_cols, 16, 80 / (c.n_q_heads / c.n_kv_heads)});
+}
+
 // model in one pass: the linear layers see all columns at once, attention runs per sequence.
 static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, int ng, const int32_t* d_tokens,
                    bool full, int32_t* d_out, float* d_logits) {
@@ -169,6 +175,7 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, 
     const ColGroup& g = grp[i];
     if (g.seq < 0 || g.seq >= kv->desc.max_seqs || g.seq >= model_seqs(c) || g.ncols < 1 || g.slot0 < 0)
       return CAS_EINVAL;
+    if (g.ncols > seq_cols_max(c)) return CAS_EINVAL;
     if (kv->h_len[g.seq] + g.slot0 + g.ncols > c.max_pos || g.slot0 + g.ncols > c.max_cols) return CAS_EINVAL;
     for (int j = 0; j < i; ++j)
       if (grp[j].seq == g.seq) return CAS_EINVAL;  // one run per sequence and pass
@@ -269,9 +276,9 @@ static int check_cfg(const cas_model_cfg* c) {
   if (!c || c->hidden < 1 || c->n_layers < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->ffn < 1 || c->vocab < 1)
     return CAS_EINVAL;
   if (c->head_dim != 128) return CAS_ENOTSUP;
-  if (c->n_q_heads % c->n_kv_heads != 0 || c->max_cols < 1 || c->max_cols > 16 || c->max_pos < 1) return CAS_EINVAL;
+  if (c->n_q_heads % c->n_kv_heads != 0 || c->max_cols < 1 || c->max_cols > 32 || c->max_pos < 1) return CAS_EINVAL;
   if (c->max_seqs < 0 || c->max_seqs > 64) return CAS_EINVAL;
-  if (c->max_cols * (c->n_q_heads / c->n_kv_heads) > 80 || c->n_q_heads / c->n_kv_heads > 48) return CAS_EINVAL;
+  if (c->n_q_heads / c->n_kv_heads > 48) return CAS_EINVAL;
   return CAS_OK;
 }
 
@@ -467,7 +474,7 @@ int cas_spec_round_multi(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, con
 int cas_prefill(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_tokens, int n) {
   if (check_step(ctx, m, kv, seq) != CAS_OK || !d_tokens || n < 0) return CAS_EINVAL;
   for (int done = 0; done < n;) {
-    const int nc = std::min(n - done, (int)m->cfg.max_cols);
+    const int nc = std::min(n - done, cas::seq_cols_max(m->cfg));
     const cas::ColGroup g{seq, nc, 0};
     int rc = cas::forward(ctx, m, kv, &g, 1, d_tokens + done, true, nullptr, nullptr);
     if (rc != CAS_OK) return rc;

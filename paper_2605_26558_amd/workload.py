@@ -153,9 +153,9 @@ class ModelRoundWorkload:
         rope = torch.from_numpy(synth.rope_table(max_pos, shape.head_dim, shape.rope_theta)).cuda()
         self.layers, self.head, self.g_final = layers, head, gain()
         nb = self.batch
-        # 16 columns per verification pass at most; more sequences x drafts take a second pass
+        # 32 columns per verification pass at most; more sequences x drafts take a second pass
         self.model = B.Model(ctx, shape, layers, head, embed, self.g_final, rope,
-                             max_cols=min(16, nb * (self.k + 1)), max_seqs=nb)
+                             max_cols=min(32, nb * (self.k + 1)), max_seqs=nb)
         pages = (max_pos + 63) // 64
         self.kv = B.KVCache(ctx, shape.n_layers, shape.n_kv_heads, n_pages=pages * nb, max_seqs=nb,
                             max_pages_per_seq=pages, keep_permille=args.keep, trunc_bits=args.trunc)
@@ -187,8 +187,8 @@ class ModelRoundWorkload:
         self.verify_kv = per_tok_full * self.ctx_len
         self.values = sum(m.desc.rows * m.desc.cols for m in mats)
         # a pass reads the weights once for all sequences and every sequence's cache; the
-        # verification columns go into passes of at most 16 columns
-        per_pass = max(1, min(nb, 16 // (self.k + 1)))
+        # verification columns go into passes of at most 32 columns
+        per_pass = max(1, min(nb, 32 // (self.k + 1)))
         self.draft_kv *= nb
         self.verify_kv *= nb
         self.verify_w *= (nb + per_pass - 1) // per_pass

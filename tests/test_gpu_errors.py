@@ -32,12 +32,12 @@ def test_linear_entry_points_reject_what_they_cannot_do(env):
     torch, B, ctx = env
     lib = B._lib()
     ew = B.cas_encode_weight(ctx, _dev(torch, synth.weight_matrix(32, 256, seed=1)), 600, 4)
-    X = _dev(torch, synth.activations(256, 17, seed=2))
-    y = torch.empty((17, 32), device="cuda")
+    X = _dev(torch, synth.activations(256, 33, seed=2))
+    y = torch.empty((33, 32), device="cuda")
     # batch and column limits
     assert lib.cas_gemv_draft(ctx.h, C.byref(ew.desc), B._ptr(ew.spec), B._ptr(X), 5, B._ptr(y)) == B.CAS_EINVAL
     assert lib.cas_gemv_draft(ctx.h, C.byref(ew.desc), B._ptr(ew.spec), B._ptr(X), 0, B._ptr(y)) == B.CAS_EINVAL
-    assert lib.cas_gemm_verify(ctx.h, C.byref(ew.desc), B._ptr(ew.spec), B._ptr(ew.verif), B._ptr(X), 17,
+    assert lib.cas_gemm_verify(ctx.h, C.byref(ew.desc), B._ptr(ew.spec), B._ptr(ew.verif), B._ptr(X), 33,
                                B._ptr(y)) == B.CAS_EINVAL
     # a speculation buffer that is not 256-byte aligned, a missing buffer
     off = C.c_void_p(ew.spec.data_ptr() + 64)

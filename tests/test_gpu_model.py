@@ -223,13 +223,14 @@ def test_multi_sequence_passes_equal_single_sequence_passes(env):
             assert torch.equal(Ka, Kb) and torch.equal(Va, Vb)
 
 
-@pytest.mark.parametrize("max_cols", [12, 8, 4])
-def test_multi_sequence_round_equals_single_sequence_rounds(env, max_cols):
+@pytest.mark.parametrize("max_cols,k,nseq", [(12, 3, 3), (8, 3, 3), (4, 3, 3), (20, 4, 4), (32, 7, 4)])
+def test_multi_sequence_round_equals_single_sequence_rounds(env, max_cols, k, nseq):
     """cas_spec_round_multi emits, sequence by sequence, the stream cas_spec_round emits, also
-    when the verification columns of the three sequences need two or three passes."""
+    when the verification columns of the sequences need two or three passes, and when one pass
+    carries more than 16 columns (20 and 32: the second column block of the verify GEMM)."""
     torch, B, ctx = env
-    print(f"case max_cols={max_cols}", flush=True)
-    keep, t, k, nseq = 600, 4, 3, 3
+    print(f"case max_cols={max_cols} k={k} nseq={nseq}", flush=True)
+    keep, t = 600, 4
     weights = synth.model_weights(SHAPE, seed=2)
     model, _ = gpu_model(torch, B, ctx, weights, keep, t, max_cols=12)
     # same weights, room for three sequences
@@ -239,7 +240,7 @@ def test_multi_sequence_round_equals_single_sequence_rounds(env, max_cols):
         return B.KVCache(ctx, SHAPE.n_layers, SHAPE.n_kv_heads, n_pages=2 * nseq, max_seqs=nseq, max_pages_per_seq=2,
                          keep_permille=keep, trunc_bits=t)
     kv_a, kv_b = cache(), cache()
-    prompts = [synth.token_ids(n, SHAPE.vocab, seed=40 + n) for n in (5, 20, 33)]
+    prompts = [synth.token_ids(n, SHAPE.vocab, seed=40 + n) for n in (5, 20, 33, 11)[:nseq]]
     for kv in (kv_a, kv_b):
         for s, p in enumerate(prompts):
             B.cas_prefill(ctx, model, kv, s, torch.from_numpy(p[:-1].copy()).cuda())

@@ -120,6 +120,27 @@ def test_gemm_verify_matches_oracle_and_is_column_invariant(env, rows, cols, kee
     np.testing.assert_array_equal(Y9[:5], Y)
 
 
+@pytest.mark.parametrize("rows,cols,keep,t", [(70, 4096, 600, 4), (33, 2500, 250, 0), (300, 300, 1000, 7), (20, 9000, 600, 3)])
+@pytest.mark.parametrize("ncols", [9, 16, 20, 32])
+def test_gemm_verify_many_columns(env, rows, cols, keep, t, ncols):
+    """9 to 32 columns (X staged per decode step; a second block of output columns above 16):
+    against the oracle, and every column bit-identical to the one-column call."""
+    torch, B, ctx = env
+    print(f"case rows={rows} cols={cols} keep={keep} t={t} ncols={ncols}", flush=True)
+    W = synth.weight_matrix(rows, cols, seed=rows + cols)
+    X = synth.activations(cols, ncols, seed=13)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t)
+    Xd = _dev(torch, X)
+    Y = B.cas_gemm_verify(ctx, ew, Xd).cpu().numpy()
+    ref = O.bf16_to_f64(X) @ O.bf16_to_f64(W).T
+    err = np.abs(Y - ref) / _tol(W, X)
+    assert err.max() < 2e-3
+    assert err.max() < 2e-5, err.max()
+    for c in sorted({0, 7, 8, 15, 16, ncols - 1} & set(range(ncols))):
+        y1 = B.cas_gemm_verify(ctx, ew, Xd[c:c + 1].contiguous()).cpu().numpy()
+        np.testing.assert_array_equal(y1[0], Y[c])
+
+
 def test_config0_full_size_linear_layer(env):
     """W 4096x4096, 0.5 % outlier input columns, 25 % kept, t = 4, one draft GEMV and a
     verify GEMM with k = 4 extra columns."""
