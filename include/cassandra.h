@@ -187,8 +187,8 @@ int cas_unary_decode(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, 
 
 /* Draft GEMV y = Wdraft x read from the unary speculation buffer alone (Sec. 4.1 draft
  * inference on the Sec. 4.2 lossless format).  d_x: bf16 [cols]; d_y: float [rows].  Same values
- * as cas_gemv_draft on the raw form up to summation order.  CAS_ENOTSUP if x and the
- * exponents of four rows do not fit the LDS. */
+ * as cas_gemv_draft on the raw form up to summation order.  CAS_ENOTSUP if x (as fp32) and
+ * the exponents of eight rows do not fit the LDS. */
 int cas_gemv_draft_unary(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, const uint16_t* d_x,
                          float* d_y);
 

@@ -118,8 +118,12 @@ __global__ __launch_bounds__(256) void unary_emit_kernel(UnaryArgs a) {
   }
 }
 
-// Exponents of the K kept values of one row into exps[] (LDS), by one wave.  ue_row: the row's
-// code words (nw of them); tab: exp_of_rank in LDS.  All 64 lanes must call this together.
+constexpr int kExpSlack = 32;  // bytes behind a row's K exponents: exhausted lanes read them, and a code
+                               // stream with more codes than values spills into them instead of beyond
+
+// Exponents of the K kept values of one row into exps[] (LDS, K + kExpSlack bytes), by one
+// wave.  ue_row: the row's code words (nw of them); tab: exp_of_rank in LDS.  All 64 lanes must
+// call this together.
 __device__ __forceinline__ void unary_row_exponents(const uint32_t* __restrict__ ue_row, int nw, int K,
                                                     const uint8_t* tab, uint8_t* exps, int lane) {
   int ebase = 0, prev_end = -1;  // wave-uniform: codes decoded, position of the last one-bit so far
@@ -128,7 +132,7 @@ __device__ __forceinline__ void unary_row_exponents(const uint32_t* __restrict__
     uint32_t u = w < nw ? ue_row[w] : 0u;
     const int cnt = __popc(u);
     const int incl = wave_incl_scan(cnt);
-    int e = ebase + incl - cnt;
+    uint8_t* p = exps + min(ebase + incl - cnt, K);  // the lane's codes are consecutive values
     ebase += __builtin_amdgcn_readlane(incl, 63);
     const int last = u ? 32 * w + 31 - __clz(u) : -1;
     const int imax = wave_incl_max(last);
@@ -136,13 +140,13 @@ __device__ __forceinline__ void unary_row_exponents(const uint32_t* __restrict__
     if (lane == 0) pe = -1;
     pe = max(pe, prev_end);
     prev_end = max(prev_end, __builtin_amdgcn_readlane(imax, 63));
+    int q = pe + 1 - 32 * w;  // first bit after the previous one-bit, relative to this word
     while (__builtin_amdgcn_ballot_w64(u != 0u)) {
       if (u) {
-        const int g = 32 * w + lowest_bit(u);
+        const int pos = lowest_bit(u);
         u &= u - 1u;
-        if (e < K) exps[e] = tab[(g - pe - 1) & 255];
-        pe = g;
-        ++e;
+        *p++ = tab[(pos - q) & 255];  // rank = zeros since the previous one-bit
+        q = pos + 1;
       }
     }
   }
@@ -198,20 +202,33 @@ __global__ __launch_bounds__(64) void unary_decode_kernel(UnaryArgs a, uint16_t*
   }
 }
 
-// ---- draft GEMV from the unary form: four waves per workgroup, one row per wave ---------------
-constexpr int kUnaryWaves = 4;
+// ---- draft GEMV from the unary form: eight waves per workgroup, one row per wave --------------
+// Per row a wave first decodes the row's exponents into its LDS array, then walks the bitmap
+// in chunks of 64 words as the raw-exponent kernel does: a DPP prefix sum gives each lane the
+// index of its first kept value, its sign / mantissa fields are one contiguous run that is
+// loaded as a register window and aligned once, and step i of the bit walk uses field i of the
+// window and exponent i of the lane's run.  x sits in LDS as fp32 in segments of 1 + 32
+// entries whose entry 0 is 0.0, so a lane that has run out of set bits multiplies by zero.
+constexpr int kUnaryWaves = 8;
+
+template <int T>
 __global__ __launch_bounds__(64 * kUnaryWaves) void gemv_draft_unary_kernel(UnaryArgs a, const uint16_t* __restrict__ x,
                                                                            float* __restrict__ y, int kpad) {
+  constexpr int SW = 8 - T;  // field: sign, then 7 - T mantissa bits
   extern __shared__ uint8_t lds8[];
+  const int nseg = ((a.bw + 63) >> 6) << 6;
   uint8_t* tab = lds8;                                           // exp_of_rank
-  uint16_t* xs = reinterpret_cast<uint16_t*>(lds8 + 256);        // [bw * 32] bf16, zero beyond cols
-  uint8_t* exps_all = lds8 + 256 + (size_t)a.bw * 64;           // [waves][kpad]
+  float* xs = reinterpret_cast<float*>(lds8 + 256);              // [nseg][33]
+  uint8_t* exps_all = lds8 + 256 + (size_t)nseg * 33 * 4;        // [waves][kpad + kExpSlack]
   const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (tid < 256) tab[tid] = a.table[tid];
-  for (int c = tid; c < a.bw * 32; c += 64 * kUnaryWaves) xs[c] = c < a.cols ? x[c] : (uint16_t)0;
+  for (int sg = tid; sg < nseg; sg += 64 * kUnaryWaves) xs[sg * 33] = 0.f;
+  for (int c = tid; c < nseg * 32; c += 64 * kUnaryWaves)
+    xs[(c >> 5) * 33 + 1 + (c & 31)] = c < a.cols ? bf16_to_f32(x[c]) : 0.f;
+  uint8_t* exps = exps_all + (size_t)wv * (kpad + kExpSlack);
+  // what lies past a row's last exponent must be a finite number's exponent
+  for (int i = lane; i < kpad + kExpSlack; i += 64) exps[i] = 0;
   __syncthreads();
-  uint8_t* exps = exps_all + (size_t)wv * kpad;
-  const int mb = 7 - a.t, SW = 8 - a.t;
   // rows are dealt round-robin to all waves of the grid; a workgroup stages x once
   for (int row = blockIdx.x * kUnaryWaves + wv; row < a.rows; row += gridDim.x * kUnaryWaves) {
     const uint32_t o0 = a.rowoff[row], o1 = a.rowoff[row + 1];
@@ -227,17 +244,40 @@ __global__ __launch_bounds__(64 * kUnaryWaves) void gemv_draft_unary_kernel(Unar
       uint32_t m = w < a.bw ? bm_row[w] : 0u;
       const int cnt = __popc(m);
       const int incl = wave_incl_scan(cnt);
-      int e = base + incl - cnt;
+      const int e0 = base + incl - cnt;
       base += __builtin_amdgcn_readlane(incl, 63);
-      while (m) {
+      // window of the lane's fields: SW + 1 words from the word its first field starts in
+      const uint32_t bit = (uint32_t)e0 * SW, sh = bit & 31u;
+      const uint32_t* src = sm_row + (bit >> 5);
+      uint32_t d[SW + 1], win[SW];
+#pragma unroll
+      for (int j = 0; j <= SW; ++j) d[j] = src[j];
+#pragma unroll
+      for (int j = 0; j < SW; ++j) win[j] = __builtin_amdgcn_alignbit(d[j + 1], d[j], sh);
+      const uint8_t* ex = exps + e0;
+      const float* xb = xs + w * 33 + 1;
+      auto step = [&](auto I) {
+        constexpr int i = decltype(I)::value;
         const int pos = lowest_bit(m);
         m &= m - 1u;
-        const uint32_t sm = read_field(sm_row, (uint32_t)e * SW, SW);
-        // fp32 pattern of the zero-padded bf16: sign, exponent, leading mantissa bits
-        const uint32_t bits = ((sm >> mb) << 31) | ((uint32_t)exps[e] << 23) | ((sm & ((1u << mb) - 1u)) << (16 + a.t));
-        acc = fmaf(__uint_as_float(bits), bf16_to_f32(xs[w * 32 + pos]), acc);
-        ++e;
-      }
+        const uint32_t top = field_top<SW, i>(win);  // sign at bit 31, mantissa bits below
+        // fp32 pattern of the zero-padded bf16: sign | exponent | leading mantissa bits
+        const uint32_t mant = __builtin_amdgcn_ubfe(top, 8, 23);
+        const uint32_t bits = (top & 0x80000000u) | ((uint32_t)ex[i] << 23) | mant;
+        acc = fmaf(__uint_as_float(bits), xb[pos], acc);
+      };
+      static_for<0, 16>(step);
+      auto tail = [&](auto self, auto I) -> void {
+        constexpr int i = decltype(I)::value;
+        if constexpr (i < 32) {
+          if (__builtin_amdgcn_ballot_w64(m != 0u)) {
+            step(std::integral_constant<int, i>{});
+            step(std::integral_constant<int, i + 1>{});
+            self(self, std::integral_constant<int, i + 2>{});
+          }
+        }
+      };
+      tail(tail, std::integral_constant<int, 16>{});
     }
     acc = wave_sum(acc);
     if (lane == 0) y[row] = acc;
@@ -406,7 +446,7 @@ extern "C" int cas_unary_decode(cas_ctx* ctx, const cas_udesc* udesc, const void
   const cas_wdesc& d = udesc->base;
   if (d.rows == 0) return CAS_OK;
   if (!d_uspec || !d_out || !aligned256(d_uspec) || !aligned256(d_verif)) return CAS_EINVAL;
-  const size_t lds = 256 + (size_t)((d.K + 3) & ~3);
+  const size_t lds = 256 + (size_t)((d.K + 3) & ~3) + kExpSlack;
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
   UnaryArgs a = make_uargs(*udesc, nullptr, const_cast<void*>(d_uspec), d_verif);
   static size_t raised = 48 * 1024;
@@ -420,6 +460,20 @@ extern "C" int cas_unary_decode(cas_ctx* ctx, const cas_udesc* udesc, const void
   return CAS_OK;
 }
 
+template <int T>
+static int launch_unary_gemv(cas_ctx* ctx, const UnaryArgs& a, const uint16_t* d_x, float* d_y, int kpad, int grid,
+                             size_t lds) {
+  static size_t raised = 48 * 1024;
+  if (lds > raised) {
+    CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_unary_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)lds));
+    raised = lds;
+  }
+  hipLaunchKernelGGL(gemv_draft_unary_kernel<T>, dim3(grid), dim3(64 * kUnaryWaves), lds, ctx->stream, a, d_x, d_y, kpad);
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
+}
+
 extern "C" int cas_gemv_draft_unary(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, const uint16_t* d_x,
                                     float* d_y) {
   if (!ctx || check_udesc(udesc) != CAS_OK) return CAS_EINVAL;
@@ -427,17 +481,17 @@ extern "C" int cas_gemv_draft_unary(cas_ctx* ctx, const cas_udesc* udesc, const 
   if (d.rows == 0) return CAS_OK;
   if (!d_uspec || !d_x || !d_y || !aligned256(d_uspec)) return CAS_EINVAL;
   const int kpad = (d.K + 15) & ~15;
-  const size_t lds = 256 + (size_t)d.bw * 64 + (size_t)kUnaryWaves * kpad;
+  const size_t nseg = (size_t)((d.bw + 63) / 64 * 64);
+  const size_t lds = 256 + nseg * 33 * sizeof(float) + (size_t)kUnaryWaves * (kpad + kExpSlack);
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
   UnaryArgs a = make_uargs(*udesc, nullptr, const_cast<void*>(d_uspec), nullptr);
-  static size_t raised = 48 * 1024;
-  if (lds > raised) {
-    CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_unary_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)lds));
-    raised = lds;
+  // as many workgroups as stay resident: every one of them stages x once
+  const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, (size_t)ctx->lds_max / lds));
+  const int grid = (int)std::min<int64_t>((d.rows + kUnaryWaves - 1) / kUnaryWaves, (int64_t)ctx->num_cu * per_cu);
+#define CAS_T(TV) case TV: return launch_unary_gemv<TV>(ctx, a, d_x, d_y, kpad, grid, lds);
+  switch (d.t) {
+    CAS_T(0) CAS_T(1) CAS_T(2) CAS_T(3) CAS_T(4) CAS_T(5) CAS_T(6) CAS_T(7)
   }
-  const int grid = (int)std::min<int64_t>((d.rows + kUnaryWaves - 1) / kUnaryWaves, (int64_t)ctx->num_cu * 8);
-  hipLaunchKernelGGL(gemv_draft_unary_kernel, dim3(grid), dim3(64 * kUnaryWaves), lds, ctx->stream, a, d_x, d_y, kpad);
-  CAS_HIP(ctx, hipGetLastError());
-  return CAS_OK;
+#undef CAS_T
+  return CAS_EINVAL;
 }
