@@ -152,3 +152,49 @@ def test_speculative_stream_equals_plain_stream_at_8b_shape(env, keep, t):
     assert all(0 <= tok < shape.vocab for tok in plain)
     if keep == 1000 and t == 0:
         assert sum(acc) >= len(acc)      # the fp32 draft and the MFMA target agree on most tokens
+
+
+def test_repeated_launches_give_identical_bits(env):
+    """Every kernel on the path is deterministic (fixed summation orders, no atomics on floats):
+    100 launches of the draft GEMV and 50 of the verify GEMM on the gate/up shape, and 50 of each
+    attention form at 8192 committed positions, return the bits of the first launch; the exact
+    reconstruction of the matrix is checked as often."""
+    torch, B, _ = env
+    from paper_2605_26558_amd.workload import _random_weight
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    ctx = B.Context(workspace=ws)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(123)
+    rows, cols = 28672, 4096
+    W = _random_weight(torch, rows, cols, gen)
+    ew = B.cas_encode_weight(ctx, W, 600, 4)
+    X = torch.randn((7, cols), device="cuda", generator=gen).to(torch.bfloat16).view(torch.int16)
+    x1 = X[:1].contiguous()
+    yd0 = B.cas_gemv_draft(ctx, ew, x1).clone()
+    yv0 = B.cas_gemm_verify(ctx, ew, X).clone()
+    bad = torch.zeros((), dtype=torch.int64, device="cuda")
+    for i in range(100):
+        bad += (B.cas_gemv_draft(ctx, ew, x1) != yd0).sum()
+        if i % 2 == 0:
+            bad += (B.cas_gemm_verify(ctx, ew, X) != yv0).sum()
+        if i % 10 == 0:
+            bad += (B.cas_decode_weight(ctx, ew, full=True) != W).sum()
+    assert int(bad) == 0
+    nq, nkv, L = 32, 8, 8192
+    kv = B.KVCache(ctx, 1, nkv, n_pages=130, max_seqs=1, max_pages_per_seq=130)
+    K = torch.randn((L, nkv, 128), device="cuda", generator=gen).to(torch.bfloat16).view(torch.int16).contiguous()
+    V = torch.randn((L, nkv, 128), device="cuda", generator=gen).to(torch.bfloat16).view(torch.int16).contiguous()
+    B.cas_kv_append(ctx, kv, 0, 0, K, V)
+    B.cas_kv_set_len(kv, 0, L)
+    bf = lambda *s: torch.randn(s, device="cuda", generator=gen).to(torch.bfloat16).view(torch.int16)
+    Q, Kn, Vn = bf(7, nq, 128), bf(7, nkv, 128), bf(7, nkv, 128)
+    Q1, Kn1, Vn1 = Q[:1].contiguous(), Kn[:1].contiguous(), Vn[:1].contiguous()
+    od0 = B.cas_attention(ctx, kv, 0, 0, False, Q1, Kn1, Vn1).clone()
+    ov0 = B.cas_attention(ctx, kv, 0, 0, True, Q, Kn, Vn).clone()
+    bad.zero_()
+    for _ in range(50):
+        bad += (B.cas_attention(ctx, kv, 0, 0, False, Q1, Kn1, Vn1) != od0).sum()
+        bad += (B.cas_attention(ctx, kv, 0, 0, True, Q, Kn, Vn) != ov0).sum()
+    assert int(bad) == 0
+    # the first verification column alone gets the bits it gets among seven (Sec. 2.2)
+    o1 = B.cas_attention(ctx, kv, 0, 0, True, Q1, Kn1, Vn1)
+    assert torch.equal(o1[0], ov0[0])
