@@ -111,3 +111,27 @@ def test_unary_empty_matrix(env):
     assert B.cas_unary_decode(ctx, uw, full=True).shape == (0, 256)
     x = _dev(torch, synth.activations(256, 1, seed=1))
     assert B.cas_gemv_draft_unary(ctx, uw, x).shape == (0,)
+
+
+def test_unary_plan_and_encode_are_reproducible_on_many_rows(env):
+    """More row workgroups than the chip holds at once: every plan of the same matrix reports
+    the same codebook and stream size, every encoding the same bytes, and the exact
+    reconstruction returns the matrix."""
+    torch, B, ctx = env
+    rows, cols = 6000, 1024
+    gen = torch.Generator(device="cuda"); gen.manual_seed(9)
+    W = (torch.randn((rows, cols), device="cuda", generator=gen) * 0.02).to(torch.bfloat16).view(torch.int16)
+    ew = B.cas_encode_weight(ctx, W, 600, 4)
+    u0 = B.cas_unary_plan(ctx, ew)
+    first = B.cas_unary_encode(ctx, ew, u0)
+    for _ in range(10):
+        u = B.cas_unary_plan(ctx, ew)
+        assert u.ue_words == u0.ue_words and bytes(u.exp_of_rank) == bytes(u0.exp_of_rank)
+    for _ in range(3):
+        again = B.cas_unary_encode(ctx, ew)
+        assert torch.equal(again.uspec, first.uspec)
+    assert torch.equal(B.cas_unary_decode(ctx, first, full=True), W)
+    mx0 = B.cas_mx_encode(ctx, ew)
+    for _ in range(3):
+        mx = B.cas_mx_encode(ctx, ew)
+        assert torch.equal(mx.spec, mx0.spec) and torch.equal(mx.verif, mx0.verif)
