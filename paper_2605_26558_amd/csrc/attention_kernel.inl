@@ -344,18 +344,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 template <int MT, bool FULL>
 int launch_mt(cas_ctx* ctx, const AttnArgs& a, dim3 grid) {
   constexpr size_t lds = attn_lds_bytes<MT>();
-#define CAS_LAUNCH(TV)                                                                                          \
-  case TV:                                                                                                      \
-    if (lds > 48 * 1024) {                                                                                      \
-      static size_t raised = 48 * 1024;                                                                               \
-      if (lds > raised) {                                                                                            \
-        CAS_HIP(ctx, hipFuncSetAttribute((const void*)attn_partial_kernel<MT, FULL, TV>,                        \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));            \
-        raised = lds;                                                                                           \
-      }                                                                                                         \
-    }                                                                                                           \
-    hipLaunchKernelGGL((attn_partial_kernel<MT, FULL, TV>), grid, dim3(256), lds, ctx->stream, a);              \
-    break;
+#define CAS_LAUNCH(TV)                                                                                     \
+  case TV: {                                                                                               \
+    static LdsLimit lim;                                                                                   \
+    const int rc = allow_lds(ctx, (const void*)attn_partial_kernel<MT, FULL, TV>, lds, lim);               \
+    if (rc != CAS_OK) return rc;                                                                           \
+    hipLaunchKernelGGL((attn_partial_kernel<MT, FULL, TV>), grid, dim3(256), lds, ctx->stream, a);         \
+  } break;
   switch (a.g.t) {
     CAS_LAUNCH(0) CAS_LAUNCH(1) CAS_LAUNCH(2) CAS_LAUNCH(3) CAS_LAUNCH(4) CAS_LAUNCH(5) CAS_LAUNCH(6) CAS_LAUNCH(7)
     default: return CAS_EINVAL;

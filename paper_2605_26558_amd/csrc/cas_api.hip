@@ -21,6 +21,7 @@ int cas_ctx_create(cas_ctx** out, void* hip_stream, void* d_workspace, size_t ws
   c->last_hip = 0;
   int dev = 0, v = 0;
   hipError_t e = hipGetDevice(&dev);
+  c->device = dev;
   if (e == hipSuccess) e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) { c->last_hip = (int)e; delete c; return CAS_EHIP; }
   c->num_cu = v;

@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include "../../include/cassandra.h"
 
+#include <atomic>
 #include <vector>
 
 namespace cas {
@@ -20,6 +21,7 @@ struct cas_ctx {
   int last_hip;
   int num_cu;
   int lds_max;  // bytes of LDS one workgroup may use
+  int device;   // the device that was current when the context was made
 };
 
 #define CAS_HIP(ctx, expr)                          \
@@ -50,6 +52,22 @@ struct cas_kv {
 };
 
 namespace cas {
+// Kernels that ask for more than 48 KB of dynamic LDS must be allowed to, once per device and
+// kernel; one LdsLimit (a function-local static at the launch site) remembers what has been
+// granted.  Two threads racing here both make the call, which is harmless.
+struct LdsLimit {
+  std::atomic<size_t> granted[16];
+};
+inline int allow_lds(cas_ctx* ctx, const void* kernel, size_t lds, LdsLimit& lim) {
+  if (lds <= 48 * 1024) return CAS_OK;
+  std::atomic<size_t>& g = lim.granted[ctx->device & 15];
+  if (lds > g.load(std::memory_order_relaxed)) {
+    CAS_HIP(ctx, hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    g.store(lds, std::memory_order_relaxed);
+  }
+  return CAS_OK;
+}
+
 inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
 int launch_encode_weight(cas_ctx*, const uint16_t* W, int64_t ld, const float* act, const cas_wdesc&, void* spec, void* verif);

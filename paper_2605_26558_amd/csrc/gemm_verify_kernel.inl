@@ -224,14 +224,11 @@ static int launch_gq(cas_ctx* ctx, const VerifyArgs& a, int t) {
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
   const int groups = (a.rows + 15) / 16;
   const int grid = (groups + G - 1) / G;
-#define CAS_LAUNCH(TV)                                                                                  \
-  case TV: {                                                                                            \
-    static size_t raised = 48 * 1024;                                                                   \
-    if (lds > raised) {                                                                                 \
-      CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemm_verify_kernel<TV, G, Q, XST, NB>,                       \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));          \
-      raised = lds;                                                                                     \
-    }                                                                                                   \
+#define CAS_LAUNCH(TV)                                                                                        \
+  case TV: {                                                                                                  \
+    static LdsLimit lim;                                                                                      \
+    const int rc = allow_lds(ctx, (const void*)gemm_verify_kernel<TV, G, Q, XST, NB>, lds, lim);              \
+    if (rc != CAS_OK) return rc;                                                                              \
     hipLaunchKernelGGL((gemm_verify_kernel<TV, G, Q, XST, NB>), dim3(grid), dim3(64 * NW), lds, ctx->stream, a); \
   } break;
   switch (t) {

@@ -320,15 +320,12 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   }
 }
 
-// hipFuncSetAttribute once per instantiation and LDS size, then the launch
+// LDS allowance of the instantiation, then the launch
 template <int T, int NB, bool MX>
 static int launch_gemv_instance(cas_ctx* ctx, const GemvArgs& a, int grid, size_t lds) {
-  static size_t raised = 48 * 1024;
-  if (lds > raised) {
-    CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_kernel<T, NB, MX>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    raised = lds;
-  }
+  static LdsLimit lim;
+  const int rc = allow_lds(ctx, (const void*)gemv_draft_kernel<T, NB, MX>, lds, lim);
+  if (rc != CAS_OK) return rc;
   hipLaunchKernelGGL((gemv_draft_kernel<T, NB, MX>), dim3(grid), dim3(kGemvThreads), lds, ctx->stream, a);
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;

@@ -449,11 +449,9 @@ extern "C" int cas_unary_decode(cas_ctx* ctx, const cas_udesc* udesc, const void
   const size_t lds = 256 + (size_t)((d.K + 3) & ~3) + kExpSlack;
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
   UnaryArgs a = make_uargs(*udesc, nullptr, const_cast<void*>(d_uspec), d_verif);
-  static size_t raised = 48 * 1024;
-  if (lds > raised) {
-    CAS_HIP(ctx, hipFuncSetAttribute((const void*)unary_decode_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    raised = lds;
-  }
+  static LdsLimit lim;
+  const int rc = allow_lds(ctx, (const void*)unary_decode_kernel, lds, lim);
+  if (rc != CAS_OK) return rc;
   hipLaunchKernelGGL(unary_decode_kernel, dim3((unsigned)d.rows), dim3(64), lds, ctx->stream, a, d_out, ld,
                      d_verif ? 1 : 0);
   CAS_HIP(ctx, hipGetLastError());
@@ -463,12 +461,9 @@ extern "C" int cas_unary_decode(cas_ctx* ctx, const cas_udesc* udesc, const void
 template <int T>
 static int launch_unary_gemv(cas_ctx* ctx, const UnaryArgs& a, const uint16_t* d_x, float* d_y, int kpad, int grid,
                              size_t lds) {
-  static size_t raised = 48 * 1024;
-  if (lds > raised) {
-    CAS_HIP(ctx, hipFuncSetAttribute((const void*)gemv_draft_unary_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)lds));
-    raised = lds;
-  }
+  static LdsLimit lim;
+  const int rc = allow_lds(ctx, (const void*)gemv_draft_unary_kernel<T>, lds, lim);
+  if (rc != CAS_OK) return rc;
   hipLaunchKernelGGL(gemv_draft_unary_kernel<T>, dim3(grid), dim3(64 * kUnaryWaves), lds, ctx->stream, a, d_x, d_y, kpad);
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;

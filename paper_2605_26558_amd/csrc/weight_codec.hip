@@ -211,8 +211,9 @@ int launch_encode_weight(cas_ctx* ctx, const uint16_t* W, int64_t ld, const floa
   CodecArgs a = make_args(d, spec, verif, ld);
   size_t lds = sizeof(uint32_t) * ((size_t)d.sw + d.lw + d.pw + 256 + 2 * (size_t)d.bw);
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
-  if (lds > 48 * 1024)
-    CAS_HIP(ctx, hipFuncSetAttribute((const void*)encode_rows_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  static LdsLimit lim;
+  const int rc = allow_lds(ctx, (const void*)encode_rows_kernel, lds, lim);
+  if (rc != CAS_OK) return rc;
   int grid = (int)std::min<int64_t>(d.rows, (int64_t)ctx->num_cu * 8);
   if (grid < 1) return CAS_OK;
   hipLaunchKernelGGL(encode_rows_kernel, dim3(grid), dim3(256), lds, ctx->stream, W, act, a);
