@@ -300,7 +300,9 @@ int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_to
  * d_O: bf16 [ncols][n_q_heads][head_dim].  ncols <= 16 and ncols * n_q_heads / n_kv_heads <= 80
  * (48 when full = 0).
  * Uses the context workspace for the per-split partial results (CAS_ENOMEM if too small:
- * splits * n_kv_heads * ncols * group * 132 floats, one split per 64 positions).
+ * splits * n_kv_heads * ncols * group * 132 floats, one split per 64 positions; the model
+ * passes run up to four sequences per launch and need the sum of their amounts, each rounded
+ * up to 256 bytes).
  * A column's value depends only on the positions it sees: not on ncols, and not on whether an
  * earlier position is already committed or still in flight.
  */

@@ -20,14 +20,15 @@
 //      registers.
 // Partial (max, sum, output) of every page go to the workspace; a merge kernel combines them
 // in a fixed order.
+#include <algorithm>
 #include "attention_kernel.inl"
 
 namespace cas {
 
 // the draft form (speculation data only) is compiled in attention_draft.hip
-extern template int launch_mt<1, false>(cas_ctx*, const AttnArgs&, dim3);
-extern template int launch_mt<2, false>(cas_ctx*, const AttnArgs&, dim3);
-extern template int launch_mt<3, false>(cas_ctx*, const AttnArgs&, dim3);
+extern template int launch_mt<1, false>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<2, false>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<3, false>(cas_ctx*, const AttnBatch&, dim3);
 
 // Combine the splits: o = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, rounded to bf16.
 // One workgroup per (query row, kv head, half of the channels): the split weights are computed
@@ -36,12 +37,14 @@ extern template int launch_mt<3, false>(cas_ctx*, const AttnArgs&, dim3);
 // does not depend on timing, nor on how many rows ride along).
 constexpr int kMergeParts = 8;
 constexpr int kMergePre = 20;  // splits per thread whose outputs are requested before the weights exist
-__global__ __launch_bounds__(512) void attn_merge_kernel(AttnArgs a) {
+__global__ __launch_bounds__(512) void attn_merge_kernel(AttnBatch batch) {
+  const AttnArgs a = attn_args_of(batch, blockIdx.z >> 1);  // blockIdx.z = 2 * sequence + channel half
   extern __shared__ float sw[];  // [nsplit] weights, then [kMergeParts][64] partial sums
   __shared__ float red[16];
   const int rr = blockIdx.x, head = blockIdx.y, tid = threadIdx.x;
-  const int d = blockIdx.z * 64 + (tid & 63), part = tid >> 6;
+  const int d = (blockIdx.z & 1) * 64 + (tid & 63), part = tid >> 6;
   const int R = a.ncols * a.grp;
+  if (rr >= R) return;  // a sequence with fewer rows than the widest of the launch
   const size_t sstride = (size_t)a.g.n_kv_heads * R * kPartStride;
   const float* base = a.part + ((size_t)head * R + rr) * kPartStride;
   // everything this thread needs from the first 512 splits goes out in one batch: its split's
@@ -103,54 +106,87 @@ __global__ __launch_bounds__(512) void attn_merge_kernel(AttnArgs a) {
   }
 }
 
-int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
+// Up to kAttnBatch sequences of one pass in one pair of launches (same layer, same form, same
+// number of query heads); every sequence gets exactly what a launch of its own would give it.
+static int launch_attention_group(cas_ctx* ctx, cas_kv* kv, const AttnCall* calls, int n, size_t* ws_used) {
   const KvGeom& g = kv->geom;
-  AttnArgs a;
+  const AttnCall& c0 = calls[0];
+  AttnBatch b{};
+  AttnArgs& a = b.common;
   a.g = g;
   a.spec_pool = (const uint32_t*)kv->d_spec;
   a.verif_pool = (const uint32_t*)kv->d_verif;
-  a.page_row = kv->d_page_table + (size_t)c.seq * g.max_pages_per_seq;
-  a.layer = c.layer;
-  a.len = kv->h_len[c.seq];
-  a.Q = c.Q; a.ncols = c.ncols; a.n_q_heads = c.n_q_heads; a.grp = c.n_q_heads / g.n_kv_heads;
-  a.Knew = c.Knew; a.Vnew = c.Vnew; a.n_new = c.n_new;
-  a.qkv = c.qkv; a.ystride = c.ystride; a.slot0 = c.slot0; a.rope = c.rope;
-  a.Kslot = c.Kslot; a.Vslot = c.Vslot;
+  a.layer = c0.layer;
+  a.n_q_heads = c0.n_q_heads; a.grp = c0.n_q_heads / g.n_kv_heads;
+  a.ystride = c0.ystride; a.rope = c0.rope;
   a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
-  a.O = c.O;
-  const int R = a.ncols * a.grp;
-  const int MT = (R + 15) / 16;
-  if (MT < 1 || MT > (c.full ? 5 : 3) || c.n_new > kPT || c.n_new < c.ncols || c.ncols > kMaxCols) return CAS_EINVAL;
-  const int pages = (a.len + a.n_new + kPT - 1) / kPT;
-  if (pages > g.max_pages_per_seq) return CAS_ENOMEM;
   a.pages_per_split = kPagesPerSplit;  // fixed: a query's value must not depend on the length
-  a.nsplit = (pages + kPagesPerSplit - 1) / kPagesPerSplit;
-  size_t need = sizeof(float) * (size_t)a.nsplit * g.n_kv_heads * R * kPartStride;
-  if (need > ctx->ws_bytes || !ctx->d_ws) return CAS_ENOMEM;
-  a.part = (float*)ctx->d_ws;
-  dim3 grid(a.nsplit, g.n_kv_heads);
-  int rc;
-  {
+  int max_r = 0, max_split = 0;
+  double bytes = 0.0;
+  for (int i = 0; i < n; ++i) {
+    const AttnCall& c = calls[i];
+    if (c.layer != c0.layer || c.full != c0.full || c.n_q_heads != c0.n_q_heads || c.ystride != c0.ystride ||
+        c.rope != c0.rope || (c.qkv == nullptr) != (c0.qkv == nullptr))
+      return CAS_EINVAL;
+    AttnSeq& q = b.s[i];
+    q.page_row = kv->d_page_table + (size_t)c.seq * g.max_pages_per_seq;
+    q.len = kv->h_len[c.seq];
+    q.Q = c.Q; q.ncols = c.ncols;
+    q.Knew = c.Knew; q.Vnew = c.Vnew; q.n_new = c.n_new;
+    q.qkv = c.qkv; q.slot0 = c.slot0;
+    q.Kslot = c.Kslot; q.Vslot = c.Vslot;
+    q.O = c.O;
+    const int R = c.ncols * a.grp;
+    const int MT = (R + 15) / 16;
+    if (MT < 1 || MT > (c.full ? 5 : 3) || c.n_new > kPT || c.n_new < c.ncols || c.ncols > kMaxCols) return CAS_EINVAL;
+    const int pages = (q.len + q.n_new + kPT - 1) / kPT;
+    if (pages > g.max_pages_per_seq) return CAS_ENOMEM;
+    q.nsplit = (pages + kPagesPerSplit - 1) / kPagesPerSplit;
+    const size_t need = sizeof(float) * (size_t)q.nsplit * g.n_kv_heads * R * kPartStride;
+    if (!ctx->d_ws || *ws_used + need > ctx->ws_bytes) return CAS_ENOMEM;
+    q.part = (float*)((char*)ctx->d_ws + *ws_used);
+    *ws_used += (need + 255) / 256 * 256;
+    max_r = std::max(max_r, R);
+    max_split = std::max(max_split, q.nsplit);
     // committed positions: bitmap + spec (+ lo + pruned) of K and V; in-flight ones: plain bf16
     const double per_tok = 4.0 * (4 + g.sw + (c.full ? g.lw + g.pw : 0));
-    const double bytes = 2.0 * g.n_kv_heads * (per_tok * a.len + 256.0 * a.n_new);
-    ProfScope prof(ctx, c.full ? PROF_ATTN_VERIFY : PROF_ATTN_DRAFT, bytes);
-  if (c.full) {
-    rc = MT == 1   ? launch_mt<1, true>(ctx, a, grid)
-         : MT == 2 ? launch_mt<2, true>(ctx, a, grid)
-         : MT == 3 ? launch_mt<3, true>(ctx, a, grid)
-         : MT == 4 ? launch_mt<4, true>(ctx, a, grid)
-                   : launch_mt<5, true>(ctx, a, grid);
-  } else {
-    rc = MT == 1 ? launch_mt<1, false>(ctx, a, grid) : MT == 2 ? launch_mt<2, false>(ctx, a, grid)
-                                                                : launch_mt<3, false>(ctx, a, grid);
+    bytes += 2.0 * g.n_kv_heads * (per_tok * q.len + 256.0 * q.n_new);
   }
+  const int MT = (max_r + 15) / 16;
+  dim3 grid(max_split, g.n_kv_heads, n);
+  int rc;
+  {
+    ProfScope prof(ctx, c0.full ? PROF_ATTN_VERIFY : PROF_ATTN_DRAFT, bytes);
+    if (c0.full) {
+      rc = MT == 1   ? launch_mt<1, true>(ctx, b, grid)
+           : MT == 2 ? launch_mt<2, true>(ctx, b, grid)
+           : MT == 3 ? launch_mt<3, true>(ctx, b, grid)
+           : MT == 4 ? launch_mt<4, true>(ctx, b, grid)
+                     : launch_mt<5, true>(ctx, b, grid);
+    } else {
+      rc = MT == 1 ? launch_mt<1, false>(ctx, b, grid) : MT == 2 ? launch_mt<2, false>(ctx, b, grid)
+                                                                  : launch_mt<3, false>(ctx, b, grid);
+    }
   }
   if (rc != CAS_OK) return rc;
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(R, g.n_kv_heads, 2), dim3(512), sizeof(float) * (a.nsplit + kMergeParts * 64),
-                     ctx->stream, a);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(max_r, g.n_kv_heads, 2 * n), dim3(512),
+                     sizeof(float) * (max_split + kMergeParts * 64), ctx->stream, b);
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;
 }
+
+int launch_attention_batch(cas_ctx* ctx, cas_kv* kv, const AttnCall* calls, int n) {
+  if (n < 1) return CAS_OK;
+  // the launches of a group follow those of the group before on the stream, so every group
+  // starts at the beginning of the workspace again
+  for (int i = 0; i < n; i += kAttnBatch) {
+    size_t ws_used = 0;
+    const int rc = launch_attention_group(ctx, kv, calls + i, std::min(kAttnBatch, n - i), &ws_used);
+    if (rc != CAS_OK) return rc;
+  }
+  return CAS_OK;
+}
+
+int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) { return launch_attention_batch(ctx, kv, &c, 1); }
 
 }  // namespace cas

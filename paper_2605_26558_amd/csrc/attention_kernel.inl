@@ -33,6 +33,33 @@ struct AttnArgs {
   uint16_t* O;
 };
 
+// What differs between the sequences of one launch; blockIdx.z picks the sequence.
+constexpr int kAttnBatch = 4;
+struct AttnSeq {
+  const int32_t* page_row;
+  int len, nsplit, ncols, n_new, slot0;
+  const uint16_t* Q;
+  const uint16_t* Knew;
+  const uint16_t* Vnew;
+  const float* qkv;
+  uint16_t* Kslot;
+  uint16_t* Vslot;
+  float* part;
+  uint16_t* O;
+};
+struct AttnBatch {
+  AttnArgs common;  // its per-sequence members are filled in from s[] inside the kernels
+  AttnSeq s[kAttnBatch];
+};
+__device__ __forceinline__ AttnArgs attn_args_of(const AttnBatch& b, int z) {
+  AttnArgs a = b.common;
+  const AttnSeq& q = b.s[z];
+  a.page_row = q.page_row; a.len = q.len; a.nsplit = q.nsplit; a.ncols = q.ncols; a.n_new = q.n_new;
+  a.slot0 = q.slot0; a.Q = q.Q; a.Knew = q.Knew; a.Vnew = q.Vnew; a.qkv = q.qkv;
+  a.Kslot = q.Kslot; a.Vslot = q.Vslot; a.part = q.part; a.O = q.O;
+  return a;
+}
+
 constexpr int kPT = 64;          // tokens per page
 constexpr int kQP = 136;         // Q row pitch (bf16)
 constexpr int kKG = 36, kKP = 148;  // K tile: group pitch (4 dump + 32), row pitch
@@ -70,7 +97,9 @@ __device__ __forceinline__ float row16_sum(float v) {
 }
 
 template <int MT, bool FULL, int T>
-__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
+  const AttnArgs a = attn_args_of(batch, blockIdx.z);
+  if ((int)blockIdx.x >= a.nsplit) return;  // a shorter sequence of the launch: uniform for the workgroup
   extern __shared__ uint16_t lds16[];
   uint16_t* Qs = lds16;                       // [MT*16][kQP]; dead once the scores are in registers
   uint16_t* Ph = lds16;                       // [MT*16][kPP] over the Q region
@@ -342,7 +371,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 }
 
 template <int MT, bool FULL>
-int launch_mt(cas_ctx* ctx, const AttnArgs& a, dim3 grid) {
+int launch_mt(cas_ctx* ctx, const AttnBatch& a, dim3 grid) {
   constexpr size_t lds = attn_lds_bytes<MT>();
 #define CAS_LAUNCH(TV)                                                                                     \
   case TV: {                                                                                               \
@@ -351,7 +380,7 @@ int launch_mt(cas_ctx* ctx, const AttnArgs& a, dim3 grid) {
     if (rc != CAS_OK) return rc;                                                                           \
     hipLaunchKernelGGL((attn_partial_kernel<MT, FULL, TV>), grid, dim3(256), lds, ctx->stream, a);         \
   } break;
-  switch (a.g.t) {
+  switch (a.common.g.t) {
     CAS_LAUNCH(0) CAS_LAUNCH(1) CAS_LAUNCH(2) CAS_LAUNCH(3) CAS_LAUNCH(4) CAS_LAUNCH(5) CAS_LAUNCH(6) CAS_LAUNCH(7)
     default: return CAS_EINVAL;
   }

@@ -100,6 +100,8 @@ struct AttnCall {
   uint16_t* Vslot = nullptr;
 };
 int launch_attention(cas_ctx*, cas_kv*, const AttnCall&);
+// the same for the sequences of one pass (same layer and form), four of them per pair of launches
+int launch_attention_batch(cas_ctx*, cas_kv*, const AttnCall* calls, int n);
 // Brackets one kernel launch with HIP events on the context stream when profiling is on.
 struct ProfScope {
   cas_ctx* ctx;

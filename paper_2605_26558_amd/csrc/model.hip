@@ -165,7 +165,8 @@ static int seq_cols_max(const cas_model_cfg& c) {
   return std::min({(int)c.max_cols, 16, 80 / (c.n_q_heads / c.n_kv_heads)});
 }
 
-// model in one pass: the linear layers see all columns at once, attention runs per sequence.
+// model in one pass: the linear layers see all columns at once, attention runs over each sequence's own
+// cache and in-flight slots, four sequences per launch.
 static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, int ng, const int32_t* d_tokens,
                    bool full, int32_t* d_out, float* d_logits) {
   const cas_model_cfg& c = m->cfg;
@@ -197,18 +198,19 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, 
     }
     // the attention kernel splits the projection itself: bf16 rounding, rotary embedding of q and
     // k, and the copy of this pass's k, v into their in-flight slots
+    AttnCall calls[16];
     for (int i = 0, c0 = 0; i < ng; c0 += grp[i].ncols, ++i) {
       const ColGroup& g = grp[i];
       const size_t slots = ((size_t)g.seq * c.n_layers + l) * c.max_cols * kvd;  // in-flight K/V of (sequence, layer)
-      AttnCall ac;
+      AttnCall& ac = calls[i];
       ac.layer = l; ac.seq = g.seq; ac.full = full ? 1 : 0;
       ac.Q = m->q; ac.ncols = g.ncols; ac.n_q_heads = c.n_q_heads;
       ac.Knew = m->knew + slots; ac.Vnew = m->vnew + slots; ac.n_new = g.slot0 + g.ncols;
       ac.O = m->ao + (size_t)c0 * qd;
       ac.qkv = m->y + (size_t)c0 * (qd + 2 * kvd); ac.ystride = qd + 2 * kvd; ac.slot0 = g.slot0; ac.rope = m->d_rope;
       ac.Kslot = m->knew + slots; ac.Vslot = m->vnew + slots;
-      CAS_TRY(launch_attention(ctx, kv, ac));
     }
+    CAS_TRY(launch_attention_batch(ctx, kv, calls, ng));
     if (full) {
       // residual adds and SwiGLU ride in the epilogue of the verification GEMM
       CAS_TRY(launch_gemm_verify_fused(ctx, L.wo.desc, L.wo.d_spec, L.wo.d_verif, m->ao, ncols, nullptr, 1, m->h));

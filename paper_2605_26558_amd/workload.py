@@ -120,7 +120,12 @@ class ModelRoundWorkload:
             shape = synth.LlamaShape("llama3-8b", 4096, args.layers, 32, 8, 128, 14336, 128256)
         self.shape = shape
         name = "Llama-3-70B" if big else "Llama-3-8B"
-        self.ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        # attention partials of the (up to four) sequences that share a launch: one (max, sum,
+        # output) record of 132 floats per page, kv head and query row
+        rows = (args.k + 1) * (shape.n_q_heads // shape.n_kv_heads)
+        pages_ws = (args.context + 1024 + 63) // 64 + 1
+        need = min(self.batch, 4) * (pages_ws * shape.n_kv_heads * rows * 132 * 4 + 256)
+        self.ws = torch.empty(max(64 << 20, need), dtype=torch.uint8, device="cuda")
         self.ctx = B.Context(workspace=self.ws)
         ctx = self.ctx
         gen = torch.Generator(device="cuda")
