@@ -158,15 +158,14 @@ struct ColGroup {
 
 static int model_seqs(const cas_model_cfg& c) { return c.max_seqs > 0 ? c.max_seqs : 1; }
 
-// Runs the columns of `ng` groups (token ids on the device, group after group) through the
-
 // columns one sequence may contribute to a pass: what one attention call takes
 static int seq_cols_max(const cas_model_cfg& c) {
   return std::min({(int)c.max_cols, 16, 80 / (c.n_q_heads / c.n_kv_heads)});
 }
 
-// model in one pass: the linear layers see all columns at once, attention runs over each sequence's own
-// cache and in-flight slots, four sequences per launch.
+// Runs the columns of `ng` groups (token ids on the device, group after group) through the
+// model in one pass: the linear layers see all columns at once, attention runs over each
+// sequence's own cache and in-flight slots, four sequences per launch.
 static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, int ng, const int32_t* d_tokens,
                    bool full, int32_t* d_out, float* d_logits) {
   const cas_model_cfg& c = m->cfg;
