@@ -198,3 +198,62 @@ def test_repeated_launches_give_identical_bits(env):
     # the first verification column alone gets the bits it gets among seven (Sec. 2.2)
     o1 = B.cas_attention(ctx, kv, 0, 0, True, Q1, Kn1, Vn1)
     assert torch.equal(o1[0], ov0[0])
+
+
+def test_one_8b_shaped_layer_against_oracle_with_4096_cached_positions(env):
+    """One decoder layer of Llama-3-8B shape (hidden 4096, 32 q / 8 kv heads, FFN 14336; a
+    512-row output head keeps the oracle short), 4096 cached positions whose keys have 4 outlier
+    channels per head, draft length 4: the logits of the 5-column verification pass and of the
+    first draft pass against the oracle (Sec. 4.1 target and draft inference)."""
+    torch, B, _ = env
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    ctx = B.Context(workspace=ws)
+    keep, t, k, L = 600, 4, 4, 4096
+    shape = synth.LlamaShape("llama3-8b-1l", 4096, 1, 32, 8, 128, 14336, 512)
+    weights = synth.model_weights(shape, seed=3)
+    tab = synth.rope_table(L + 64, shape.head_dim, shape.rope_theta)
+    print("weights ready", flush=True)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+    lw = weights["layers"][0]
+    layer = {n: B.cas_encode_weight(ctx, dev(lw[n]), keep, t) for n in ("wqkv", "wo", "wgu", "wd")}
+    layer["g_attn"], layer["g_ffn"] = dev(lw["g_attn"]), dev(lw["g_ffn"])
+    head = B.cas_encode_weight(ctx, dev(weights["lm_head"]), keep, t)
+    model = B.Model(ctx, shape, [layer], head, dev(weights["embed"]), dev(weights["g_final"]),
+                    torch.from_numpy(tab).cuda(), max_cols=k + 1)
+    kv = B.KVCache(ctx, 1, shape.n_kv_heads, n_pages=66, max_seqs=1, max_pages_per_seq=66,
+                   keep_permille=keep, trunc_bits=t)
+    K = synth.kv_tensor(L, shape.n_kv_heads, 128, seed=21, outlier_channels=4)
+    V = synth.kv_tensor(L, shape.n_kv_heads, 128, seed=22, outlier_channels=0)
+    B.cas_kv_append(ctx, kv, 0, 0, dev(K), dev(V))
+    B.cas_kv_set_len(kv, 0, L)
+    # the oracle's cache: the same vectors through its own encoder, decoded once per view
+    om = O.OracleModel(shape, weights, tab, w_keep=keep, w_t=t, kv_keep=keep, kv_t=t)
+    pk, pv = O.encode_kv(K.reshape(-1, 128), keep, t), O.encode_kv(V.reshape(-1, 128), keep, t)
+    views = {True: (O.decode_draft(pk).reshape(K.shape), O.decode_draft(pv).reshape(V.shape)),
+             False: (O.decode_full(pk).reshape(K.shape), O.decode_full(pv).reshape(V.shape))}
+    assert np.array_equal(views[False][0], K) and np.array_equal(views[False][1], V)
+    om._cache_kv = lambda layer_index, draft: views[draft]
+    om.cache_len = lambda: L
+    print("oracle ready", flush=True)
+
+    def check(gpu, ref, draft, what):
+        W = om.W(None, "lm_head", draft)
+        tol = 2e-3 * np.linalg.norm(W, axis=1) * np.linalg.norm(O.bf16_to_f64(om.g_final))
+        err = np.abs(gpu - ref)
+        # bf16 roundings between the ops of the layer can fall differently in fp32 and fp64 and
+        # reach the head: 8x the one-GEMV tolerance, as for the small model
+        assert (err <= 8 * tol[None, :]).all(), (what, float((err / tol[None, :]).max()))
+        print(what, "max err / tol", float((err / tol[None, :]).max()), flush=True)
+
+    tokens = synth.token_ids(k + 1, shape.vocab, seed=9)
+    tgt = torch.empty(k + 1, dtype=torch.int32, device="cuda")
+    logits = torch.empty((k + 1, shape.vocab), dtype=torch.float32, device="cuda")
+    B.cas_verify_step(ctx, model, kv, 0, torch.from_numpy(tokens).cuda(), k, tgt, logits)
+    ref, _ = om.forward(tokens, draft=False)
+    check(logits.cpu().numpy().astype(np.float64), ref, False, "verify")
+    nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+    dl = torch.empty((1, shape.vocab), dtype=torch.float32, device="cuda")
+    B.cas_draft_step(ctx, model, kv, 0, torch.from_numpy(tokens[:1].copy()).cuda(), 0, nxt, dl)
+    empty = [(np.zeros((0, shape.n_kv_heads, 128), np.uint16),) * 2]
+    dref, _ = om.forward(tokens[:1], draft=True, extra_kv=empty)
+    check(dl.cpu().numpy().astype(np.float64), dref, True, "draft")
