@@ -79,3 +79,26 @@ def test_objective_and_grid_search_against_oracle_and_closed_forms():
         assert got == ref == tuple(int(v) for v in np.unravel_index(np.argmax(vals), vals.shape))
     with __import__("pytest").raises(B.CasError):
         B.cas_objective(1.0, 0.0, 600, 4, 0.0, 600, 4)
+
+
+def test_header_is_plain_c_and_host_calls_work_from_c(tmp_path):
+    """include/cassandra.h compiles as strict C99 and a C program linked against the library
+    can use the host-only entry points (no GPU touched)."""
+    import shutil
+    import subprocess
+    from paper_2605_26558_amd import binding as B
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+    gcc = shutil.which("gcc")
+    assert gcc, "gcc is part of the image"
+    exe = tmp_path / "abi_host_calls"
+    libdir = os.path.dirname(B.LIB_PATH)
+    cmd = [gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c", "abi_host_calls.c"), "-o", str(exe),
+           "-L", libdir, "-l:" + os.path.basename(B.LIB_PATH), "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "abi host calls ok" in r.stdout
