@@ -1,5 +1,6 @@
-"""Error behaviour of the C ABI as the header states it: requests outside the limits come back
-as an error code from the host-side checks, before any kernel is launched."""
+"""Behaviour of the C ABI as the header states it: requests outside the limits come back as an
+error code from the host-side checks, before any kernel is launched; and the library used from
+a plain C program."""
 import copy
 import ctypes as C
 
@@ -91,3 +92,19 @@ def test_attention_limits(env):
     assert _code(B, lambda: B.cas_attention(ctx, kv, 0, 1, False, z(1, 2, 128), z(1, 2, 128), z(1, 2, 128))) == B.CAS_EINVAL
     # appending past the pages a sequence may hold
     assert _code(B, lambda: B.cas_kv_append(ctx, kv, 0, 0, z(129, 2, 128), z(129, 2, 128))) == B.CAS_ENOMEM
+
+
+def test_library_from_a_plain_c_program():
+    """tests/c/abi_gpu_roundtrip.c: encode, exact and draft reconstruction, draft GEMV and
+    verification GEMM through the C ABI with device memory from the HIP runtime, no Python in the
+    path.  The program is built with the library (built here if it is missing)."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = os.path.join(root, "tests", "c", "abi_gpu_roundtrip")
+    if not os.path.exists(exe):
+        import __graft_entry__ as g
+        exe = g.build_c_program()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "abi gpu roundtrip ok" in r.stdout
