@@ -191,3 +191,37 @@ def test_kv_append_special_values_and_empty_append(env):
     Kd, Vd = B.cas_kv_read(ctx, kv, 0, 0, 0, ntok, full=False)
     np.testing.assert_array_equal(_host(Kd).reshape(-1, 128), O.decode_draft(O.encode_kv(Kh.reshape(-1, 128), 600, 4)))
     np.testing.assert_array_equal(_host(Vd).reshape(-1, 128), O.decode_draft(O.encode_kv(Vh.reshape(-1, 128), 600, 4)))
+
+
+@pytest.mark.parametrize("nq,nkv,ncols,full,keep,t", [
+    (3, 3, 1, False, 600, 4),      # one query head per kv head, odd head count
+    (3, 3, 16, True, 600, 4),      # the largest number of columns
+    (6, 3, 4, False, 600, 4),      # four draft columns of a group of two (a multi-sequence draft shape)
+    (16, 1, 5, True, 1000, 0),     # one kv head for sixteen query heads = 80 query rows; nothing pruned or truncated
+    (16, 1, 3, False, 250, 4),     # 48 draft rows; a quarter kept
+    (8, 2, 7, True, 500, 7),       # sign and exponent only in the speculation data
+])
+def test_attention_head_layouts_and_cache_formats(env, nq, nkv, ncols, full, keep, t):
+    torch, B, ctx = env
+    print(f"case nq={nq} nkv={nkv} ncols={ncols} full={full} keep={keep} t={t}", flush=True)
+    L = 200
+    kv = B.KVCache(ctx, 1, nkv, n_pages=5, max_seqs=1, max_pages_per_seq=5, keep_permille=keep, trunc_bits=t)
+    Kh = synth.kv_tensor(L, nkv, 128, seed=23)
+    Vh = synth.kv_tensor(L, nkv, 128, seed=24, outlier_channels=0)
+    B.cas_kv_append(ctx, kv, 0, 0, _dev(torch, Kh), _dev(torch, Vh))
+    B.cas_kv_set_len(kv, 0, L)
+    Q = synth.normal_bf16((ncols, nq, 128), 0.7, seed=25)
+    Kn = synth.kv_tensor(ncols, nkv, 128, seed=26)
+    Vn = synth.kv_tensor(ncols, nkv, 128, seed=27, outlier_channels=0)
+    out = _host(B.cas_attention(ctx, kv, 0, 0, full, _dev(torch, Q), _dev(torch, Kn), _dev(torch, Vn)))
+    pk = O.encode_kv(Kh.reshape(-1, 128), keep, t); pv = O.encode_kv(Vh.reshape(-1, 128), keep, t)
+    dec = O.decode_full if full else O.decode_draft
+    Kc = dec(pk).reshape(L, nkv, 128); Vc = dec(pv).reshape(L, nkv, 128)
+    ref = _ref_attention(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv)
+    reff = O.bf16_to_f64(ref)
+    err = np.abs(O.bf16_to_f64(out) - reff)
+    tol = _attn_tol(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv, reff)
+    assert (err <= tol).all(), float((err / tol).max())
+    # the last column alone gets the bits it gets in company
+    o1 = _host(B.cas_attention(ctx, kv, 0, 0, full, _dev(torch, Q[ncols - 1:]), _dev(torch, Kn), _dev(torch, Vn)))
+    np.testing.assert_array_equal(o1[0], out[ncols - 1])
