@@ -140,6 +140,13 @@ int cas_gemv_draft_fused(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec
 int cas_gemm_verify(cas_ctx* ctx, const cas_wdesc* desc, const void* d_spec,
                     const void* d_verif, const uint16_t* d_X, int ncols, float* d_Y);
 
+/* Dense bf16 GEMV on the uncompressed matrix: the BFloat16 baseline the paper's speedups are
+ * normalised to (Sec. 7).  d_W: bf16 [rows][ld], d_x: bf16 [cols], d_y: float [rows].  Context
+ * for measurements only, not part of the method.  CAS_ENOTSUP unless cols and ld are multiples
+ * of 8, d_W and d_x are 16-byte aligned and x fits the LDS. */
+int cas_gemv_bf16(cas_ctx* ctx, const uint16_t* d_W, int64_t rows, int64_t cols, int64_t ld,
+                  const uint16_t* d_x, float* d_y);
+
 /* ---- speculation data with unary-coded exponents (Sec. 4.2 "Exponent Compression": the
  *      lossless configuration; decoder of Sec. 5.1, zero counting with carry across chunks) ---- */
 

@@ -138,6 +138,7 @@ _SIGNATURES = {
     "cas_unary_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p]),
     "cas_unary_decode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
     "cas_gemv_draft_unary": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p]),
+    "cas_gemv_bf16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "cas_mx_plan": (C.c_int, [C.POINTER(cas_wdesc), C.POINTER(cas_mxdesc)]),
     "cas_mx_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "cas_mx_decode": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
@@ -312,6 +313,17 @@ def cas_gemv_draft_unary(ctx: Context, uw: UnaryWeight, x, out=None):
         out = torch.empty(d.rows, dtype=torch.float32, device=x.device)
     ctx._check(_lib().cas_gemv_draft_unary(ctx.h, C.byref(uw.desc), _ptr(uw.uspec), _ptr(x), _ptr(out)),
                "cas_gemv_draft_unary")
+    return out
+
+
+def cas_gemv_bf16(ctx: Context, W, x, out=None):
+    """Dense baseline: W bf16 bits [rows, cols] (row-major), x bf16 bits [cols] -> float32 [rows]."""
+    torch = ctx._torch
+    assert W.dim() == 2 and W.is_contiguous() and W.element_size() == 2 and x.numel() == W.shape[1]
+    if out is None:
+        out = torch.empty(W.shape[0], dtype=torch.float32, device=W.device)
+    ctx._check(_lib().cas_gemv_bf16(ctx.h, _ptr(W), W.shape[0], W.shape[1], W.shape[1], _ptr(x), _ptr(out)),
+               "cas_gemv_bf16")
     return out
 
 

@@ -363,7 +363,7 @@ class ModelRoundWorkload:
         t_draft, t_verify, t_plain = self._time_passes()
         k = self.k
         # context: the same linear layers as plain bf16 through the vendor GEMV (torch.mv), one pass
-        t_bf16 = None
+        t_bf16 = t_own = None
         if self.dense:
             torch = self.torch
             xs = {c: torch.randn(c, device="cuda").to(torch.bfloat16) for c in {w.shape[1] for w in self.dense}}
@@ -380,6 +380,23 @@ class ModelRoundWorkload:
             e1.record()
             torch.cuda.synchronize()
             t_bf16 = e0.elapsed_time(e1) / 3
+            # and through the library's own dense kernel (cas_gemv_bf16)
+            B = self.B
+            ys = {r: torch.empty(r, device="cuda") for r in {w.shape[0] for w in self.dense}}
+            xb = {c: v.view(torch.int16) for c, v in xs.items()}
+            wd = [w.view(torch.int16) for w in self.dense]
+
+            def own():
+                for w in wd:
+                    B.cas_gemv_bf16(self.ctx, w, xb[w.shape[1]], ys[w.shape[0]])
+            own()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(3):
+                own()
+            e1.record()
+            torch.cuda.synchronize()
+            t_own = e0.elapsed_time(e1) / 3
         # Speed model of Sec. 2.2: a round costs k t_draft + t_verify and yields accepted + 1 tokens.
         # The acceptance of a random-init model is ~0, so the table below uses an ASSUMED per-token
         # acceptance probability alpha (synthetic; the paper's acceptance table did not survive).
@@ -395,6 +412,8 @@ class ModelRoundWorkload:
                "plain_decode_tokens_per_s": self.batch * 1e3 / t_plain,
                "context_vendor_bf16_gemv_pass_ms": t_bf16,
                "context_vendor_bf16_gemv_GBps": None if t_bf16 is None else 2.0 * self.values / (t_bf16 * 1e-3) / 1e9,
+               "context_own_bf16_gemv_pass_ms": t_own,
+               "context_own_bf16_gemv_GBps": None if t_own is None else 2.0 * self.values / (t_own * 1e-3) / 1e9,
                "tokens_per_s_at_assumed_acceptance": synth_tps,
                "tokens_per_s_forced_acceptance_schedule": {f"alpha={a}": self._forced_rounds(a)
                                                            for a in (0.6, 0.8, 1.0)},

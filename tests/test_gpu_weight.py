@@ -274,3 +274,26 @@ def test_empty_matrix_is_accepted(env):
     assert B.cas_gemv_draft(ctx, ew, x[:1].contiguous()).shape == (1, 0)
     assert B.cas_gemm_verify(ctx, ew, x).shape == (2, 0)
     assert B.cas_decode_weight(ctx, ew, full=True).shape == (0, 256)
+
+
+@pytest.mark.parametrize("rows,cols", [(40, 4096), (7, 14336), (300, 64), (5, 8), (1000, 1032), (33, 28672)])
+def test_dense_bf16_baseline_gemv(env, rows, cols):
+    """The uncompressed baseline kernel against the plain definition y = W x."""
+    torch, B, ctx = env
+    W = synth.weight_matrix(rows, cols, seed=rows + cols)
+    x = synth.activations(cols, 1, seed=3)
+    y = B.cas_gemv_bf16(ctx, _dev(torch, W), _dev(torch, x[0])).cpu().numpy()
+    ref = O.gemv(W, x[0])
+    err = np.abs(y - ref) / _tol(W, x)[0]
+    assert err.max() < 2e-5, err.max()
+
+
+def test_dense_bf16_baseline_rejects_unaligned_rows(env):
+    torch, B, ctx = env
+    W = _dev(torch, synth.weight_matrix(4, 77, seed=1))
+    x = _dev(torch, synth.activations(77, 1, seed=2)[0])
+    with pytest.raises(B.CasError) as e:
+        B.cas_gemv_bf16(ctx, W, x)
+    assert e.value.code == B.CAS_ENOTSUP
+    assert B.cas_gemv_bf16(ctx, torch.empty((0, 64), dtype=torch.int16, device="cuda"),
+                           torch.zeros(64, dtype=torch.int16, device="cuda")).shape == (0,)
