@@ -1,0 +1,64 @@
+"""Forty seeded random small cases (rows 1..40, columns 1..700, any kept fraction and
+truncation, with and without activation norms) through every weight-side entry point of the C
+ABI against the oracle: encoded streams and both reconstructions bit for bit, draft GEMV (1..4
+columns), verification GEMM (1..20 columns), and the unary and shared-exponent re-codings."""
+import numpy as np
+import pytest
+
+from oracle import cassandra_oracle as O
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+
+
+def test_random_small_cases_match_oracle():
+    import torch
+    from paper_2605_26558_amd import binding as B
+    ctx = B.Context(workspace=torch.empty(8 << 20, dtype=torch.uint8, device="cuda"))
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        rows, cols = int(rng.integers(1, 41)), int(rng.integers(1, 701))
+        keep = int(rng.choice([0, 100, 250, 500, 600, 900, 1000]))
+        t = int(rng.integers(0, 8))
+        batch, ncols = int(rng.integers(1, 5)), int(rng.integers(1, 21))
+        use_act = bool(rng.integers(0, 2))
+        print(f"case {case}: rows={rows} cols={cols} keep={keep} t={t} batch={batch} ncols={ncols} act={use_act}", flush=True)
+        W = synth.weight_matrix(rows, cols, seed=1000 + case)
+        act = synth.act_norm(cols, seed=case) if use_act else None
+        X = synth.activations(cols, max(batch, ncols), seed=2000 + case)
+        ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t, None if act is None else torch.from_numpy(act).cuda())
+        p = O.encode_weight(W, keep, t, act)
+        d = ew.desc
+        sp, vf = ew.spec.cpu().numpy(), ew.verif.cpu().numpy()
+        def region(buf, off, w):
+            return buf[off: off + rows * w * 4].view("<u4").reshape(rows, w)
+        np.testing.assert_array_equal(region(sp, d.off_bitmap, d.bw), p.bitmap)
+        np.testing.assert_array_equal(region(sp, d.off_spec, d.sw), p.spec)
+        np.testing.assert_array_equal(region(vf, d.off_lo, d.lw), p.lo)
+        np.testing.assert_array_equal(region(vf, d.off_pruned, d.pw), p.pruned)
+        np.testing.assert_array_equal(B.cas_decode_weight(ctx, ew, full=True).cpu().numpy().view(np.uint16), W)
+        np.testing.assert_array_equal(B.cas_decode_weight(ctx, ew, full=False).cpu().numpy().view(np.uint16),
+                                      O.decode_draft(p))
+        wn = np.linalg.norm(O.bf16_to_f64(W), axis=1) + 1e-30
+        xn = np.linalg.norm(O.bf16_to_f64(X), axis=1)
+        yd = B.cas_gemv_draft(ctx, ew, _dev(torch, X[:batch])).cpu().numpy()
+        for b in range(batch):
+            assert (np.abs(yd[b] - O.gemv_draft(p, X[b])) <= 2e-5 * wn * xn[b] + 1e-30).all()
+        yv = B.cas_gemm_verify(ctx, ew, _dev(torch, X[:ncols])).cpu().numpy()
+        ref = O.bf16_to_f64(X[:ncols]) @ O.bf16_to_f64(W).T
+        assert (np.abs(yv - ref) <= 2e-5 * wn[None, :] * xn[:ncols, None] + 1e-30).all()
+        # re-codings of the speculation data
+        uw = B.cas_unary_encode(ctx, ew)
+        np.testing.assert_array_equal(B.cas_unary_decode(ctx, uw, full=True).cpu().numpy().view(np.uint16), W)
+        yu = B.cas_gemv_draft_unary(ctx, uw, _dev(torch, X[:1])).cpu().numpy()
+        assert (np.abs(yu - O.gemv_draft(p, X[0])) <= 2e-5 * wn * xn[0] + 1e-30).all()
+        mw = B.cas_mx_encode(ctx, ew)
+        m = O.to_mx(p)
+        np.testing.assert_array_equal(B.cas_mx_decode(ctx, mw, full=True).cpu().numpy().view(np.uint16),
+                                      O.decode_full_mx(m))
+        ym = B.cas_gemv_draft_mx(ctx, mw, _dev(torch, X[:1])).cpu().numpy()
+        assert (np.abs(ym - O.gemv_draft_mx(m, X[0])) <= 2e-5 * wn * xn[0] + 1e-30).all()
