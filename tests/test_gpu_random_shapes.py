@@ -62,3 +62,60 @@ def test_random_small_cases_match_oracle():
                                       O.decode_full_mx(m))
         ym = B.cas_gemv_draft_mx(ctx, mw, _dev(torch, X[:1])).cpu().numpy()
         assert (np.abs(ym - O.gemv_draft_mx(m, X[0])) <= 2e-5 * wn * xn[0] + 1e-30).all()
+
+
+def test_random_attention_cases_match_oracle():
+    """Thirty seeded random cases of the online KV encoder and of attention over the compressed
+    cache: cache lengths 0..300 over shuffled pages, 1..3 kv heads with 1..8 query heads each,
+    any cache format, draft (up to 4 columns) and verification (up to 16) calls."""
+    import torch
+    from paper_2605_26558_amd import binding as B
+    ctx = B.Context(workspace=torch.empty(16 << 20, dtype=torch.uint8, device="cuda"))
+    rng = np.random.default_rng(77)
+    for case in range(30):
+        nkv, grp = int(rng.integers(1, 4)), int(rng.choice([1, 2, 4, 8]))
+        nq = nkv * grp
+        full = bool(rng.integers(0, 2))
+        max_cols = min(16, (80 if full else 48) // grp)
+        ncols = int(rng.integers(1, (max_cols if full else min(4, max_cols)) + 1))
+        n_new = int(rng.integers(ncols, min(ncols + 4, 64) + 1))
+        L = int(rng.integers(0, 301))
+        keep, t = int(rng.choice([250, 600, 1000])), int(rng.choice([0, 4, 7]))
+        print(f"case {case}: nq={nq} nkv={nkv} L={L} ncols={ncols} n_new={n_new} full={full} keep={keep} t={t}", flush=True)
+        pages = 6
+        perm = torch.from_numpy(rng.permutation(pages).astype(np.int32)).reshape(1, pages)
+        kv = B.KVCache(ctx, 1, nkv, n_pages=pages, max_seqs=1, max_pages_per_seq=pages, keep_permille=keep,
+                       trunc_bits=t, page_table=perm)
+        Kh = synth.kv_tensor(max(L, 1), nkv, 128, seed=100 + case)
+        Vh = synth.kv_tensor(max(L, 1), nkv, 128, seed=200 + case, outlier_channels=0)
+        if L:
+            B.cas_kv_append(ctx, kv, 0, 0, _dev(torch, Kh[:L]), _dev(torch, Vh[:L]))
+            Kf, Vf = B.cas_kv_read(ctx, kv, 0, 0, 0, L, full=True)
+            np.testing.assert_array_equal(Kf.cpu().numpy().view(np.uint16), Kh[:L])      # the encoder is lossless
+            np.testing.assert_array_equal(Vf.cpu().numpy().view(np.uint16), Vh[:L])
+        B.cas_kv_set_len(kv, 0, L)
+        dec = O.decode_full if full else O.decode_draft
+        if L:
+            Kc = dec(O.encode_kv(Kh[:L].reshape(-1, 128), keep, t)).reshape(L, nkv, 128)
+            Vc = dec(O.encode_kv(Vh[:L].reshape(-1, 128), keep, t)).reshape(L, nkv, 128)
+            if not full:
+                Kd, Vd = B.cas_kv_read(ctx, kv, 0, 0, 0, L, full=False)
+                np.testing.assert_array_equal(Kd.cpu().numpy().view(np.uint16), Kc)
+                np.testing.assert_array_equal(Vd.cpu().numpy().view(np.uint16), Vc)
+        else:
+            Kc = np.zeros((0, nkv, 128), np.uint16); Vc = Kc.copy()
+        Q = synth.normal_bf16((ncols, nq, 128), 0.6, seed=300 + case)
+        Kn = synth.kv_tensor(n_new, nkv, 128, seed=400 + case)
+        Vn = synth.kv_tensor(n_new, nkv, 128, seed=500 + case, outlier_channels=0)
+        out = B.cas_attention(ctx, kv, 0, 0, full, _dev(torch, Q), _dev(torch, Kn), _dev(torch, Vn))
+        out = O.bf16_to_f64(out.cpu().numpy().view(np.uint16))
+        for c in range(ncols):
+            vis = n_new - ncols + c + 1
+            k = O.bf16_to_f64(np.concatenate([Kc, Kn[:vis]])); v = O.bf16_to_f64(np.concatenate([Vc, Vn[:vis]]))
+            for h in range(nq):
+                q = O.bf16_to_f64(Q[c, h])
+                ref = O.attention_one(q, k[:, h // grp, :], v[:, h // grp, :])
+                s = k[:, h // grp, :] @ q / np.sqrt(128.0)
+                pr = np.exp(s - s.max()); pr /= pr.sum()
+                tol = 2e-3 * np.linalg.norm(pr) * np.linalg.norm(v[:, h // grp, :], axis=0) + 2.0 ** -8 * np.abs(ref)
+                assert (np.abs(out[c, h] - ref) <= tol).all(), (case, c, h)
