@@ -370,7 +370,11 @@ int cas_model_destroy(cas_model* model);
 /* One draft pass (Sec. 4.1 draft inference): speculation data only for every linear layer and
  * for the cache.  d_token_in: the token at in-flight slot `slot` (position len + slot);
  * its K/V go to slot `slot`, earlier slots must hold the K/V of the previous draft passes of
- * this round.  d_token_out: the drafted next token.  d_logits: NULL or float [vocab]. */
+ * this round.  d_token_out: the drafted next token.  d_logits: NULL or float [vocab].
+ * This call and cas_verify_step enqueue kernels only (no copies, no memsets, no
+ * synchronisation) and may be recorded into a HIP graph once they have run eagerly with the
+ * same shapes; the cache length is an argument of the kernels, so a graph is valid for the
+ * cache state it was captured in. */
 int cas_draft_step(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const int32_t* d_token_in,
                    int slot, int32_t* d_token_out, float* d_logits);
 

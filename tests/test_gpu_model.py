@@ -261,3 +261,47 @@ def test_multi_sequence_round_equals_single_sequence_rounds(env, max_cols, k, ns
     assert multi == single
     for s in range(nseq):
         assert B.cas_kv_len(kv_a, s) == B.cas_kv_len(kv_b, s)
+
+
+def test_step_calls_replay_from_a_hip_graph():
+    """cas_draft_step and cas_verify_step enqueue kernels only (no copies, no memsets), so a
+    caller may capture them.  A graph holding one draft pass and one 4-column verification pass
+    is replayed three times with other work and synchronisations in between; every replay gives
+    the bits of the eager calls.  (The cache length is an argument of the kernels: a graph stays
+    valid for the cache state it was captured in.)"""
+    import torch
+    from paper_2605_26558_amd import binding as B
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx = B.Context(workspace=torch.empty(32 << 20, dtype=torch.uint8, device="cuda"))
+        weights = synth.model_weights(SHAPE, seed=4)
+        model, kv = gpu_model(torch, B, ctx, weights, 600, 4, max_cols=8)
+        prompt = synth.token_ids(20, SHAPE.vocab, seed=6)
+        B.cas_prefill(ctx, model, kv, 0, torch.from_numpy(prompt).cuda())
+        tok = torch.tensor([5], dtype=torch.int32, device="cuda")
+        toks4 = torch.tensor([5, 9, 2, 7], dtype=torch.int32, device="cuda")
+        nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+        dl = torch.empty((1, SHAPE.vocab), dtype=torch.float32, device="cuda")
+        tgt = torch.empty(4, dtype=torch.int32, device="cuda")
+        vl = torch.empty((4, SHAPE.vocab), dtype=torch.float32, device="cuda")
+
+        def steps():
+            B.cas_draft_step(ctx, model, kv, 0, tok, 0, nxt, dl)
+            B.cas_verify_step(ctx, model, kv, 0, toks4, 3, tgt, vl)
+        steps()                                  # eager: also grants the kernels their LDS sizes
+        side.synchronize()
+        want = [t.clone() for t in (nxt, dl, tgt, vl)]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            steps()
+        for rep in range(3):
+            for t in (nxt, dl, tgt, vl):
+                t.zero_()
+            scratch = torch.randn(1 << 20, device="cuda").sum()      # unrelated eager work between replays
+            side.synchronize()
+            graph.replay()
+            side.synchronize()
+            for got, ref in zip((nxt, dl, tgt, vl), want):
+                assert torch.equal(got, ref), rep
+            assert bool(torch.isfinite(scratch))
+    torch.cuda.synchronize()
