@@ -13,7 +13,9 @@ Parity pins (tests/test_oracle_*.py): exhaustive bit-exact round trip over all
 65536 bf16 patterns, bit-prefix property of truncation, kept count, brute-force
 subset search for the selection, closed-form stream sizes, library matmul /
 attention special cases, brute-force acceptance, speculative == plain token
-streams, and for the unary exponent code the printed code words, a sequential
+streams, hand-worked roundings of the residual add, tied maxima of the greedy token, Eq. 2 and
+the grid search worked by hand, the forward composition (target and draft pass) against a
+separately written float64 decoder made of library operations, and for the unary exponent code the printed code words, a sequential
 scan, the closed-form length and an exhaustive search over code assignments; for the
 shared-exponent form the conversion restated as real arithmetic, the lossless special case,
 the error bound of one unit of the block's last place and hand-worked blocks.  Parity unpinned:

@@ -87,10 +87,12 @@ def test_decoder_ops_against_library():
     gb, ub = O.round_bf16(gate), O.round_bf16(up)
     ref = (torch.nn.functional.silu(torch.tensor(gb)) * torch.tensor(ub)).numpy()
     np.testing.assert_allclose(O.bf16_to_f64(O.swiglu(gate, up)), ref, rtol=2.0 ** -8, atol=1e-30)
-    # residual add rounds the addend, then the sum
+    # residual add: against the library's bf16 tensors, addend rounded, then the sum (the
+    # hand-worked cases that separate other readings are in test_oracle_pins.py)
     y = np.array([0.1, -3.7, 1e-3])
     hh = O.f64_to_bf16(np.array([1.0, 2.0, -4.0]))
-    np.testing.assert_array_equal(O.add_bf16(hh, y), O.f64_to_bf16(O.bf16_to_f64(hh) + O.round_bf16(y)))
+    ref = (torch.tensor([1.0, 2.0, -4.0], dtype=torch.bfloat16) + torch.tensor(y).to(torch.bfloat16))
+    np.testing.assert_array_equal(O.add_bf16(hh, y).view(np.int16), ref.view(torch.int16).numpy())
 
 
 def test_rope_is_a_rotation_by_position_angle():
