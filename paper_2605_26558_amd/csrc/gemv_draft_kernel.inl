@@ -48,6 +48,17 @@ constexpr int kGemvWaves = kGemvThreads / 64;
 // x in LDS: fp32 for one column; bf16 bit patterns (XH) for a batch, whose gathers of NB
 // values per kept weight would otherwise saturate the LDS (measured 2.4x slower at NB = 4).
 // The staged values are bf16-representable either way; XH costs one shift per use.
+// Layout: per chunk of 64 bitmap words a block [1 + 32][64 lanes][NB]; row 0 holds zeros, row
+// 1 + k the values of column k of every lane's word.  A lane only ever reads entries of its own
+// 4-byte column of the block, so the gathers of a wave never meet in a bank whatever positions
+// the lanes are at (with one 33-entry segment per lane they collided at ~3.8 extra cycles per
+// gather, which made the LDS a co-limit of the kernel).
+constexpr int kXRows = 33;
+template <int NB>
+__device__ __forceinline__ int x_index(int col) {  // index of x[col][0] in the staged layout
+  const int w = col >> 5;
+  return (((w >> 6) * kXRows + 1 + (col & 31)) * 64 + (w & 63)) * NB;
+}
 template <bool XH>
 struct XStage {
   using type = float;
@@ -119,7 +130,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
 #pragma unroll
     for (int j = 0; j < FW; ++j) win[j] = __builtin_amdgcn_alignbit(w.d[j + 1], w.d[j], w.sh);
     uint32_t m = w.m;
-    const XT* xb = xs + ((c.chunk * 64 + lane) * 33 + 1) * NB;
+    const XT* xb = xs + ((c.chunk * kXRows + 1) * 64 + lane) * NB;
     float accw[NB];  // shared-exponent form: unscaled sum of the lane's word
 #pragma unroll
     for (int b = 0; b < NB; ++b) accw[b] = 0.f;
@@ -128,7 +139,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
       int pos = lowest_bit(m);
       m &= m - 1u;
       const uint32_t top = field_top<FW, i>(win);
-      const XT* xp = xb + pos * NB;
+      const XT* xp = xb + pos * (64 * NB);
       if constexpr (MX) {
         // sign at bit 31, magnitude below it; a lane past its last field reads neighbouring
         // bits, always a finite number, and multiplies it by the zero entry of the segment
@@ -182,7 +193,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
     }
   };
 
-  // ---- x is staged as fp32, segment layout [word][1 + 32][NB]; entry 0 of a segment is 0.0.
+  // ---- x is staged in blocks [chunk][1 + 32][64][NB]; row 0 of a block is 0.0.
   // Fast path (cols a multiple of 8, at most 2 pieces of 8 per thread): x and the norm gain are
   // read once with 16-byte loads, requested before anything else so they travel together with
   // the first bitmap words, and stay in registers between the norm reduction and the LDS writes.
@@ -207,7 +218,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   auto stage_x = [&]() {
     for (int sgi = tid; sgi < nseg; sgi += kGemvThreads) {
 #pragma unroll
-      for (int b = 0; b < NB; ++b) xs[sgi * 33 * NB + b] = XS::put(0.f);
+      for (int b = 0; b < NB; ++b) xs[(((sgi >> 6) * kXRows) * 64 + (sgi & 63)) * NB + b] = XS::put(0.f);
     }
     float rn[NB];
 #pragma unroll
@@ -253,7 +264,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
         const int col = piece * 8;
         if (piece < npiece) {
           const uint32_t gw4[4] = {gv[k].x, gv[k].y, gv[k].z, gv[k].w};
-          XT* dst = xs + ((col >> 5) * 33 + 1 + (col & 31)) * NB;
+          XT* dst = xs + x_index<NB>(col);  // the 8 columns of a piece lie in one word: 64 * NB apart
 #pragma unroll
           for (int b = 0; b < NB; ++b) {
             const uint32_t wd[4] = {raw[k][b].x, raw[k][b].y, raw[k][b].z, raw[k][b].w};
@@ -264,8 +275,8 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
                 lo = round_bf16(lo * rn[b] * __uint_as_float(gw4[e] << 16));
                 hi = round_bf16(hi * rn[b] * __uint_as_float(gw4[e] & 0xFFFF0000u));
               }
-              dst[(2 * e) * NB + b] = XS::put(lo);
-              dst[(2 * e + 1) * NB + b] = XS::put(hi);
+              dst[(2 * e) * 64 * NB + b] = XS::put(lo);
+              dst[(2 * e + 1) * 64 * NB + b] = XS::put(hi);
             }
           }
         }
@@ -291,7 +302,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
             v = bf16_to_f32(a.x[(size_t)b * a.cols + col]);
             if (a.gain) v = round_bf16(v * rn[b] * bf16_to_f32(a.gain[col]));
           }
-          xs[((col >> 5) * 33 + 1 + (col & 31)) * NB + b] = XS::put(v);
+          xs[x_index<NB>(col) + b] = XS::put(v);
         }
       }
     }

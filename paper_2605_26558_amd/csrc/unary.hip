@@ -207,8 +207,9 @@ __global__ __launch_bounds__(64) void unary_decode_kernel(UnaryArgs a, uint16_t*
 // in chunks of 64 words as the raw-exponent kernel does: a DPP prefix sum gives each lane the
 // index of its first kept value, its sign / mantissa fields are one contiguous run that is
 // loaded as a register window and aligned once, and step i of the bit walk uses field i of the
-// window and exponent i of the lane's run.  x sits in LDS as fp32 in segments of 1 + 32
-// entries whose entry 0 is 0.0, so a lane that has run out of set bits multiplies by zero.
+// window and exponent i of the lane's run.  x sits in LDS as fp32 in blocks [1 + 32][64 lanes]
+// per chunk whose row 0 is 0.0, so a lane that has run out of set bits multiplies by zero, and
+// a lane reads only its own 4-byte column of the block (no bank conflicts between lanes).
 constexpr int kUnaryWaves = 8;
 
 template <int T>
@@ -218,13 +219,13 @@ __global__ __launch_bounds__(64 * kUnaryWaves) void gemv_draft_unary_kernel(Unar
   extern __shared__ uint8_t lds8[];
   const int nseg = ((a.bw + 63) >> 6) << 6;
   uint8_t* tab = lds8;                                           // exp_of_rank
-  float* xs = reinterpret_cast<float*>(lds8 + 256);              // [nseg][33]
+  float* xs = reinterpret_cast<float*>(lds8 + 256);              // [nseg / 64][33][64]
   uint8_t* exps_all = lds8 + 256 + (size_t)nseg * 33 * 4;        // [waves][kpad + kExpSlack]
   const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (tid < 256) tab[tid] = a.table[tid];
-  for (int sg = tid; sg < nseg; sg += 64 * kUnaryWaves) xs[sg * 33] = 0.f;
+  for (int sg = tid; sg < nseg; sg += 64 * kUnaryWaves) xs[(sg >> 6) * 33 * 64 + (sg & 63)] = 0.f;
   for (int c = tid; c < nseg * 32; c += 64 * kUnaryWaves)
-    xs[(c >> 5) * 33 + 1 + (c & 31)] = c < a.cols ? bf16_to_f32(x[c]) : 0.f;
+    xs[((c >> 11) * 33 + 1 + (c & 31)) * 64 + ((c >> 5) & 63)] = c < a.cols ? bf16_to_f32(x[c]) : 0.f;
   uint8_t* exps = exps_all + (size_t)wv * (kpad + kExpSlack);
   // what lies past a row's last exponent must be a finite number's exponent
   for (int i = lane; i < kpad + kExpSlack; i += 64) exps[i] = 0;
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(64 * kUnaryWaves) void gemv_draft_unary_kernel(Unar
 #pragma unroll
       for (int j = 0; j < SW; ++j) win[j] = __builtin_amdgcn_alignbit(d[j + 1], d[j], sh);
       const uint8_t* ex = exps + e0;
-      const float* xb = xs + w * 33 + 1;
+      const float* xb = xs + ((w0 >> 6) * 33 + 1) * 64 + lane;
       auto step = [&](auto I) {
         constexpr int i = decltype(I)::value;
         const int pos = lowest_bit(m);
@@ -264,7 +265,7 @@ __global__ __launch_bounds__(64 * kUnaryWaves) void gemv_draft_unary_kernel(Unar
         // fp32 pattern of the zero-padded bf16: sign | exponent | leading mantissa bits
         const uint32_t mant = __builtin_amdgcn_ubfe(top, 8, 23);
         const uint32_t bits = (top & 0x80000000u) | ((uint32_t)ex[i] << 23) | mant;
-        acc = fmaf(__uint_as_float(bits), xb[pos], acc);
+        acc = fmaf(__uint_as_float(bits), xb[pos * 64], acc);
       };
       static_for<0, 16>(step);
       auto tail = [&](auto self, auto I) -> void {
