@@ -38,7 +38,7 @@ enum {
   CAS_OK = 0,
   CAS_EINVAL = -1,   /* bad shape, alignment, format or NULL pointer */
   CAS_ENOTSUP = -2,  /* valid request without a kernel (e.g. exp_mode != 0) */
-  CAS_ENOMEM = -3,   /* workspace or pool too small */
+  CAS_ENOMEM = -3,   /* workspace, pool or the library's fixed scratch array too small */
   CAS_EHIP = -4      /* a HIP call failed; cas_last_hip_error() has the code */
 };
 
@@ -316,6 +316,27 @@ int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_to
 int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q,
                   int ncols, int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew,
                   int n_new, uint16_t* d_O);
+
+/*
+ * cas_attention for callers that cannot allocate device memory or have none to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit for bit the same output as cas_attention, but the per-split
+ * partial results go to a fixed device array inside the library (cas_attention_static_capacity()
+ * bytes, 32 MiB, held by every GPU the library runs on until the process ends) instead of the
+ * context workspace; the context may have been created without one.  The call allocates
+ * nothing (no hipMalloc / hipFree, no events, no library that allocates) and does not
+ * synchronise.  CAS_ENOMEM when the partials of the call (splits * n_kv_heads * ncols * group *
+ * 132 floats, one split per 64 positions) exceed the array; CAS_EINVAL when the device that was
+ * current at cas_ctx_create is not current.  The array keeps the contents of the last call and
+ * nothing in it needs clearing (every record is written before it is read); all calls on one GPU
+ * share it, so two calls that may overlap on that GPU (different streams or threads) race:
+ * serialise them.  The measurement hooks (cas_prof_*) do not see this call.
+ */
+int cas_attention_static(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q,
+                         int ncols, int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew,
+                         int n_new, uint16_t* d_O);
+/* Host only: size in bytes of that array. */
+size_t cas_attention_static_capacity(void);
 
 /* ---- model-level steps of one speculative round (Sec. 2.2, Sec. 4.1) --------------------- */
 

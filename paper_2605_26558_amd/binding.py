@@ -107,6 +107,9 @@ _SIGNATURES = {
                               C.c_void_p, C.c_void_p]),
     "cas_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
                                 C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
+    "cas_attention_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
+                                       C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
+    "cas_attention_static_capacity": (C.c_size_t, []),
     "cas_model_act_bytes": (C.c_int, [C.POINTER(cas_model_cfg), C.POINTER(C.c_size_t)]),
     "cas_model_create": (C.c_int, [C.POINTER(cas_model_cfg), C.POINTER(cas_model_weights), C.c_void_p, C.c_size_t,
                                    C.POINTER(C.c_void_p)]),
@@ -513,6 +516,19 @@ def cas_attention(ctx: Context, kv: KVCache, layer, seq, full, Q, Knew, Vnew, ou
     ctx._check(_lib().cas_attention(ctx.h, kv.h, layer, seq, 1 if full else 0, _ptr(Q), Q.shape[0], Q.shape[1],
                                     _ptr(Knew), _ptr(Vnew), Knew.shape[0], _ptr(out)), "cas_attention")
     return out
+
+
+def cas_attention_static(ctx: Context, kv: KVCache, layer, seq, full, Q, Knew, Vnew, out):
+    """cas_attention with the partial results in the library's fixed device array; `out` must be
+    given (this wrapper allocates nothing either)."""
+    assert Q.is_contiguous() and Knew.is_contiguous() and Vnew.is_contiguous() and out.is_contiguous()
+    ctx._check(_lib().cas_attention_static(ctx.h, kv.h, layer, seq, 1 if full else 0, _ptr(Q), Q.shape[0], Q.shape[1],
+                                           _ptr(Knew), _ptr(Vnew), Knew.shape[0], _ptr(out)), "cas_attention_static")
+    return out
+
+
+def cas_attention_static_capacity() -> int:
+    return int(_lib().cas_attention_static_capacity())
 
 
 def _tensor(ew: EncodedWeight) -> cas_tensor:

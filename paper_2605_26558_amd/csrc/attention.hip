@@ -21,6 +21,7 @@
 // Partial (max, sum, output) of every page go to the workspace; a merge kernel combines them
 // in a fixed order.
 #include <algorithm>
+#include <atomic>
 #include "attention_kernel.inl"
 
 namespace cas {
@@ -108,7 +109,11 @@ __global__ __launch_bounds__(512) void attn_merge_kernel(AttnBatch batch) {
 
 // Up to kAttnBatch sequences of one pass in one pair of launches (same layer, same form, same
 // number of query heads); every sequence gets exactly what a launch of its own would give it.
-static int launch_attention_group(cas_ctx* ctx, cas_kv* kv, const AttnCall* calls, int n, size_t* ws_used) {
+// ws / ws_bytes: device memory for the per-split partial results; prof: bracket the launch with
+// events when the context's measurement hooks are on (creates events: not for callers that may
+// not allocate).
+static int launch_attention_group(cas_ctx* ctx, cas_kv* kv, const AttnCall* calls, int n, void* ws, size_t ws_bytes,
+                                  size_t* ws_used, bool prof) {
   const KvGeom& g = kv->geom;
   const AttnCall& c0 = calls[0];
   AttnBatch b{};
@@ -143,8 +148,8 @@ static int launch_attention_group(cas_ctx* ctx, cas_kv* kv, const AttnCall* call
     if (pages > g.max_pages_per_seq) return CAS_ENOMEM;
     q.nsplit = (pages + kPagesPerSplit - 1) / kPagesPerSplit;
     const size_t need = sizeof(float) * (size_t)q.nsplit * g.n_kv_heads * R * kPartStride;
-    if (!ctx->d_ws || *ws_used + need > ctx->ws_bytes) return CAS_ENOMEM;
-    q.part = (float*)((char*)ctx->d_ws + *ws_used);
+    if (!ws || *ws_used + need > ws_bytes) return CAS_ENOMEM;
+    q.part = (float*)((char*)ws + *ws_used);
     *ws_used += (need + 255) / 256 * 256;
     max_r = std::max(max_r, R);
     max_split = std::max(max_split, q.nsplit);
@@ -156,7 +161,7 @@ static int launch_attention_group(cas_ctx* ctx, cas_kv* kv, const AttnCall* call
   dim3 grid(max_split, g.n_kv_heads, n);
   int rc;
   {
-    ProfScope prof(ctx, c0.full ? PROF_ATTN_VERIFY : PROF_ATTN_DRAFT, bytes);
+    ProfScope scope(prof ? ctx : nullptr, c0.full ? PROF_ATTN_VERIFY : PROF_ATTN_DRAFT, bytes);
     if (c0.full) {
       rc = MT == 1   ? launch_mt<1, true>(ctx, b, grid)
            : MT == 2 ? launch_mt<2, true>(ctx, b, grid)
@@ -181,12 +186,40 @@ int launch_attention_batch(cas_ctx* ctx, cas_kv* kv, const AttnCall* calls, int 
   // starts at the beginning of the workspace again
   for (int i = 0; i < n; i += kAttnBatch) {
     size_t ws_used = 0;
-    const int rc = launch_attention_group(ctx, kv, calls + i, std::min(kAttnBatch, n - i), &ws_used);
+    const int rc = launch_attention_group(ctx, kv, calls + i, std::min(kAttnBatch, n - i), ctx->d_ws, ctx->ws_bytes,
+                                          &ws_used, true);
     if (rc != CAS_OK) return rc;
   }
   return CAS_OK;
 }
 
 int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) { return launch_attention_batch(ctx, kv, &c, 1); }
+
+// ---- the variant for callers that cannot allocate: the partial results live in a fixed array of
+// the library's own instead of a workspace the caller had to obtain.  Every GPU holds its own copy
+// of the array at its own address; the address is looked up once per device, with that device
+// current, and only that pointer (never the array's name) is handed to kernels.
+constexpr size_t kAttnScratchBytes = 32u << 20;
+static __device__ __align__(256) unsigned char scratch[kAttnScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+size_t attention_static_capacity() { return kAttnScratchBytes; }
+
+int launch_attention_static(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) {
+  int dev = -1;
+  CAS_HIP(ctx, hipGetDevice(&dev));
+  if (dev != ctx->device || dev < 0 || dev >= kMaxDevices) return CAS_EINVAL;  // the context's device must be current
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    CAS_HIP(ctx, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return CAS_EHIP;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // two threads racing store the same address
+  }
+  size_t ws_used = 0;
+  // nothing in the array has to start at zero: every split writes its whole record before the
+  // merge kernel, which follows on the same stream, reads exactly the records of this call
+  return launch_attention_group(ctx, kv, &c, 1, ptr, kAttnScratchBytes, &ws_used, false);
+}
 
 }  // namespace cas

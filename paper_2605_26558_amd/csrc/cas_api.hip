@@ -47,7 +47,7 @@ const char* cas_strerror(int code) {
     case CAS_OK: return "ok";
     case CAS_EINVAL: return "invalid argument (shape, alignment, format or NULL pointer)";
     case CAS_ENOTSUP: return "not supported by this build";
-    case CAS_ENOMEM: return "workspace or pool too small";
+    case CAS_ENOMEM: return "workspace, pool or the library's fixed scratch array too small for this call";
     case CAS_EHIP: return "HIP call failed (see cas_last_hip_error)";
   }
   return "unknown error";
@@ -247,19 +247,35 @@ int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_to
   return cas::launch_kv_read(ctx, kv, layer, seq, pos0, n_tok, full, d_K, d_V);
 }
 
-int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q, int ncols,
-                  int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew, int n_new, uint16_t* d_O) {
+static int attention_call(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q, int ncols,
+                          int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew, int n_new, uint16_t* d_O,
+                          cas::AttnCall* c) {
   if (!ctx || !d_Q || !d_Knew || !d_Vnew || !d_O || check_seq(kv, layer, seq) != CAS_OK) return CAS_EINVAL;
   if (ncols < 1 || n_new < ncols || n_new > 64 || n_q_heads < kv->desc.n_kv_heads ||
       n_q_heads % kv->desc.n_kv_heads != 0)
     return CAS_EINVAL;
   if (ncols * (n_q_heads / kv->desc.n_kv_heads) > (full ? 80 : 48) || ncols > 16) return CAS_EINVAL;
-  cas::AttnCall c;
-  c.layer = layer; c.seq = seq; c.full = full ? 1 : 0;
-  c.Q = d_Q; c.ncols = ncols; c.n_q_heads = n_q_heads;
-  c.Knew = d_Knew; c.Vnew = d_Vnew; c.n_new = n_new; c.O = d_O;
-  return cas::launch_attention(ctx, kv, c);
+  c->layer = layer; c->seq = seq; c->full = full ? 1 : 0;
+  c->Q = d_Q; c->ncols = ncols; c->n_q_heads = n_q_heads;
+  c->Knew = d_Knew; c->Vnew = d_Vnew; c->n_new = n_new; c->O = d_O;
+  return CAS_OK;
 }
+
+int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q, int ncols,
+                  int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew, int n_new, uint16_t* d_O) {
+  cas::AttnCall c;
+  const int rc = attention_call(ctx, kv, layer, seq, full, d_Q, ncols, n_q_heads, d_Knew, d_Vnew, n_new, d_O, &c);
+  return rc != CAS_OK ? rc : cas::launch_attention(ctx, kv, c);
+}
+
+int cas_attention_static(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q, int ncols,
+                         int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew, int n_new, uint16_t* d_O) {
+  cas::AttnCall c;
+  const int rc = attention_call(ctx, kv, layer, seq, full, d_Q, ncols, n_q_heads, d_Knew, d_Vnew, n_new, d_O, &c);
+  return rc != CAS_OK ? rc : cas::launch_attention_static(ctx, kv, c);
+}
+
+size_t cas_attention_static_capacity(void) { return cas::attention_static_capacity(); }
 
 int cas_accept(const int32_t* h_draft, const int32_t* h_target, int k, int32_t* n_accepted, int32_t* h_out) {
   if (k < 0 || !h_target || !n_accepted || !h_out || (k > 0 && !h_draft)) return CAS_EINVAL;

@@ -100,6 +100,10 @@ struct AttnCall {
   uint16_t* Vslot = nullptr;
 };
 int launch_attention(cas_ctx*, cas_kv*, const AttnCall&);
+// the same with the partial results in the library's own fixed device array (no workspace, no
+// allocation of any kind); CAS_ENOMEM beyond attention_static_capacity() bytes of partials
+int launch_attention_static(cas_ctx*, cas_kv*, const AttnCall&);
+size_t attention_static_capacity();
 // the same for the sequences of one pass (same layer and form), four of them per pair of launches
 int launch_attention_batch(cas_ctx*, cas_kv*, const AttnCall* calls, int n);
 // Brackets one kernel launch with HIP events on the context stream when profiling is on.
@@ -107,7 +111,7 @@ struct ProfScope {
   cas_ctx* ctx;
   bool on;
   ProfRec rec;
-  ProfScope(cas_ctx* c, int cls, double bytes) : ctx(c), on(c->prof_on) {
+  ProfScope(cas_ctx* c, int cls, double bytes) : ctx(c), on(c && c->prof_on) {
     if (!on) return;
     rec.cls = cls; rec.bytes = bytes;
     if (hipEventCreate(&rec.e0) != hipSuccess || hipEventCreate(&rec.e1) != hipSuccess) { on = false; return; }
