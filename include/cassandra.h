@@ -317,6 +317,18 @@ int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const 
                   int ncols, int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew,
                   int n_new, uint16_t* d_O);
 
+/* cas_attention for n_seqs (1..16) distinct sequences of one layer and one form at once, as the
+ * multi-sequence passes issue it (low-batch serving, Sec. 1; Sec. 4.1 for the data each form
+ * reads): up to four sequences share one pair of launches.  The h_* arguments are HOST arrays of
+ * n_seqs entries; h_d_Q / h_d_Knew / h_d_Vnew / h_d_O hold DEVICE pointers with the shapes of
+ * cas_attention for h_ncols[i] columns and h_n_new[i] in-flight vectors.  Every sequence gets bit
+ * for bit what cas_attention gives it alone.  Workspace: the partials of the (up to four)
+ * sequences of a launch side by side. */
+int cas_attention_multi(cas_ctx* ctx, cas_kv* kv, int layer, int n_seqs, const int32_t* h_seqs, int full,
+                        const uint16_t* const* h_d_Q, const int32_t* h_ncols, int n_q_heads,
+                        const uint16_t* const* h_d_Knew, const uint16_t* const* h_d_Vnew,
+                        const int32_t* h_n_new, uint16_t* const* h_d_O);
+
 /*
  * cas_attention for callers that cannot allocate device memory or have none to hand over:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same

@@ -107,6 +107,9 @@ _SIGNATURES = {
                               C.c_void_p, C.c_void_p]),
     "cas_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
                                 C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
+    "cas_attention_multi": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_int32), C.c_int,
+                                      C.POINTER(C.c_void_p), C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_void_p),
+                                      C.POINTER(C.c_void_p), C.POINTER(C.c_int32), C.POINTER(C.c_void_p)]),
     "cas_attention_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
                                        C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
     "cas_attention_static_capacity": (C.c_size_t, []),
@@ -516,6 +519,21 @@ def cas_attention(ctx: Context, kv: KVCache, layer, seq, full, Q, Knew, Vnew, ou
     ctx._check(_lib().cas_attention(ctx.h, kv.h, layer, seq, 1 if full else 0, _ptr(Q), Q.shape[0], Q.shape[1],
                                     _ptr(Knew), _ptr(Vnew), Knew.shape[0], _ptr(out)), "cas_attention")
     return out
+
+
+def cas_attention_multi(ctx: Context, kv: KVCache, layer, seqs, full, Qs, Knews, Vnews):
+    """One attention call for several sequences: lists of per-sequence tensors as in cas_attention."""
+    torch = ctx._torch
+    n = len(seqs)
+    outs = [torch.empty_like(q) for q in Qs]
+    for t in (*Qs, *Knews, *Vnews):
+        assert t.is_contiguous()
+    i32 = lambda v: (C.c_int32 * n)(*[int(x) for x in v])
+    ptrs = lambda ts: (C.c_void_p * n)(*[t.data_ptr() for t in ts])
+    ctx._check(_lib().cas_attention_multi(ctx.h, kv.h, layer, n, i32(seqs), 1 if full else 0, ptrs(Qs),
+                                          i32([q.shape[0] for q in Qs]), Qs[0].shape[1], ptrs(Knews), ptrs(Vnews),
+                                          i32([k.shape[0] for k in Knews]), ptrs(outs)), "cas_attention_multi")
+    return outs
 
 
 def cas_attention_static(ctx: Context, kv: KVCache, layer, seq, full, Q, Knew, Vnew, out):

@@ -277,6 +277,23 @@ int cas_attention_static(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full,
 
 size_t cas_attention_static_capacity(void) { return cas::attention_static_capacity(); }
 
+int cas_attention_multi(cas_ctx* ctx, cas_kv* kv, int layer, int n_seqs, const int32_t* h_seqs, int full,
+                        const uint16_t* const* h_d_Q, const int32_t* h_ncols, int n_q_heads,
+                        const uint16_t* const* h_d_Knew, const uint16_t* const* h_d_Vnew, const int32_t* h_n_new,
+                        uint16_t* const* h_d_O) {
+  if (n_seqs < 1 || n_seqs > 16 || !h_seqs || !h_d_Q || !h_ncols || !h_d_Knew || !h_d_Vnew || !h_n_new || !h_d_O)
+    return CAS_EINVAL;
+  cas::AttnCall calls[16];
+  for (int i = 0; i < n_seqs; ++i) {
+    for (int j = 0; j < i; ++j)
+      if (h_seqs[j] == h_seqs[i]) return CAS_EINVAL;
+    const int rc = attention_call(ctx, kv, layer, h_seqs[i], full, h_d_Q[i], h_ncols[i], n_q_heads, h_d_Knew[i],
+                                  h_d_Vnew[i], h_n_new[i], h_d_O[i], &calls[i]);
+    if (rc != CAS_OK) return rc;
+  }
+  return cas::launch_attention_batch(ctx, kv, calls, n_seqs);
+}
+
 int cas_accept(const int32_t* h_draft, const int32_t* h_target, int k, int32_t* n_accepted, int32_t* h_out) {
   if (k < 0 || !h_target || !n_accepted || !h_out || (k > 0 && !h_draft)) return CAS_EINVAL;
   int n = 0;

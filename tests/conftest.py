@@ -27,3 +27,17 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def record_ratio(name: str, value: float) -> None:
+    """Appends a measured error / tolerance ratio of a GPU parity test to
+    gpurun_out/parity_ratios.jsonl (the figures quoted in the design notes come from there)."""
+    import json
+    out = os.path.join(ROOT, "gpurun_out")
+    try:
+        os.makedirs(out, exist_ok=True)
+        with open(os.path.join(out, "parity_ratios.jsonl"), "a") as f:
+            f.write(json.dumps({"test": name, "err_over_tol": float(value)}) + "\n")
+    except OSError:
+        pass
+    print(f"[parity] {name}: err/tol = {value:.4g}", flush=True)
