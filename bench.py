@@ -40,7 +40,9 @@ def parse():
     ap.add_argument("--context", type=int, default=8192, help="committed KV positions when a step starts")
     ap.add_argument("--batch", type=int, default=1,
                     help="sequences decoded together (1..4, batch * (k + 1) <= 16); 1 is the configuration of the metric")
-    ap.add_argument("--workload", choices=["model", "linear"], default="model")
+    ap.add_argument("--workload", choices=["model", "linear", "probe-linear", "probe-attn"], default="model",
+                    help="model: the metric's workload; linear: the linear layers alone; probe-*: short fixed "
+                         "launch sequences for hardware-counter runs (no JSON line, see workload.py)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.k is None:
@@ -50,35 +52,104 @@ def parse():
     return args
 
 
-def cpu_baseline(keep, t, k):
-    """The oracle as it stands, on one 4096x4096 linear layer of the workload: one draft GEMV
-    and one verify GEMM with k+1 columns from the packed streams."""
+def _cpu_sample(keep, t, k, ctx_len):
+    """Seeded sample of the bench workload for the CPU oracle: 256 output rows of each of the four
+    layer matrices of the 8B shape (encoded with the oracle's own encoder, untimed: encoding is
+    offline) and the cache of one kv head of one layer over the benchmark's context.  Returns the
+    encoded inputs and the algorithmic bytes of one pass over them (draft, verification)."""
     import numpy as np
     import synth
     from oracle import cassandra_oracle as O
-    rows = cols = 4096
-    W = synth.weight_matrix(rows, cols, seed=1)
-    X = synth.activations(cols, k + 1, seed=2)
-    p = O.encode_weight(W, keep, t)
-    bw, sw, lw, pw = O.stream_words(cols, p.K, t)
-    nbytes = rows * 4 * ((bw + sw) * 1 + (bw + sw + lw + pw))
-    t0 = time.perf_counter()
-    reps = 0
-    while True:
+    rows = 256
+    mats = []
+    draft_b = verify_b = 0
+    for i, cols in enumerate((4096, 4096, 4096, 14336)):       # wqkv, wo, wgu read 4096 columns, wd 14336
+        W = synth.weight_matrix(rows, cols, seed=10 + i)
+        p = O.encode_weight(W, keep, t)
+        bw, sw, lw, pw = O.stream_words(cols, p.K, t)
+        draft_b += rows * 4 * (bw + sw)
+        verify_b += rows * 4 * (bw + sw + lw + pw)
+        mats.append((p, synth.activations(cols, k + 1, seed=20 + i)))
+    rng = np.random.Generator(np.random.Philox(31))
+    Kc = rng.standard_normal((ctx_len, 128)).astype(np.float32)
+    Kc[:, [3, 40, 77, 100]] *= 10.0
+    Vc = rng.standard_normal((ctx_len, 128)).astype(np.float32)
+    to16 = lambda a: (a.view(np.uint32) >> 16).astype(np.uint16)
+    pk, pv = O.encode_kv(to16(Kc), keep, t), O.encode_kv(to16(Vc), keep, t)
+    bw, sw, lw, pw = O.stream_words(128, pk.K, t)
+    draft_b += 2 * ctx_len * 4 * (bw + sw)
+    verify_b += 2 * ctx_len * 4 * (bw + sw + lw + pw)
+    q = to16(rng.standard_normal((k + 1, 4, 128)).astype(np.float32))     # 4 query heads share the kv head
+    return {"mats": mats, "pk": pk, "pv": pv, "q": q, "draft_bytes": draft_b, "verify_bytes": verify_b, "k": k}
+
+
+def _cpu_sample_pass(S):
+    """One draft pass and one verification pass of the oracle over the sample."""
+    from oracle import cassandra_oracle as O
+    for p, X in S["mats"]:
         O.gemv_draft(p, X[0])
         O.gemm_verify(p, X)
-        reps += 1
-        el = time.perf_counter() - t0
-        if el > 10.0 or reps >= 8:
-            break
-    try:
-        import threadpoolctl
-        cores = max([i.get("num_threads", 1) for i in threadpoolctl.threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    return {"value": nbytes * reps / el / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{reps} x (draft GEMV + verify GEMM, {k + 1} columns) on one 4096x4096 linear layer, "
-                      f"keep {keep}/1000, t={t}; algorithmic stream bytes / wall time"}
+    for full, ncols in ((False, 1), (True, S["k"] + 1)):
+        dec = O.decode_full if full else O.decode_draft
+        Kd, Vd = O.bf16_to_f64(dec(S["pk"])), O.bf16_to_f64(dec(S["pv"]))
+        for c in range(ncols):
+            for h in range(4):
+                O.attention_one(O.bf16_to_f64(S["q"][c, h]), Kd, Vd)
+
+
+def _cpu_worker(args):
+    """Runs in a process of its own (one BLAS thread): passes over the sample for `seconds`."""
+    keep, t, k, ctx_len, seconds = args
+    import threadpoolctl
+    with threadpoolctl.threadpool_limits(1):
+        S = _cpu_sample(keep, t, k, ctx_len)
+        _cpu_sample_pass(S)                      # warm
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < seconds:
+            _cpu_sample_pass(S)
+            reps += 1
+        return reps, time.perf_counter() - t0, S["draft_bytes"] + S["verify_bytes"]
+
+
+def cpu_baseline(keep, t, k, ctx_len):
+    """The oracle as it stands, timed on the host cores BEFORE the GPU is touched (worker
+    processes are spawned): a bounded sample of the benchmark workload (see _cpu_sample), one
+    draft pass + one verification pass per repetition, (a) in one process with one thread and
+    (b) in one single-threaded process per available core, each on its own copy of the sample
+    (output rows and kv heads are independent, so this is the oracle run row-parallel).  The
+    rate is algorithmic stream bytes per second, the unit of the GPU figure; the time of the
+    benchmark's whole step at that rate is an extrapolation and labelled so.  Also timed in
+    full: the single 4096x4096 linear layer at 25 % kept with 4 extra columns."""
+    import multiprocessing as mp
+    import numpy as np
+    import synth
+    from oracle import cassandra_oracle as O
+    nproc = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    nproc = min(nproc, int(os.environ.get("OMP_NUM_THREADS", nproc)) or nproc)
+    r1, el1, nbytes = _cpu_worker((keep, t, k, ctx_len, 4.0))
+    single = nbytes * r1 / el1 / 1e9
+    ctxm = mp.get_context("spawn")
+    with ctxm.Pool(nproc) as pool:
+        res = pool.map(_cpu_worker, [(keep, t, k, ctx_len, 6.0)] * nproc)
+    allc = sum(nb * r / el for r, el, nb in res) / 1e9
+    # the single-linear-layer workload in full, one thread
+    import threadpoolctl
+    with threadpoolctl.threadpool_limits(1):
+        W = synth.weight_matrix(4096, 4096, seed=1)
+        X = synth.activations(4096, 5, seed=2)
+        p = O.encode_weight(W, 250, 4)
+        t0 = time.perf_counter(); O.gemv_draft(p, X[0]); td = time.perf_counter() - t0
+        t0 = time.perf_counter(); O.gemm_verify(p, X); tv = time.perf_counter() - t0
+    return {"value": allc, "unit": "GB/s", "cores": int(nproc), "kind": "oracle",
+            "nproc": int(nproc), "single_thread_value": single,
+            "sample": f"per repetition one draft pass + one verification pass ({k + 1} columns) over 256 output rows "
+                      f"of each 8B-shaped layer matrix (3 x 256x4096, 256x14336) and the cache of one kv head over "
+                      f"{ctx_len} positions (4 query heads), keep {keep}/1000, t={t}; `value`: {nproc} single-threaded "
+                      f"processes, each on its own copy, {sum(r for r, _, _ in res)} repetitions in "
+                      f"{max(el for _, el, _ in res):.1f} s; `single_thread_value`: one process, {r1} repetitions "
+                      f"in {el1:.1f} s; algorithmic stream bytes / wall time",
+            "single_linear_layer_4096x4096_keep250_k4_one_thread": {"draft_gemv_s": td, "verify_gemm_5col_s": tv}}
 
 
 def main():
@@ -87,12 +158,18 @@ def main():
         print("bench.py measures the one-GPU path only: run with --gpus 1 "
               "(no multi-GPU figure is produced in this build)", file=sys.stderr)
         sys.exit(2)
+    # the CPU oracle first: its worker processes are spawned before this process touches the GPU
+    cpu = None if args.no_cpu_baseline or args.workload.startswith("probe") else \
+        cpu_baseline(args.keep, args.trunc, args.k, args.context)
     import torch
     from paper_2605_26558_amd import binding as B
     from paper_2605_26558_amd import workload
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload.startswith("probe"):
+        workload.run_probe(B, args)
+        return
     wl = workload.build(B, args, dev)
 
     for _ in range(args.warmup):
@@ -120,8 +197,11 @@ def main():
         "pct_of_hbm_peak": 100.0 * wl.bytes_per_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
     }
     out.update(wl.extra(ms_per_step))
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.keep, args.trunc, args.k)
+    if cpu is not None:
+        # time of this benchmark's whole step at the oracle's sampled rate (an extrapolation)
+        cpu["extrapolated_s_per_step_all_cores"] = wl.bytes_per_step / (cpu["value"] * 1e9)
+        cpu["extrapolated_s_per_step_single_thread"] = wl.bytes_per_step / (cpu["single_thread_value"] * 1e9)
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 

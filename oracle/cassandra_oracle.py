@@ -777,6 +777,70 @@ def tune_grid(alpha, keeps, truncs, s_w, s_kv, kv_keep, kv_t, b_bits=BF16_BITS):
     return arg
 
 
+def expected_tokens_per_round(alpha: float, gamma: int) -> float:
+    """Speed model of Sec. 2.2 with a per-token acceptance probability alpha (reading: the
+    acceptance rate is the probability that a drafted token is accepted, independently per
+    position): the i-th draft is accepted iff all of 1..i are, so a round emits
+    1 + alpha + alpha^2 + ... + alpha^gamma tokens on average (the accepted drafts and the
+    target's own next token)."""
+    return sum(float(alpha) ** i for i in range(0, gamma + 1))
+
+
+def speed_model(alpha: float, gamma: int, t_draft: float, t_verify: float, t_plain: float):
+    """Sec. 2.2: a round of gamma draft passes and one verification pass costs
+    gamma * t_draft + t_verify; plain decoding costs t_plain per token.  Returns
+    (tokens per round, tokens per second, speedup over plain decoding)."""
+    n = expected_tokens_per_round(alpha, gamma)
+    rate = n / (gamma * t_draft + t_verify)
+    return n, rate, rate * t_plain
+
+
+def tune_measured(alpha, t_draft, t_verify, gamma: int):
+    """Format search with measured pass times in place of Eq. 2's bit count (Sec. 7.2.2 searches
+    the grid for the best acceptance per cost; here the cost of a format is the measured time of
+    its draft and verification passes): the grid point with the most tokens per second under the
+    speed model of Sec. 2.2, the first one in row-major order among equals.  alpha, t_draft,
+    t_verify: [n_keep][n_trunc]."""
+    best, arg = -1.0, None
+    for i in range(len(alpha)):
+        for j in range(len(alpha[i])):
+            v = expected_tokens_per_round(alpha[i][j], gamma) / (gamma * t_draft[i][j] + t_verify[i][j])
+            if v > best:
+                best, arg = v, (i, j)
+    return arg
+
+
+def token_prob(logits, token: int) -> float:
+    """Probability of `token` under the softmax of one row of logits (p_i(x), q_i(x) of Eq. 1:
+    'the probability of the i-th token obtained from the model's logits')."""
+    z = np.asarray(logits, dtype=np.float64)
+    e = np.exp(z - z.max())
+    return float(e[int(token)] / e.sum())
+
+
+def spec_round_sampling(model: "OracleModel", pending: int, k: int, r):
+    """One round with the acceptance rule of Eq. 1 (Sec. 2.2).  Readings where the paper is
+    silent: the drafted tokens are the draft model's greedy tokens, and the token emitted after the
+    n accepted drafts is the target model's greedy token at that position (Eq. 1 only defines n).
+    r: k uniform numbers.  Returns (n, emitted tokens, p, q) and appends the accepted
+    positions to the model's cache."""
+    s = model.s
+    drafts, cur, q = [], int(pending), []
+    extra = [(np.zeros((0, s.n_kv_heads, s.head_dim), np.uint16),) * 2 for _ in range(s.n_layers)]
+    for _ in range(k):
+        lg, nkv = model.forward([cur], draft=True, extra_kv=extra)
+        extra = [(np.concatenate([e[0], n[0]]), np.concatenate([e[1], n[1]])) for e, n in zip(extra, nkv)]
+        cur = argmax_lowest(lg[0])
+        drafts.append(cur)
+        q.append(token_prob(lg[0], cur))
+    vlogits, vkv = model.forward([int(pending)] + drafts, draft=False)
+    p = [token_prob(vlogits[i], drafts[i]) for i in range(k)]
+    n = accept_sampling(p, q, r)
+    emitted = drafts[:n] + [argmax_lowest(vlogits[n])]
+    model.append_kv(vkv, n + 1)
+    return n, emitted, p, q
+
+
 def prefill(model: OracleModel, prompt):
     """Fill the cache for prompt[:-1] with the target model; prompt[-1] stays pending."""
     if len(prompt) > 1:

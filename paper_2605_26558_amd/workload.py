@@ -222,12 +222,14 @@ class ModelRoundWorkload:
 
     def _chain_buffers(self):
         torch, shape = self.torch, self.shape
-        z = lambda n, c=1: torch.zeros((c, n), dtype=torch.int16, device="cuda")
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(4321)
+        # seeded N(0,1) activations (the residual stream h is updated in place by the chain)
+        z = lambda n, c=1: torch.randn((c, n), device="cuda", generator=gen).to(torch.bfloat16).view(torch.int16)
         nb, nv = self.batch, min(16, self.batch * (self.k + 1))
         return {"h": z(shape.hidden, nb), "ao": z(shape.q_dim, nb), "act": z(shape.ffn, nb),
                 "y": torch.empty((nv, max(shape.vocab, 2 * shape.ffn)), dtype=torch.float32, device="cuda"),
-                "X": {c: torch.randn((nv, c), device="cuda").to(torch.bfloat16).view(torch.int16)
-                      for c in (shape.hidden, shape.q_dim, shape.ffn)}}
+                "X": {c: z(c, nv) for c in (shape.hidden, shape.q_dim, shape.ffn)}}
 
     def _draft_gemv_chain(self, buf):
         """The draft-GEMV launches of one draft pass, back to back, with the same fused
@@ -423,6 +425,86 @@ class ModelRoundWorkload:
                 out["kernels"][name] = {"launches": n, "avg_us": ms / n * 1e3, "GBps": by / (ms * 1e-3) / 1e9,
                                         "frac_of_peak": by / (ms * 1e-3) / 1e9 / 8000.0}
         return out
+
+
+def run_probe(B, args):
+    """Short fixed launch sequences for hardware-counter and kernel-trace runs (`bench.py --workload
+    probe-linear | probe-attn`).  Each starts with three device-to-device copies of 256 MiB, the
+    calibration kernel of known size for the FETCH_SIZE / WRITE_SIZE counters, and prints the
+    algorithmic bytes of every launch that follows so that counter readings can be compared.
+
+    probe-linear: draft GEMV (1 column) and verify GEMM (k+1 columns) on four distinct matrices of
+    each 8B layer shape and one output head, then the unary-coded and shared-exponent draft GEMVs on
+    the 28672 x 4096 matrices.  probe-attn: draft (1 column) and verification (k+1 columns) attention
+    of one layer over a compressed cache of `--context` positions, six distinct layers."""
+    import torch
+    ctx = B.Context(workspace=torch.empty(256 << 20, dtype=torch.uint8, device="cuda"))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    k, keep, t = args.k, args.keep, args.trunc
+    bf = lambda *s: torch.randn(s, device="cuda", generator=gen).to(torch.bfloat16).view(torch.int16)
+    src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()   # 256 MiB
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        dst.copy_(src)
+    print("copy_bytes_read", src.numel() * 4, "copy_bytes_written", src.numel() * 4)
+    if args.workload == "probe-linear":
+        shapes = (("wqkv", 6144, 4096, 4), ("wo", 4096, 4096, 4), ("wgu", 28672, 4096, 4), ("wd", 4096, 14336, 4),
+                  ("head", 128256, 4096, 1))
+        y = torch.empty((k + 1, 128256), device="cuda")
+        for name, rows, cols, n in shapes:
+            mats = [B.cas_encode_weight(ctx, _random_weight(torch, rows, cols, gen), keep, t) for _ in range(n)]
+            x = bf(k + 1, cols)
+            x1 = x[:1].contiguous()
+            for _ in range(3):
+                for m in mats:
+                    B.cas_gemv_draft(ctx, m, x1, y[:1, :rows])
+            for _ in range(3):
+                for m in mats:
+                    B.cas_gemm_verify(ctx, m, x, y[:, :rows])
+            d = mats[0].desc
+            print(f"{name} {rows}x{cols}: gemv_draft_algorithmic_bytes", rows * (d.bw + d.sw) * 4,
+                  "gemm_verify_algorithmic_bytes", rows * (d.bw + d.sw + d.lw + d.pw) * 4, flush=True)
+            if name == "wgu":
+                yu = torch.empty(rows, device="cuda")
+                umats = [B.cas_unary_encode(ctx, m) for m in mats]
+                for _ in range(3):
+                    for u in umats:
+                        B.cas_gemv_draft_unary(ctx, u, x1, yu)
+                xmats = [B.cas_mx_encode(ctx, m) for m in mats]
+                for _ in range(3):
+                    for xm in xmats:
+                        B.cas_gemv_draft_mx(ctx, xm, x1, yu)
+                u, xd = umats[0].desc, xmats[0].desc
+                print("gemv_draft_unary_algorithmic_bytes", rows * (d.bw + u.smw) * 4 + (u.ue_words + rows + 1) * 4)
+                print("gemv_draft_mx_algorithmic_bytes", rows * (d.bw * 4 + d.bw + xd.fw * 4), flush=True)
+                del umats, xmats
+            del mats
+    else:
+        nq, nkv, ctx_len, layers = 32, 8, args.context, 6
+        pages = (ctx_len + 64 + 63) // 64
+        kv = B.KVCache(ctx, layers, nkv, n_pages=pages, max_seqs=1, max_pages_per_seq=pages, keep_permille=keep,
+                       trunc_bits=t)
+        for layer in range(layers):
+            K = torch.randn((ctx_len, nkv, 128), device="cuda", generator=gen)
+            K[:, :, torch.tensor([3, 40, 77, 100])] *= 10.0
+            V = torch.randn((ctx_len, nkv, 128), device="cuda", generator=gen)
+            B.cas_kv_set_len(kv, 0, 0)
+            B.cas_kv_append(ctx, kv, layer, 0, K.to(torch.bfloat16).view(torch.int16).contiguous(),
+                            V.to(torch.bfloat16).view(torch.int16).contiguous())
+        B.cas_kv_set_len(kv, 0, ctx_len)
+        Q, Kn, Vn = bf(k + 1, nq, 128), bf(k + 1, nkv, 128), bf(k + 1, nkv, 128)
+        for _ in range(2):
+            for layer in range(layers):
+                B.cas_attention(ctx, kv, layer, 0, False, Q[:1].contiguous(), Kn[:1].contiguous(), Vn[:1].contiguous())
+        for _ in range(2):
+            for layer in range(layers):
+                B.cas_attention(ctx, kv, layer, 0, True, Q, Kn, Vn)
+        d = kv.desc
+        print("attn_draft_algorithmic_bytes", 2 * nkv * 4 * (4 + d.sw) * ctx_len)
+        print("attn_verify_algorithmic_bytes", 2 * nkv * 4 * (4 + d.sw + d.lw + d.pw) * ctx_len, flush=True)
+    torch.cuda.synchronize()
 
 
 def build(B, args, dev):

@@ -29,6 +29,12 @@ def pytest_collection_modifyitems(config, items):
             it.add_marker(skip)
 
 
+# Logits of a whole pass are held to the one-GEMV bar 2e-3 |W_row| |x| of the output head times this
+# factor (bf16 roundings between the ops can fall differently in fp32 and fp64 and reach the head;
+# the measured worst case over all logits tests is below a tenth of the bar).
+LOGIT_SLACK = 1.0
+
+
 def record_ratio(name: str, value: float) -> None:
     """Appends a measured error / tolerance ratio of a GPU parity test to
     gpurun_out/parity_ratios.jsonl (the figures quoted in the design notes come from there)."""

@@ -9,7 +9,7 @@ import pytest
 
 from oracle import cassandra_oracle as O
 import synth
-from conftest import record_ratio
+from conftest import LOGIT_SLACK, record_ratio
 
 pytestmark = pytest.mark.gpu
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -158,8 +158,6 @@ def test_llama70b_shaped_layer_against_stored_oracle_logits(env):
             top2 = np.sort(ref)[-2:]
             assert top2[1] - top2[0] <= LOGIT_SLACK * tol_v.max(), (c, int(tgt[c]), int(np.argmax(ref)))
 
-
-LOGIT_SLACK = 8.0
 
 
 def test_speculative_rounds_emit_the_oracles_accepted_tokens(env):

@@ -7,6 +7,7 @@ import pytest
 
 from oracle import cassandra_oracle as O
 import synth
+from conftest import LOGIT_SLACK, record_ratio
 
 pytestmark = pytest.mark.gpu
 
@@ -241,9 +242,9 @@ def test_one_8b_shaped_layer_against_oracle_with_4096_cached_positions(env):
         tol = 2e-3 * np.linalg.norm(W, axis=1) * np.linalg.norm(O.bf16_to_f64(om.g_final))
         err = np.abs(gpu - ref)
         # bf16 roundings between the ops of the layer can fall differently in fp32 and fp64 and
-        # reach the head: 8x the one-GEMV tolerance, as for the small model
-        assert (err <= 8 * tol[None, :]).all(), (what, float((err / tol[None, :]).max()))
-        print(what, "max err / tol", float((err / tol[None, :]).max()), flush=True)
+        # reach the head
+        assert (err <= LOGIT_SLACK * tol[None, :]).all(), (what, float((err / tol[None, :]).max()))
+        record_ratio(f"llama8b_layer_{what}_logits", float((err / tol[None, :]).max()))
 
     tokens = synth.token_ids(k + 1, shape.vocab, seed=9)
     tgt = torch.empty(k + 1, dtype=torch.int32, device="cuda")

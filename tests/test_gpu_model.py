@@ -5,6 +5,7 @@ import pytest
 
 from oracle import cassandra_oracle as O
 import synth
+from conftest import LOGIT_SLACK, record_ratio
 
 pytestmark = pytest.mark.gpu
 
@@ -54,13 +55,13 @@ def _logit_tol(om, draft):
 
 def _check_logits(gpu, ref, tol, what):
     err = np.abs(gpu - ref)
-    # errors of earlier layers (bf16 roundings that fall differently) also reach the head: allow 8x
-    assert (err <= 8 * tol[None, :]).all(), (what, float((err / tol[None, :]).max()))
+    # errors of earlier layers (bf16 roundings that fall differently) also reach the head
+    assert (err <= LOGIT_SLACK * tol[None, :]).all(), (what, float((err / tol[None, :]).max()))
     for c in range(ref.shape[0]):
         a, b = int(np.argmax(gpu[c])), int(np.argmax(ref[c]))
         if a != b:
             top2 = np.sort(ref[c])[-2:]
-            assert top2[1] - top2[0] <= 8 * tol.max(), (what, c, a, b, top2)
+            assert top2[1] - top2[0] <= LOGIT_SLACK * tol.max(), (what, c, a, b, top2)
     return float((err / tol[None, :]).max())
 
 
@@ -78,7 +79,7 @@ def test_verify_and_draft_steps_match_oracle(env, keep, t):
     B.cas_verify_step(ctx, model, kv, 0, toks, 5, tgt, logits)
     ref, new_kv = om.forward(prompt, draft=False)
     r = _check_logits(logits.cpu().numpy().astype(np.float64), ref, _logit_tol(om, False), "verify")
-    print("verify logits err/tol", r, flush=True)
+    record_ratio(f"tiny_model_verify_logits_keep{keep}", r)
     assert (tgt.cpu().numpy() == np.argmax(logits.cpu().numpy(), axis=1)).all()
     # commit all six, compare the cache contents with the oracle's K/V
     B.cas_commit(ctx, model, kv, 0, 5)
@@ -100,7 +101,7 @@ def test_verify_and_draft_steps_match_oracle(env, keep, t):
         oref, okv = om.forward([int(cur.item())], draft=True, extra_kv=extra)
         extra = [(np.concatenate([e[0], n[0]]), np.concatenate([e[1], n[1]])) for e, n in zip(extra, okv)]
         r = _check_logits(dl.cpu().numpy().astype(np.float64), oref, _logit_tol(om, True), f"draft{slot}")
-        print("draft logits err/tol", r, flush=True)
+        record_ratio(f"tiny_model_draft{slot}_logits_keep{keep}", r)
         cur = torch.tensor([int(np.argmax(oref[0]))], dtype=torch.int32, device="cuda")   # teacher forcing
 
 
@@ -160,7 +161,7 @@ def test_gpu_stream_against_oracle_teacher_forced(env):
         got = int(tgt.item())
         if got != want:
             top2 = np.sort(ref[0])[-2:]
-            assert top2[1] - top2[0] <= 8 * tol.max(), (step, got, want)
+            assert top2[1] - top2[0] <= LOGIT_SLACK * tol.max(), (step, got, want)
             excused += 1
         pending = want
     print("excused near-ties:", excused, flush=True)
