@@ -40,9 +40,14 @@ def parse():
     ap.add_argument("--context", type=int, default=8192, help="committed KV positions when a step starts")
     ap.add_argument("--batch", type=int, default=1,
                     help="sequences decoded together (1..4, batch * (k + 1) <= 16); 1 is the configuration of the metric")
-    ap.add_argument("--workload", choices=["model", "linear", "probe-linear", "probe-attn"], default="model",
+    ap.add_argument("--workload", choices=["model", "linear", "probe-linear", "probe-attn", "tune"], default="model",
                     help="model: the metric's workload; linear: the linear layers alone; probe-*: short fixed "
-                         "launch sequences for hardware-counter runs (no JSON line, see workload.py)")
+                         "launch sequences for hardware-counter runs (no JSON line, see workload.py); tune: format "
+                         "search on measured draft / verification pass times with user-supplied acceptance rates")
+    ap.add_argument("--alpha", type=float, default=0.8, help="tune: acceptance rate assumed for every grid point")
+    ap.add_argument("--alpha-grid", default=None, help="tune: JSON file with a [n_keep][n_trunc] table of acceptance rates")
+    ap.add_argument("--tune-keeps", default="700,600,500,400", help="tune: kept fractions in 1/1000 (Sec. 7.2.2 grid)")
+    ap.add_argument("--tune-truncs", default="0,1,2,3,4,5", help="tune: truncation bits")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.k is None:
@@ -159,7 +164,7 @@ def main():
               "(no multi-GPU figure is produced in this build)", file=sys.stderr)
         sys.exit(2)
     # the CPU oracle first: its worker processes are spawned before this process touches the GPU
-    cpu = None if args.no_cpu_baseline or args.workload.startswith("probe") else \
+    cpu = None if args.no_cpu_baseline or args.workload.startswith("probe") or args.workload == "tune" else \
         cpu_baseline(args.keep, args.trunc, args.k, args.context)
     import torch
     from paper_2605_26558_amd import binding as B
@@ -169,6 +174,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.workload.startswith("probe"):
         workload.run_probe(B, args)
+        return
+    if args.workload == "tune":
+        workload.run_tune(B, args, dev)
         return
     wl = workload.build(B, args, dev)
 

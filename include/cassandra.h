@@ -467,6 +467,27 @@ int cas_accept(const int32_t* h_draft, const int32_t* h_target, int k, int32_t* 
 int cas_accept_sampling(const double* h_p, const double* h_q, const double* h_r, int gamma,
                         int32_t* n_accepted);
 
+/* Probability of a token under the softmax of a row of logits, as Eq. 1 needs it for the drafted
+ * tokens (p_i(x) from the target model's logits, q_i(x) from the draft model's).  d_logits: float
+ * [n][vocab]; d_tokens: int32 [n]; d_probs: float [n] (0 for a token outside the vocabulary).
+ * fp32 with the row maximum subtracted; reductions in a fixed order.  Enqueues one kernel. */
+int cas_token_probs(cas_ctx* ctx, const float* d_logits, int vocab, int n, const int32_t* d_tokens,
+                    float* d_probs);
+
+/* One whole round with the rejection-sampling acceptance rule (Sec. 2.2, Eq. 1) in place of the
+ * greedy one: k draft passes, one verification pass, p_i and q_i of the k drafted tokens from the
+ * two sets of logits on the device (cas_token_probs), n from Eq. 1 with the caller's uniform
+ * numbers h_r[k] (cas_accept_sampling, ratio in double precision), commit.  Where the paper is
+ * silent: the drafted tokens are the draft model's greedy tokens, and the token emitted after
+ * the n accepted drafts is the target model's greedy token at that position.  d_scratch: device
+ * floats, cas_spec_round_sampling_scratch_floats(vocab, k) of them (the logits of the 2k+1
+ * columns and the 2k probabilities), caller-owned.  h_out: n + 1 tokens; h_p, h_q: NULL or
+ * double [k], the probabilities used.  Synchronises the stream once. */
+size_t cas_spec_round_sampling_scratch_floats(int vocab, int k);
+int cas_spec_round_sampling(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, int32_t pending, int k,
+                            const double* h_r, float* d_scratch, int32_t* h_out, int32_t* n_accepted,
+                            double* h_p, double* h_q);
+
 /* Objective of the format search (Eq. 2): acceptance rate per bit the draft model reads,
  *   J = alpha / (S_w (1 - w_p)(B - w_t) + S_kv (1 - kv_p)(B - kv_t)),
  * with the kept fractions 1 - w_p, 1 - kv_p given in 1/1000.  Host only.  s_w, s_kv: numbers of
@@ -482,6 +503,25 @@ int cas_objective(double alpha, double s_w, int w_keep_permille, int w_trunc_bit
 int cas_tune_grid(const double* h_alpha, int n_keep, const int32_t* h_keep_permille, int n_trunc,
                   const int32_t* h_trunc_bits, double s_w, double s_kv, int kv_keep_permille,
                   int kv_trunc_bits, int b_bits, int32_t* best_keep_index, int32_t* best_trunc_index);
+
+/* Speed model of Sec. 2.2.  A round of gamma draft passes and one verification pass costs
+ * gamma * t_draft + t_verify and emits the accepted drafts plus the target's own next token;
+ * with a per-token acceptance probability alpha (reading: the i-th draft is accepted iff drafts
+ * 1..i all are, independently with probability alpha each) that is 1 + alpha + ... + alpha^gamma
+ * tokens on average.  Plain decoding costs t_plain per token.  Host only; each output may be
+ * NULL.  speedup = tokens_per_s * t_plain.  CAS_EINVAL unless 0 <= alpha <= 1, t_verify > 0. */
+int cas_speed_model(double alpha, int gamma, double t_draft, double t_verify, double t_plain,
+                    double* tokens_per_round, double* tokens_per_s, double* speedup);
+
+/* Format search (Sec. 7.2.2) with MEASURED pass times as the cost of a format in place of Eq. 2's
+ * bit count: h_alpha, h_t_draft, h_t_verify are [n_keep][n_trunc] (the acceptance rate the caller
+ * measured or assumes for every grid point, and the times of one draft pass and one verification
+ * pass of gamma + 1 columns in that format on this machine).  Returns the grid point with the
+ * most tokens per second under cas_speed_model (first in row-major order among equals);
+ * h_tokens_per_s: NULL or [n_keep][n_trunc], the rate of every point.  Host only. */
+int cas_tune_measured(const double* h_alpha, const double* h_t_draft, const double* h_t_verify,
+                      int n_keep, int n_trunc, int gamma, int32_t* best_keep_index,
+                      int32_t* best_trunc_index, double* h_tokens_per_s);
 
 #ifdef __cplusplus
 }

@@ -140,6 +140,16 @@ _SIGNATURES = {
     "cas_tune_grid": (C.c_int, [C.POINTER(C.c_double), C.c_int, C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32),
                                 C.c_double, C.c_double, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32),
                                 C.POINTER(C.c_int32)]),
+    "cas_speed_model": (C.c_int, [C.c_double, C.c_int, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double),
+                                  C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "cas_tune_measured": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int,
+                                    C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_double)]),
+    "cas_token_probs": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
+    "cas_spec_round_sampling_scratch_floats": (C.c_size_t, [C.c_int, C.c_int]),
+    "cas_spec_round_sampling": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int,
+                                          C.POINTER(C.c_double), C.c_void_p, C.POINTER(C.c_int32),
+                                          C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "cas_unary_plan": (C.c_int, [C.c_void_p, C.POINTER(cas_wdesc), C.c_void_p, C.POINTER(cas_udesc)]),
     "cas_unary_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p]),
     "cas_unary_decode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
@@ -277,6 +287,30 @@ def cas_tune_grid(alpha, keep_permille, trunc_bits, s_w, s_kv, kv_keep_permille,
     if rc != CAS_OK:
         raise CasError(rc, "cas_tune_grid")
     return bi.value, bj.value
+
+
+def cas_speed_model(alpha, gamma, t_draft, t_verify, t_plain=0.0):
+    """Returns (tokens per round, tokens per second, speedup over plain decoding)."""
+    n, r, sp = C.c_double(), C.c_double(), C.c_double()
+    rc = _lib().cas_speed_model(float(alpha), int(gamma), float(t_draft), float(t_verify), float(t_plain),
+                                C.byref(n), C.byref(r), C.byref(sp))
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_speed_model")
+    return n.value, r.value, sp.value
+
+
+def cas_tune_measured(alpha, t_draft, t_verify, gamma):
+    """alpha, t_draft, t_verify: [n_keep][n_trunc] nested sequences; returns
+    ((keep index, trunc index), tokens per second of every grid point as nested lists)."""
+    nk, nt = len(alpha), len(alpha[0])
+    flat = lambda a: (C.c_double * (nk * nt))(*[float(a[i][j]) for i in range(nk) for j in range(nt)])
+    rates = (C.c_double * (nk * nt))()
+    bi, bj = C.c_int32(), C.c_int32()
+    rc = _lib().cas_tune_measured(flat(alpha), flat(t_draft), flat(t_verify), nk, nt, int(gamma), C.byref(bi),
+                                  C.byref(bj), rates)
+    if rc != CAS_OK:
+        raise CasError(rc, "cas_tune_measured")
+    return (bi.value, bj.value), [[rates[i * nt + j] for j in range(nt)] for i in range(nk)]
 
 
 class UnaryWeight:
@@ -626,6 +660,35 @@ def cas_spec_round(ctx, model: Model, kv: KVCache, seq, pending, k):
     n = C.c_int32()
     ctx._check(_lib().cas_spec_round(ctx.h, model.h, kv.h, seq, int(pending), k, out, C.byref(n)), "cas_spec_round")
     return n.value, [out[i] for i in range(n.value + 1)]
+
+
+def cas_token_probs(ctx, logits, tokens, out=None):
+    """logits: float32 [n][vocab]; tokens: int32 [n]; returns float32 [n] softmax probabilities."""
+    torch = ctx._torch
+    assert logits.is_contiguous() and logits.dtype == torch.float32 and tokens.dtype == torch.int32
+    n, vocab = logits.shape
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=logits.device)
+    ctx._check(_lib().cas_token_probs(ctx.h, logits.data_ptr(), vocab, n, tokens.data_ptr(), out.data_ptr()),
+               "cas_token_probs")
+    return out
+
+
+def cas_spec_round_sampling(ctx, model: Model, kv: KVCache, seq, pending, k, r, scratch=None):
+    """One round with the acceptance rule of Eq. 1; r: k uniform numbers.  Returns
+    (n_accepted, emitted tokens, p, q)."""
+    torch = ctx._torch
+    need = _lib().cas_spec_round_sampling_scratch_floats(model.shape.vocab, k)
+    if scratch is None:
+        scratch = torch.empty(max(need, 1), dtype=torch.float32, device="cuda")
+    assert scratch.numel() >= need and scratch.dtype == torch.float32
+    out = (C.c_int32 * (k + 1))()
+    n = C.c_int32()
+    p, q = (C.c_double * max(k, 1))(), (C.c_double * max(k, 1))()
+    rr = (C.c_double * max(k, 1))(*[float(x) for x in r])
+    ctx._check(_lib().cas_spec_round_sampling(ctx.h, model.h, kv.h, seq, int(pending), k, rr, scratch.data_ptr(), out,
+                                              C.byref(n), p, q), "cas_spec_round_sampling")
+    return n.value, [out[i] for i in range(n.value + 1)], [p[i] for i in range(k)], [q[i] for i in range(k)]
 
 
 def cas_spec_round_multi(ctx, model: Model, kv: KVCache, seqs, pending, k):

@@ -354,4 +354,47 @@ int cas_tune_grid(const double* h_alpha, int n_keep, const int32_t* h_keep_permi
   return CAS_OK;
 }
 
+static double expected_tokens(double alpha, int gamma) {
+  double n = 0.0, a = 1.0;  // 1 + alpha + ... + alpha^gamma
+  for (int i = 0; i <= gamma; ++i) {
+    n += a;
+    a *= alpha;
+  }
+  return n;
+}
+
+int cas_speed_model(double alpha, int gamma, double t_draft, double t_verify, double t_plain, double* tokens_per_round,
+                    double* tokens_per_s, double* speedup) {
+  if (!(alpha >= 0.0) || !(alpha <= 1.0) || gamma < 0 || !(t_draft >= 0.0) || !(t_verify > 0.0) || !(t_plain >= 0.0))
+    return CAS_EINVAL;
+  const double n = expected_tokens(alpha, gamma);
+  const double rate = n / ((double)gamma * t_draft + t_verify);
+  if (tokens_per_round) *tokens_per_round = n;
+  if (tokens_per_s) *tokens_per_s = rate;
+  if (speedup) *speedup = rate * t_plain;
+  return CAS_OK;
+}
+
+int cas_tune_measured(const double* h_alpha, const double* h_t_draft, const double* h_t_verify, int n_keep, int n_trunc,
+                      int gamma, int32_t* best_keep_index, int32_t* best_trunc_index, double* h_tokens_per_s) {
+  if (!h_alpha || !h_t_draft || !h_t_verify || !best_keep_index || !best_trunc_index || n_keep < 1 || n_trunc < 1)
+    return CAS_EINVAL;
+  double best = -1.0;
+  for (int i = 0; i < n_keep; ++i) {
+    for (int j = 0; j < n_trunc; ++j) {
+      const size_t e = (size_t)i * n_trunc + j;
+      double rate;
+      const int rc = cas_speed_model(h_alpha[e], gamma, h_t_draft[e], h_t_verify[e], 0.0, nullptr, &rate, nullptr);
+      if (rc != CAS_OK) return rc;
+      if (h_tokens_per_s) h_tokens_per_s[e] = rate;
+      if (rate > best) {
+        best = rate;
+        *best_keep_index = i;
+        *best_trunc_index = j;
+      }
+    }
+  }
+  return CAS_OK;
+}
+
 }  // extern "C"

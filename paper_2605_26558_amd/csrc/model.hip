@@ -138,6 +138,38 @@ __global__ __launch_bounds__(64) void argmax_final_kernel(const float* __restric
   if (threadIdx.x == 0) out[c] = idx == 0x7FFFFFFF ? 0 : idx;
 }
 
+// Probability of one token under the softmax of a row of logits (p_i(x), q_i(x) of Eq. 1): one
+// workgroup per row; maximum, then sum of exponentials, both reduced in a fixed order.
+constexpr int kProbThreads = 1024;
+__global__ __launch_bounds__(kProbThreads) void token_prob_kernel(const float* __restrict__ logits, int vocab,
+                                                                  const int32_t* __restrict__ tokens,
+                                                                  float* __restrict__ probs) {
+  __shared__ float red[kProbThreads / 64];
+  const float* x = logits + (size_t)blockIdx.x * vocab;
+  const int tid = threadIdx.x;
+  float mx = -INFINITY;
+  for (int i = tid; i < vocab; i += kProbThreads) mx = fmaxf(mx, x[i]);
+  mx = wave_max(mx);
+  if ((tid & 63) == 0) red[tid >> 6] = mx;
+  __syncthreads();
+  mx = red[0];
+#pragma unroll
+  for (int w = 1; w < kProbThreads / 64; ++w) mx = fmaxf(mx, red[w]);
+  __syncthreads();
+  float sum = 0.f;
+  for (int i = tid; i < vocab; i += kProbThreads) sum += expf(x[i] - mx);
+  sum = wave_sum(sum);
+  if ((tid & 63) == 0) red[tid >> 6] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < kProbThreads / 64; ++w) t += red[w];
+    const int tok = tokens[blockIdx.x];
+    probs[blockIdx.x] = (tok >= 0 && tok < vocab) ? expf(x[tok] - mx) / t : 0.f;
+  }
+}
+
 // tokens [steps][n_seqs] -> [n_seqs][steps]
 __global__ void transpose_tokens_kernel(const int32_t* __restrict__ in, int32_t* __restrict__ out, int steps, int n_seqs) {
   const int i = threadIdx.x;
@@ -470,6 +502,64 @@ int cas_spec_round_multi(cas_ctx* ctx, cas_model* m, cas_kv* kv, int n_seqs, con
     if (rc != CAS_OK) return rc;
   }
   return CAS_OK;
+}
+
+int cas_token_probs(cas_ctx* ctx, const float* d_logits, int vocab, int n, const int32_t* d_tokens, float* d_probs) {
+  if (!ctx || n < 0 || vocab < 1 || (n > 0 && (!d_logits || !d_tokens || !d_probs))) return CAS_EINVAL;
+  if (n == 0) return CAS_OK;
+  hipLaunchKernelGGL(cas::token_prob_kernel, dim3(n), dim3(cas::kProbThreads), 0, ctx->stream, d_logits, vocab, d_tokens,
+                     d_probs);
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
+}
+
+size_t cas_spec_round_sampling_scratch_floats(int vocab, int k) {
+  return (vocab < 1 || k < 0) ? 0 : (size_t)(2 * k + 1) * (size_t)vocab + 2 * (size_t)k;
+}
+
+int cas_spec_round_sampling(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int32_t pending, int k, const double* h_r,
+                            float* d_scratch, int32_t* h_out, int32_t* n_accepted, double* h_p, double* h_q) {
+  if (check_step(ctx, m, kv, seq) != CAS_OK || !h_out || !n_accepted || k < 0 || k + 1 > m->cfg.max_cols || k > 16)
+    return CAS_EINVAL;
+  if (k > 0 && (!h_r || !d_scratch)) return CAS_EINVAL;
+  const size_t vocab = (size_t)m->cfg.vocab;
+  float* dlog = d_scratch;                     // [k][vocab] logits of the draft passes
+  float* vlog = d_scratch + (size_t)k * vocab; // [k+1][vocab] logits of the verification pass
+  float* dq = vlog + (size_t)(k + 1) * vocab;  // [k] draft probabilities, then [k] target probabilities
+  float* dp = dq + k;
+  CAS_HIP(ctx, hipMemcpyAsync(m->tok, &pending, sizeof(int32_t), hipMemcpyHostToDevice, ctx->stream));
+  for (int i = 0; i < k; ++i) {
+    const cas::ColGroup g{seq, 1, i};
+    int rc = cas::forward(ctx, m, kv, &g, 1, m->tok + i, false, m->tok + i + 1, dlog + (size_t)i * vocab);
+    if (rc != CAS_OK) return rc;
+  }
+  const cas::ColGroup gv{seq, k + 1, 0};
+  int rc = cas::forward(ctx, m, kv, &gv, 1, m->tok, true, m->tgt, k > 0 ? vlog : nullptr);
+  if (rc != CAS_OK) return rc;
+  // q_i: draft pass i's softmax at the token it drafted; p_i: the target's softmax after the
+  // same prefix (verification column i - 1) at that token
+  rc = cas_token_probs(ctx, dlog, (int)vocab, k, m->tok + 1, dq);
+  if (rc != CAS_OK) return rc;
+  rc = cas_token_probs(ctx, vlog, (int)vocab, k, m->tok + 1, dp);
+  if (rc != CAS_OK) return rc;
+  int32_t h_tok[17], h_tgt[17];
+  float h_pq[32];
+  CAS_HIP(ctx, hipMemcpyAsync(h_tok, m->tok, sizeof(int32_t) * (k + 1), hipMemcpyDeviceToHost, ctx->stream));
+  CAS_HIP(ctx, hipMemcpyAsync(h_tgt, m->tgt, sizeof(int32_t) * (k + 1), hipMemcpyDeviceToHost, ctx->stream));
+  if (k > 0) CAS_HIP(ctx, hipMemcpyAsync(h_pq, dq, sizeof(float) * 2 * k, hipMemcpyDeviceToHost, ctx->stream));
+  CAS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  double p[16], q[16];
+  for (int i = 0; i < k; ++i) {
+    q[i] = (double)h_pq[i];
+    p[i] = (double)h_pq[k + i];
+    if (h_q) h_q[i] = q[i];
+    if (h_p) h_p[i] = p[i];
+  }
+  rc = cas_accept_sampling(p, q, h_r, k, n_accepted);
+  if (rc != CAS_OK) return rc;
+  for (int i = 0; i < *n_accepted; ++i) h_out[i] = h_tok[i + 1];
+  h_out[*n_accepted] = h_tgt[*n_accepted];
+  return cas_commit(ctx, m, kv, seq, *n_accepted);
 }
 
 int cas_prefill(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_tokens, int n) {

@@ -296,7 +296,7 @@ class ModelRoundWorkload:
                 "traffic_source": "profiles/pmc_gemv_draft_gemm_verify_28672x4096.md (counter ratio applied "
                                   "to this run's bytes per launch)"}
 
-    def _time_passes(self):
+    def _time_passes(self, reps=3):
         """Wall time of one draft pass, one verification pass (k+1 columns) and one plain decode
         step (verification with a single column) of the whole model, by HIP events."""
         torch, B, ctx = self.torch, self.B, self.ctx
@@ -305,7 +305,7 @@ class ModelRoundWorkload:
         tok = torch.ones(nb * (k + 1), dtype=torch.int32, device="cuda")
         out = torch.empty(nb * (k + 1), dtype=torch.int32, device="cuda")
 
-        def timed(fn, reps=3):
+        def timed(fn, reps=reps):
             fn()
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -505,6 +505,72 @@ def run_probe(B, args):
         print("attn_draft_algorithmic_bytes", 2 * nkv * 4 * (4 + d.sw) * ctx_len)
         print("attn_verify_algorithmic_bytes", 2 * nkv * 4 * (4 + d.sw + d.lw + d.pw) * ctx_len, flush=True)
     torch.cuda.synchronize()
+
+
+def measure_format_grid(B, args, dev, keeps, truncs, layer_counts=(2, 8), reps=6):
+    """Measured cost of every format of a grid (Sec. 7.2.2 searches such a grid; its Eq. 2 prices a
+    format by the bits the draft reads, this prices it by time on this machine): for every
+    (keep_permille, trunc_bits) pair, weights and cache of a model of the benchmark's shape are
+    encoded with layer_counts[0] and layer_counts[1] decoder layers (plus embedding and output
+    head), one draft pass, one verification pass of k + 1 columns and one plain decode step are
+    timed by HIP events at the benchmark's context, and the times are extended linearly in the
+    number of layers to args.layers.  Returns {"t_draft": [[s]], "t_verify": [[s]], "t_plain": [[s]]}."""
+    import copy
+    import torch
+    full = args.layers
+    l0, l1 = layer_counts
+    out = {"t_draft": [], "t_verify": [], "t_plain": []}
+    for kp in keeps:
+        rows = {n: [] for n in out}
+        for t in truncs:
+            times = []
+            for nl in (l0, l1):
+                a = copy.copy(args)
+                a.keep, a.trunc, a.layers = kp, t, nl
+                wl = ModelRoundWorkload(B, a, dev)
+                times.append(wl._time_passes(reps))      # ms: draft, verify, plain
+                del wl
+                torch.cuda.empty_cache()
+            for i, n in enumerate(("t_draft", "t_verify", "t_plain")):
+                per_layer = (times[1][i] - times[0][i]) / (l1 - l0)
+                rows[n].append((times[0][i] + per_layer * (full - l0)) * 1e-3)
+        for n in out:
+            out[n].append(rows[n])
+    return out
+
+
+def run_tune(B, args, dev):
+    """`bench.py --workload tune`: the format search driven by measured pass times.  The acceptance
+    rate of every grid point is the user's (one number for all points with --alpha, or a JSON file
+    with a [n_keep][n_trunc] table with --alpha-grid): it needs a trained model and a development
+    set, which this build does not have.  Prints one JSON object: the measured times, tokens/s of
+    every point under the speed model, Eq. 2's J for comparison and the two picks."""
+    import json
+    keeps = [int(x) for x in args.tune_keeps.split(",")]
+    truncs = [int(x) for x in args.tune_truncs.split(",")]
+    if args.alpha_grid:
+        alpha = json.load(open(args.alpha_grid))
+    else:
+        alpha = [[args.alpha for _ in truncs] for _ in keeps]
+    m = measure_format_grid(B, args, dev, keeps, truncs)
+    best, rates = B.cas_tune_measured(alpha, m["t_draft"], m["t_verify"], args.k)
+    if args.model == "70b":
+        hid, nl, nq, nkv, ffn = 8192, args.layers, 64, 8, 28672
+    else:
+        hid, nl, nq, nkv, ffn = 4096, args.layers, 32, 8, 14336
+    shape_w = nl * ((nq + 2 * nkv) * 128 * hid + hid * nq * 128 + 2 * ffn * hid + hid * ffn) + 128256 * hid
+    s_kv = 2.0 * nl * nkv * 128 * args.context
+    j = [[B.cas_objective(alpha[i][jj], float(shape_w), keeps[i], truncs[jj], s_kv, keeps[i], truncs[jj])
+          for jj in range(len(truncs))] for i in range(len(keeps))]
+    bj = B.cas_tune_grid(alpha, keeps, truncs, float(shape_w), s_kv, args.keep, args.trunc)
+    speedup = [[B.cas_speed_model(alpha[i][jj], args.k, m["t_draft"][i][jj], m["t_verify"][i][jj],
+                                  m["t_plain"][i][jj])[2] for jj in range(len(truncs))] for i in range(len(keeps))]
+    print(json.dumps({"workload": "format search on measured pass times", "k": args.k, "context": args.context,
+                      "keep_permille": keeps, "trunc_bits": truncs, "alpha": alpha, "alpha_source": "user-supplied",
+                      "t_draft_s": m["t_draft"], "t_verify_s": m["t_verify"], "t_plain_s": m["t_plain"],
+                      "tokens_per_s": rates, "speedup_over_plain_decode_from_the_same_format": speedup,
+                      "best_by_measured_time": {"keep_permille": keeps[best[0]], "trunc_bits": truncs[best[1]]},
+                      "eq2_J": j, "best_by_eq2_bits": {"keep_permille": keeps[bj[0]], "trunc_bits": truncs[bj[1]]}}))
 
 
 def build(B, args, dev):

@@ -102,3 +102,30 @@ def test_header_is_plain_c_and_host_calls_work_from_c(tmp_path):
     r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "abi host calls ok" in r.stdout
+
+
+def test_speed_model_and_measured_format_search_against_oracle():
+    """cas_speed_model / cas_tune_measured (host only) against the oracle on random grids, and
+    the error paths."""
+    import numpy as np
+    import pytest
+    from oracle import cassandra_oracle as O
+    from paper_2605_26558_amd import binding as B
+    rng = np.random.Generator(np.random.Philox(11))
+    for _ in range(50):
+        a, g = float(rng.random()), int(rng.integers(0, 9))
+        td, tv, tp = (float(x) for x in rng.random(3) + 0.1)
+        got, ref = B.cas_speed_model(a, g, td, tv, tp), O.speed_model(a, g, td, tv, tp)
+        assert max(abs(x - y) for x, y in zip(got, ref)) < 1e-12
+    assert B.cas_speed_model(1.0, 4, 1.0, 2.0, 2.0)[0] == 5.0
+    for _ in range(20):
+        nk, nt, g = int(rng.integers(1, 5)), int(rng.integers(1, 7)), int(rng.integers(1, 8))
+        al, td, tv = rng.random((nk, nt)), rng.random((nk, nt)) + 0.1, rng.random((nk, nt)) + 0.5
+        best, rates = B.cas_tune_measured(al.tolist(), td.tolist(), tv.tolist(), g)
+        assert best == O.tune_measured(al, td, tv, g)
+        want = [[O.speed_model(al[i][j], g, td[i][j], tv[i][j], 0.0)[1] for j in range(nt)] for i in range(nk)]
+        assert np.abs(np.array(rates) - np.array(want)).max() < 1e-12
+    with pytest.raises(B.CasError):
+        B.cas_speed_model(1.5, 4, 1.0, 2.0, 2.0)
+    with pytest.raises(B.CasError):
+        B.cas_speed_model(0.5, 4, 1.0, 0.0, 2.0)

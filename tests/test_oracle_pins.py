@@ -244,3 +244,109 @@ def test_draft_forward_equals_library_decoder_on_the_zero_padded_weights_and_cac
     pv = [torch.cat([a, b], dim=0) for a, b in zip(past_v, vs)]
     ref, _, _ = _library_decoder(shape, wd, tab, [11], pk, pv)
     np.testing.assert_allclose(logits, ref, rtol=0, atol=1e-9 * scale)
+
+
+# ---- speed model of Sec. 2.2, the format search on measured times, softmax probabilities of Eq. 1
+def test_expected_tokens_per_round_closed_forms_and_enumeration():
+    import itertools
+    # closed form of the geometric series, and the two ends
+    for gamma in range(0, 9):
+        assert O.expected_tokens_per_round(0.0, gamma) == 1.0
+        assert O.expected_tokens_per_round(1.0, gamma) == gamma + 1
+        for a in (0.1, 0.5, 0.8, 0.97):
+            assert abs(O.expected_tokens_per_round(a, gamma) - (1 - a ** (gamma + 1)) / (1 - a)) < 1e-12
+    assert abs(O.expected_tokens_per_round(0.5, 3) - 1.875) < 1e-15          # 1 + 1/2 + 1/4 + 1/8
+    # enumeration: every accept/reject pattern of gamma independent drafts, weighted by its
+    # probability, emits (length of the leading run of accepts) + 1 tokens
+    for gamma in (1, 2, 3, 5):
+        for a in (0.3, 0.8):
+            tot = 0.0
+            for pat in itertools.product([0, 1], repeat=gamma):
+                pr = 1.0
+                for b in pat:
+                    pr *= a if b else (1 - a)
+                run = 0
+                while run < gamma and pat[run]:
+                    run += 1
+                tot += pr * (run + 1)
+            assert abs(tot - O.expected_tokens_per_round(a, gamma)) < 1e-12
+
+
+def test_speed_model_hand_worked():
+    # all drafts accepted: gamma + 1 tokens in gamma * t_draft + t_verify (the paper's example)
+    n, rate, sp = O.speed_model(1.0, 4, 1.0, 2.0, 2.0)
+    assert (n, rate) == (5.0, 5.0 / 6.0) and abs(sp - 10.0 / 6.0) < 1e-15
+    # nothing accepted: one token per round, slower than plain decoding by the drafting time
+    n, rate, sp = O.speed_model(0.0, 4, 1.0, 2.0, 2.0)
+    assert (n, rate) == (1.0, 1.0 / 6.0) and abs(sp - 2.0 / 6.0) < 1e-15
+    # no drafting at all is plain decoding when the verification of one column costs t_plain
+    assert O.speed_model(0.7, 0, 1.0, 2.0, 2.0) == (1.0, 0.5, 1.0)
+    # swapping the two times must change the answer (gamma multiplies the draft time only)
+    assert abs(O.speed_model(0.5, 3, 1.0, 4.0, 1.0)[1] - 1.875 / 7.0) < 1e-15
+    assert abs(O.speed_model(0.5, 3, 4.0, 1.0, 1.0)[1] - 1.875 / 13.0) < 1e-15
+
+
+def test_tune_measured_hand_worked():
+    # equal acceptance: the fastest format wins; equal times: the best accepted one wins
+    al = [[0.8, 0.8], [0.8, 0.8]]
+    td = [[2.0, 1.5], [1.0, 1.2]]
+    tv = [[3.0, 3.0], [3.0, 3.0]]
+    assert O.tune_measured(al, td, tv, 4) == (1, 0)
+    assert O.tune_measured([[0.5, 0.9], [0.7, 0.6]], [[1.0, 1.0], [1.0, 1.0]], tv, 4) == (0, 1)
+    # a trade worked by hand, gamma = 2: (alpha .9, t_d 2, t_v 4): (1 + .9 + .81) / 8 = 0.33875;
+    # (alpha .6, t_d 1, t_v 4): (1 + .6 + .36) / 6 = 0.32667 -> the first; with t_d = 0.9 for the second:
+    # 1.96 / 5.8 = 0.33793 -> still the first; with t_d = 0.8: 1.96 / 5.6 = 0.35 -> the second
+    assert O.tune_measured([[0.9, 0.6]], [[2.0, 1.0]], [[4.0, 4.0]], 2) == (0, 0)
+    assert O.tune_measured([[0.9, 0.6]], [[2.0, 0.9]], [[4.0, 4.0]], 2) == (0, 0)
+    assert O.tune_measured([[0.9, 0.6]], [[2.0, 0.8]], [[4.0, 4.0]], 2) == (0, 1)
+    # equals: first in row-major order
+    assert O.tune_measured([[0.5, 0.5], [0.5, 0.5]], [[1.0, 1.0], [1.0, 1.0]], [[1.0, 1.0], [1.0, 1.0]], 3) == (0, 0)
+
+
+def test_token_prob_closed_forms():
+    # uniform logits: 1 / V; two logits: the logistic function; shift invariance; sums to one
+    assert abs(O.token_prob(np.zeros(10), 3) - 0.1) < 1e-15
+    assert abs(O.token_prob(np.full(7, 123.0), 0) - 1.0 / 7.0) < 1e-15
+    for d in (-3.0, 0.0, 0.5, 20.0):
+        assert abs(O.token_prob([0.0, d], 1) - 1.0 / (1.0 + math.exp(-d))) < 1e-15
+    z = np.array([0.3, -1.2, 2.5, 0.0, 700.0])           # exp(700) overflows unless the maximum is subtracted
+    assert abs(O.token_prob(z, 4) - 1.0) < 1e-12 and O.token_prob(z, 0) < 1e-300
+    z = np.array([0.3, -1.2, 2.5, 0.0])
+    assert abs(sum(O.token_prob(z, i) for i in range(4)) - 1.0) < 1e-15
+    assert abs(O.token_prob(z + 11.0, 2) - O.token_prob(z, 2)) < 1e-15
+    # hand-worked: logits ln 1, ln 2, ln 5 -> 1/8, 2/8, 5/8
+    z = np.log(np.array([1.0, 2.0, 5.0]))
+    assert [round(O.token_prob(z, i), 12) for i in range(3)] == [0.125, 0.25, 0.625]
+    # against the library routine
+    import torch
+    z = np.random.Generator(np.random.Philox(3)).standard_normal(1000) * 4
+    ref = torch.softmax(torch.from_numpy(z), dim=0).numpy()
+    assert max(abs(O.token_prob(z, i) - ref[i]) for i in (0, 17, 999)) < 1e-15
+
+
+def test_sampling_round_against_its_parts():
+    """The sampling round is the draft passes, the verification pass, token_prob and Eq. 1 put
+    together: with r = 0 everything is accepted (0 > p/q never holds), with r just below 1 a draft
+    is rejected exactly where the target gives it less probability than the draft model, and the
+    emitted tokens are the greedy round's whenever n agrees."""
+    import synth
+    shape = synth.TINY
+    weights = synth.model_weights(shape, seed=1)
+    tab = synth.rope_table(64, shape.head_dim, shape.rope_theta)
+    prompt = synth.token_ids(5, shape.vocab, seed=5)
+    k = 3
+
+    def fresh():
+        om = O.OracleModel(shape, weights, tab, w_keep=600, w_t=4, kv_keep=600, kv_t=4)
+        return om, O.prefill(om, prompt)
+
+    om, pending = fresh()
+    n, emitted, p, q = O.spec_round_sampling(om, pending, k, [0.0] * k)
+    assert n == k and len(emitted) == k + 1 and om.cache_len() == len(prompt) - 1 + k + 1
+    assert all(0.0 < x <= 1.0 for x in p + q)
+    om2, pending2 = fresh()
+    r = [1.0 - 1e-12] * k
+    n2, emitted2, p2, q2 = O.spec_round_sampling(om2, pending2, k, r)
+    assert p2 == p and q2 == q
+    want = next((i for i in range(k) if p[i] < q[i] * r[i]), k)
+    assert n2 == want and emitted2[:n2] == emitted[:n2] and om2.cache_len() == len(prompt) - 1 + n2 + 1
