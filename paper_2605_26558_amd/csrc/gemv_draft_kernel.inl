@@ -42,6 +42,9 @@ struct Cursor {  // walks the (row, chunk) items of one wave in order
   }
 };
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kRawBufferFlags = 0x00020000;  // word 3 of a raw (unstructured, 32-bit data) buffer descriptor
+
 constexpr int kGemvThreads = 1024;  // 16 waves share one staged copy of x
 constexpr int kGemvWaves = kGemvThreads / 64;
 
@@ -97,9 +100,13 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
   const int row_first = pair ? 2 * gw : gw;
   const bool idle = row_first >= a.rows;  // still helps staging x
 
+  // bitmap words come through a buffer descriptor of the row's words: a word index past the row's
+  // end, or a row past the matrix (no records), reads as 0 without a branch
   auto load_bm = [&](const Cursor& c) -> uint32_t {
-    int wi = c.chunk * 64 + lane;
-    return (c.row < a.rows && wi < a.bw) ? a.bitmap[(size_t)c.row * a.bw + wi] : 0u;
+    const int row = c.row < a.rows ? c.row : 0;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(a.bitmap + (size_t)row * a.bw), 0, c.row < a.rows ? a.bw * 4 : 0, kRawBufferFlags);
+    return __builtin_amdgcn_raw_buffer_load_b32(rs, (c.chunk * 64 + lane) * 4, 0, 0);
   };
   uint32_t rowprefix = 0;  // kept values of the row before the chunk being issued
   auto issue = [&](const Cursor& c, uint32_t m, Window<FW>& w) {
@@ -109,12 +116,23 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_draft_kernel(GemvArgs a) {
     int total = __builtin_amdgcn_readlane(incl, 63);
     uint32_t p = rowprefix + (uint32_t)(incl - cnt);
     rowprefix = (c.chunk == nchunk - 1) ? 0u : rowprefix + (uint32_t)total;
-    uint32_t bit = p * FW;
+    uint32_t bit = __umul24(p, FW);  // p < 2^20: one full-rate multiply
     w.sh = bit & 31u;
     int row = c.row < a.rows ? c.row : row_first;  // past the end: any valid row, its bitmap word is 0
-    const uint32_t* src = a.spec + (size_t)row * a.sw + (bit >> 5);
+    // The window is read through a buffer descriptor of the row's own part of the stream: words past
+    // the row's end read as 0 (range check per word), so a lane that has run out of kept values
+    // forms its leftover products from fields of this row or from zeros, never from misaligned bits
+    // of the next row (which could look like Inf or NaN and turn 0 * f into NaN).
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(a.spec + (size_t)row * a.sw), 0, a.sw * 4, kRawBufferFlags);
+    const int voff = (int)(bit >> 5) * 4;
 #pragma unroll
-    for (int j = 0; j <= FW; ++j) w.d[j] = src[j];
+    for (int j = 0; j + 4 <= FW + 1; j += 4) {
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 4 * j, 0, 0);
+      w.d[j] = v.x; w.d[j + 1] = v.y; w.d[j + 2] = v.z; w.d[j + 3] = v.w;
+    }
+#pragma unroll
+    for (int j = (FW + 1) & ~3; j <= FW; ++j) w.d[j] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff + 4 * j, 0, 0);
     if constexpr (MX) {
       const int wi = c.chunk * 64 + lane;
       w.e = wi < a.bw ? a.sexp[(size_t)row * a.ew + wi] : 0u;

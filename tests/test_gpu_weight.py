@@ -297,3 +297,28 @@ def test_dense_bf16_baseline_rejects_unaligned_rows(env):
     assert e.value.code == B.CAS_ENOTSUP
     assert B.cas_gemv_bf16(ctx, torch.empty((0, 64), dtype=torch.int16, device="cuda"),
                            torch.zeros(64, dtype=torch.int16, device="cuda")).shape == (0,)
+
+
+@pytest.mark.parametrize("cols,keep,t", [(96, 600, 4), (160, 250, 3), (2112, 600, 4), (72, 500, 1)])
+def test_draft_gemv_rows_do_not_see_their_neighbours(env, cols, keep, t):
+    """A lane that has walked all of its kept values keeps forming products with the zero entry of x;
+    the weight bits it pairs with must come from its own row (or be zero).  Rows whose field stream
+    does not end on a word boundary (K (16 - t) not a multiple of 32), followed by rows full of
+    Inf / NaN / large values: the finite rows must give the oracle's finite result."""
+    torch, B, ctx = env
+    rows = 48
+    K = O.kept_count(cols, keep)
+    assert (K * (16 - t)) % 32 != 0
+    W = synth.weight_matrix(rows, cols, seed=31)
+    W[1::3] = 0x7F80                       # +Inf rows
+    W[2::3] = 0x7FC1                       # NaN rows
+    W[2::3, ::2] = 0xFF7F                  # ... mixed with the largest finite magnitude, negative
+    X = synth.activations(cols, 1, seed=32)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t)
+    y = B.cas_gemv_draft(ctx, ew, _dev(torch, X)).cpu().numpy()[0]
+    ref = O.gemv_draft(O.encode_weight(W, keep, t), X[0])
+    good = np.arange(0, rows, 3)
+    assert np.isfinite(ref[good]).all() and np.isfinite(y[good]).all()
+    wn = np.linalg.norm(O.bf16_to_f64(W[good]), axis=1) * np.linalg.norm(O.bf16_to_f64(X[0]))
+    assert (np.abs(y[good] - ref[good]) <= 2e-5 * wn).all()
+    assert not np.isfinite(y[1::3]).any() and np.isnan(y[2::3]).all()
