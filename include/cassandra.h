@@ -292,7 +292,10 @@ int cas_kv_set_len(cas_kv* kv, int seq, int32_t len);
 int cas_kv_len(const cas_kv* kv, int seq, int32_t* len);
 
 /* Reference read-back of positions pos0 .. pos0+n_tok-1 to dense bf16
- * [n_tok][n_kv_heads][head_dim]; full = 0 gives the zero-padded draft view. */
+ * [n_tok][n_kv_heads][head_dim]; full = 0 gives the zero-padded draft view.  The positions must
+ * have been written by cas_kv_append (published or not); positions never written read as
+ * unspecified values, and a page table entry outside the pool reads as zeros (no access outside
+ * the pools either way). */
 int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_tok, int full,
                 uint16_t* d_K, uint16_t* d_V);
 
@@ -312,6 +315,9 @@ int cas_kv_read(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int pos0, int n_to
  * up to 256 bytes).
  * A column's value depends only on the positions it sees: not on ncols, and not on whether an
  * earlier position is already committed or still in flight.
+ * The page table is consulted only for pages that hold committed positions (a page of in-flight
+ * positions alone needs no entry yet); an entry outside the pool is clamped into it, so a bad
+ * table gives wrong values, never an access outside the pools.
  */
 int cas_attention(cas_ctx* ctx, cas_kv* kv, int layer, int seq, int full, const uint16_t* d_Q,
                   int ncols, int n_q_heads, const uint16_t* d_Knew, const uint16_t* d_Vnew,
@@ -453,6 +459,27 @@ int cas_spec_round_multi(cas_ctx* ctx, cas_model* model, cas_kv* kv, int n_seqs,
 /* Prefill (functional): runs n prompt tokens through the target path in chunks of as many
  * columns as one sequence may bring to a pass (see max_cols) and commits all of them.  d_tokens: int32 [n] on the device. */
 int cas_prefill(cas_ctx* ctx, cas_model* model, cas_kv* kv, int seq, const int32_t* d_tokens, int n);
+
+/* Plain bf16 decode step of the same model from UNCOMPRESSED weights and an uncompressed cache:
+ * the BFloat16 baseline the paper's speedups are normalised to (Sec. 6, 7), built from this
+ * library's own dense kernels (cas_gemv_bf16, the attention kernels reading plain bf16 rows).
+ * Context for measurements, not part of the method; same arithmetic conventions as the encoded
+ * passes (bf16 between ops, fp32 inside).  h_layers: HOST array of n_layers entries with DEVICE
+ * pointers to the bf16 matrices in the row order of the encoded ones (d_wqkv [q_dim + 2 kv_dim]
+ * [hidden], d_wo [hidden][q_dim], d_wgu [2 ffn][hidden] with gate and up rows interleaved, d_wd
+ * [hidden][ffn]); gains, embedding and RoPE table are the model's.  d_kcache / d_vcache: bf16
+ * [n_layers][max_pos][n_kv_heads][head_dim], positions 0 .. len-1 filled; the step stores the new
+ * token's k, v at position len (the caller advances len).  d_logits: NULL or float [vocab].
+ * Needs the context's workspace for the attention partials. */
+typedef struct cas_dense_layer {
+  const uint16_t* d_wqkv;
+  const uint16_t* d_wo;
+  const uint16_t* d_wgu;
+  const uint16_t* d_wd;
+} cas_dense_layer;
+int cas_dense_decode_step(cas_ctx* ctx, cas_model* model, const cas_dense_layer* h_layers,
+                          const uint16_t* d_lm_head, uint16_t* d_kcache, uint16_t* d_vcache, int len,
+                          const int32_t* d_token_in, int32_t* d_token_out, float* d_logits);
 
 /* Greedy acceptance (Sec. 2.2).  Host only, no side effects.  h_draft: k drafted tokens;
  * h_target: k+1 target tokens.  n_accepted = number of leading positions where they are

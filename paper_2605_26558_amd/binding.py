@@ -145,6 +145,8 @@ _SIGNATURES = {
     "cas_tune_measured": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int,
                                     C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                     C.POINTER(C.c_double)]),
+    "cas_dense_decode_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                        C.c_void_p, C.c_void_p, C.c_void_p]),
     "cas_token_probs": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "cas_spec_round_sampling_scratch_floats": (C.c_size_t, [C.c_int, C.c_int]),
     "cas_spec_round_sampling": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int,
@@ -660,6 +662,25 @@ def cas_spec_round(ctx, model: Model, kv: KVCache, seq, pending, k):
     n = C.c_int32()
     ctx._check(_lib().cas_spec_round(ctx.h, model.h, kv.h, seq, int(pending), k, out, C.byref(n)), "cas_spec_round")
     return n.value, [out[i] for i in range(n.value + 1)]
+
+
+class cas_dense_layer(C.Structure):
+    _fields_ = [("d_wqkv", C.c_void_p), ("d_wo", C.c_void_p), ("d_wgu", C.c_void_p), ("d_wd", C.c_void_p)]
+
+
+def cas_dense_decode_step(ctx, model: Model, layers, lm_head, kcache, vcache, length, token_in, token_out=None,
+                          logits=None):
+    """Plain bf16 decode step (baseline).  layers: list of dicts of int16 device tensors
+    wqkv / wo / wgu / wd; kcache, vcache: int16 [n_layers][max_pos][n_kv_heads][128]."""
+    arr = (cas_dense_layer * len(layers))()
+    for i, L in enumerate(layers):
+        for n in ("wqkv", "wo", "wgu", "wd"):
+            assert L[n].is_contiguous()
+            setattr(arr[i], "d_" + n, L[n].data_ptr())
+    ctx._check(_lib().cas_dense_decode_step(ctx.h, model.h, arr, lm_head.data_ptr(), kcache.data_ptr(), vcache.data_ptr(),
+                                            int(length), token_in.data_ptr(),
+                                            None if token_out is None else token_out.data_ptr(),
+                                            None if logits is None else logits.data_ptr()), "cas_dense_decode_step")
 
 
 def cas_token_probs(ctx, logits, tokens, out=None):

@@ -195,6 +195,41 @@ int launch_attention_batch(cas_ctx* ctx, cas_kv* kv, const AttnCall* calls, int 
 
 int launch_attention(cas_ctx* ctx, cas_kv* kv, const AttnCall& c) { return launch_attention_batch(ctx, kv, &c, 1); }
 
+// Plain bf16 attention of one decode step over an UNCOMPRESSED cache (the BFloat16 baseline, for
+// context figures): the same kernels with no committed position in any pool; the cache rows play
+// the part of the in-flight vectors, which the kernels take as plain bf16.  Kc, Vc:
+// [max_pos][n_kv_heads][128], positions 0 .. len-1 filled; the k, v of the new token (position
+// len) are split from the fp32 projection `qkv`, rotated and stored at row len.
+int launch_attention_dense(cas_ctx* ctx, int n_kv_heads, int n_q_heads, uint16_t* Kc, uint16_t* Vc, int len,
+                           const float* qkv, int ystride, const float* rope, uint16_t* O) {
+  if (n_kv_heads < 1 || n_q_heads % n_kv_heads != 0 || len < 0 || !Kc || !Vc || !qkv || !rope || !O) return CAS_EINVAL;
+  AttnBatch b{};
+  AttnArgs& a = b.common;
+  a.g = KvGeom{};
+  a.g.n_kv_heads = n_kv_heads; a.g.page_tokens = kPT; a.g.n_pages = 1;
+  a.layer = 0;
+  a.n_q_heads = n_q_heads; a.grp = n_q_heads / n_kv_heads;
+  a.ystride = ystride; a.rope = rope;
+  a.scale = 0.08838834764831845f;
+  a.pages_per_split = kPagesPerSplit;
+  if (a.grp > 16) return CAS_ENOTSUP;
+  AttnSeq& q = b.s[0];
+  q.page_row = nullptr;  // never consulted: no position is committed to a pool
+  q.len = 0; q.ncols = 1; q.n_new = len + 1; q.slot0 = len;
+  q.Knew = Kc; q.Vnew = Vc; q.Kslot = Kc; q.Vslot = Vc;
+  q.qkv = qkv; q.Q = nullptr; q.O = O;
+  q.nsplit = (len + 1 + kPT - 1) / kPT;
+  const size_t need = sizeof(float) * (size_t)q.nsplit * n_kv_heads * a.grp * kPartStride;
+  if (!ctx->d_ws || need > ctx->ws_bytes) return CAS_ENOMEM;
+  q.part = (float*)ctx->d_ws;
+  const int rc = launch_mt<1, false>(ctx, b, dim3(q.nsplit, n_kv_heads, 1));
+  if (rc != CAS_OK) return rc;
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(a.grp, n_kv_heads, 2), dim3(512),
+                     sizeof(float) * (q.nsplit + kMergeParts * 64), ctx->stream, b);
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
+}
+
 // ---- the variant for callers that cannot allocate: the partial results live in a fixed array of
 // the library's own instead of a workspace the caller had to obtain.  Every GPU holds its own copy
 // of the array at its own address; the address is looked up once per device, with that device

@@ -127,7 +127,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
   const int first = a.len + a.slot0;             // position of column 0 of this pass
   // in flight and produced by this very pass: split from the projection below by all threads
   const bool own_new = a.qkv != nullptr && fresh && pos >= first;
-  const int page = a.page_row[pg];
+  // the page table is consulted only for pages that hold committed positions: a page of in-flight
+  // positions alone needs no pool page yet (and the plain-bf16 form has no pool at all)
+  const int page = tok0 < a.len ? min(max(a.page_row[pg], 0), g.n_pages - 1) : 0;
 
   // ---- 0. loads that do not depend on the page table entry go out first: the queries and,
   //         in the fused form, the k, v of this pass's columns that fall into this page
@@ -217,13 +219,15 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
     const int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
     return (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
   };
+  // only threads whose token is committed touch the pools (their masks are 0 otherwise and the
+  // decode then never looks at the windows)
   auto load_v = [&]() {
     const uint32_t p = word_prefix(mv);
-    wvw.load(p, 32u * j - p, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw);
+    if (live) wvw.load(p, 32u * j - p, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw);
   };
   {
     const uint32_t p = word_prefix(mk);
-    wk.load(p, 32u * j - p, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw);
+    if (live) wk.load(p, 32u * j - p, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw);
   }
   // the draft form has registers to spare for both windows; the exact form asks for V later
   if constexpr (!FULL) load_v();

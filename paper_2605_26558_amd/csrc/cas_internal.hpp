@@ -106,6 +106,9 @@ int launch_attention_static(cas_ctx*, cas_kv*, const AttnCall&);
 size_t attention_static_capacity();
 // the same for the sequences of one pass (same layer and form), four of them per pair of launches
 int launch_attention_batch(cas_ctx*, cas_kv*, const AttnCall* calls, int n);
+// plain bf16 attention of one decode step over an uncompressed cache (baseline for context figures)
+int launch_attention_dense(cas_ctx*, int n_kv_heads, int n_q_heads, uint16_t* Kc, uint16_t* Vc, int len,
+                           const float* qkv, int ystride, const float* rope, uint16_t* O);
 // Brackets one kernel launch with HIP events on the context stream when profiling is on.
 struct ProfScope {
   cas_ctx* ctx;

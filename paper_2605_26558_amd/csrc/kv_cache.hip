@@ -68,6 +68,7 @@ __global__ __launch_bounds__(64) void kv_append_kernel(KvGeom g, uint32_t* spec_
 
   const int pos = pos0 + tok;
   const int page = page_row[pos / g.page_tokens];
+  if (page < 0 || page >= g.n_pages) return;  // a page table entry outside the pool: nothing is written
   const int row = pos % g.page_tokens;
   const size_t tile = (((size_t)layer * g.n_pages + page) * 2 + kv) * g.n_kv_heads + head;
   uint32_t* ts = spec_pool + tile * g.tile_spec_words;
@@ -91,7 +92,11 @@ __global__ __launch_bounds__(128) void kv_read_kernel(KvGeom g, const uint32_t* 
   const int col = threadIdx.x;
   const int tok = blockIdx.x, head = blockIdx.y, kv = blockIdx.z;
   const int pos = pos0 + tok;
-  const int page = page_row[pos / g.page_tokens];
+  int page = page_row[pos / g.page_tokens];
+  if (page < 0 || page >= g.n_pages) {  // a page table entry outside the pool reads as zeros
+    (kv ? Vo : Ko)[((size_t)tok * g.n_kv_heads + head) * 128 + col] = 0;
+    return;
+  }
   const int row = pos % g.page_tokens;
   const size_t tile = (((size_t)layer * g.n_pages + page) * 2 + kv) * g.n_kv_heads + head;
   const uint32_t* ts = spec_pool + tile * g.tile_spec_words;

@@ -170,6 +170,20 @@ __global__ __launch_bounds__(kProbThreads) void token_prob_kernel(const float* _
   }
 }
 
+// Glue of the plain bf16 baseline step (the encoded passes fuse these into their GEMV / GEMM
+// launches): h = bf16(h + bf16(y)), and act[i] = bf16(silu(bf16(y[2i])) * bf16(y[2i+1])).
+__global__ __launch_bounds__(256) void residual_add_kernel(uint16_t* __restrict__ h, const float* __restrict__ y, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) h[i] = f32_to_bf16(bf16_to_f32(h[i]) + round_bf16(y[i]));
+}
+__global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ y, uint16_t* __restrict__ act, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) {
+    const float g = round_bf16(y[2 * i]), u = round_bf16(y[2 * i + 1]);
+    act[i] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
+  }
+}
+
 // tokens [steps][n_seqs] -> [n_seqs][steps]
 __global__ void transpose_tokens_kernel(const int32_t* __restrict__ in, int32_t* __restrict__ out, int steps, int n_seqs) {
   const int i = threadIdx.x;
@@ -560,6 +574,47 @@ int cas_spec_round_sampling(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, int
   for (int i = 0; i < *n_accepted; ++i) h_out[i] = h_tok[i + 1];
   h_out[*n_accepted] = h_tgt[*n_accepted];
   return cas_commit(ctx, m, kv, seq, *n_accepted);
+}
+
+int cas_dense_decode_step(cas_ctx* ctx, cas_model* m, const cas_dense_layer* h_layers, const uint16_t* d_lm_head,
+                          uint16_t* d_kcache, uint16_t* d_vcache, int len, const int32_t* d_token_in,
+                          int32_t* d_token_out, float* d_logits) {
+  if (!ctx || !m || !h_layers || !d_lm_head || !d_kcache || !d_vcache || !d_token_in || len < 0) return CAS_EINVAL;
+  const cas_model_cfg& c = m->cfg;
+  if (len + 1 > c.max_pos) return CAS_EINVAL;
+  const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+  hipStream_t st = ctx->stream;
+  float* logits = d_logits ? d_logits : m->logits;
+  hipLaunchKernelGGL(cas::embed_kernel, dim3(1), dim3(256), 0, st, d_token_in, m->d_embed, m->h, c.hidden, c.vocab);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const cas_dense_layer& D = h_layers[l];
+    const cas_layer_weights& L = m->layers[l];
+    if (!D.d_wqkv || !D.d_wo || !D.d_wgu || !D.d_wd) return CAS_EINVAL;
+    uint16_t* kc = d_kcache + (size_t)l * c.max_pos * kvd;
+    uint16_t* vc = d_vcache + (size_t)l * c.max_pos * kvd;
+    hipLaunchKernelGGL(cas::rmsnorm_kernel, dim3(1), dim3(cas::kNormThreads), 0, st, m->h, L.d_g_attn, m->xn, c.hidden,
+                       c.rms_eps);
+    CAS_TRY(cas_gemv_bf16(ctx, D.d_wqkv, qd + 2 * kvd, c.hidden, c.hidden, m->xn, m->y));
+    CAS_TRY(cas::launch_attention_dense(ctx, c.n_kv_heads, c.n_q_heads, kc, vc, len, m->y, qd + 2 * kvd, m->d_rope, m->ao));
+    CAS_TRY(cas_gemv_bf16(ctx, D.d_wo, c.hidden, qd, qd, m->ao, m->y));
+    hipLaunchKernelGGL(cas::residual_add_kernel, dim3((c.hidden + 255) / 256), dim3(256), 0, st, m->h, m->y, c.hidden);
+    hipLaunchKernelGGL(cas::rmsnorm_kernel, dim3(1), dim3(cas::kNormThreads), 0, st, m->h, L.d_g_ffn, m->xn, c.hidden,
+                       c.rms_eps);
+    CAS_TRY(cas_gemv_bf16(ctx, D.d_wgu, 2 * (int64_t)c.ffn, c.hidden, c.hidden, m->xn, m->y));
+    hipLaunchKernelGGL(cas::swiglu_kernel, dim3((c.ffn + 255) / 256), dim3(256), 0, st, m->y, m->act, c.ffn);
+    CAS_TRY(cas_gemv_bf16(ctx, D.d_wd, c.hidden, c.ffn, c.ffn, m->act, m->y));
+    hipLaunchKernelGGL(cas::residual_add_kernel, dim3((c.hidden + 255) / 256), dim3(256), 0, st, m->h, m->y, c.hidden);
+  }
+  hipLaunchKernelGGL(cas::rmsnorm_kernel, dim3(1), dim3(cas::kNormThreads), 0, st, m->h, m->d_g_final, m->xn, c.hidden,
+                     c.rms_eps);
+  CAS_TRY(cas_gemv_bf16(ctx, d_lm_head, c.vocab, c.hidden, c.hidden, m->xn, logits));
+  if (d_token_out) {
+    hipLaunchKernelGGL(cas::argmax_part_kernel, dim3(cas::kArgmaxSlices, 1), dim3(256), 0, st, logits, c.vocab, m->amax_v,
+                       m->amax_i);
+    hipLaunchKernelGGL(cas::argmax_final_kernel, dim3(1), dim3(64), 0, st, m->amax_v, m->amax_i, d_token_out);
+  }
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
 }
 
 int cas_prefill(cas_ctx* ctx, cas_model* m, cas_kv* kv, int seq, const int32_t* d_tokens, int n) {

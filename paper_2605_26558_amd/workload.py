@@ -399,6 +399,34 @@ class ModelRoundWorkload:
             e1.record()
             torch.cuda.synchronize()
             t_own = e0.elapsed_time(e1) / 3
+        # the whole plain bf16 decode step (dense GEMVs, attention over an uncompressed bf16 cache of the
+        # same context, norms and residuals as separate small kernels): the BFloat16 baseline
+        t_dense_step = None
+        if self.dense and self.batch == 1:
+            torch, B, shape = self.torch, self.B, self.shape
+            nl = shape.n_layers
+            dl = [{n: self.dense[4 * l + i].view(torch.int16) for i, n in enumerate(("wqkv", "wo", "wgu", "wd"))}
+                  for l in range(nl)]
+            head = self.dense[4 * nl].view(torch.int16)
+            kvd = shape.n_kv_heads * shape.head_dim
+            max_pos = self.ctx_len + 1024
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(99)
+            kc = torch.randn((nl, max_pos, kvd), device="cuda", generator=gen).to(torch.bfloat16).view(torch.int16)
+            vc = torch.randn((nl, max_pos, kvd), device="cuda", generator=gen).to(torch.bfloat16).view(torch.int16)
+            tin = torch.ones(1, dtype=torch.int32, device="cuda")
+            tout = torch.empty(1, dtype=torch.int32, device="cuda")
+            step = lambda: B.cas_dense_decode_step(self.ctx, self.model, dl, head, kc, vc, self.ctx_len, tin, tout)
+            step()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                step()
+            e1.record()
+            torch.cuda.synchronize()
+            t_dense_step = e0.elapsed_time(e1) / 3
+            del kc, vc
         # Speed model of Sec. 2.2: a round costs k t_draft + t_verify and yields accepted + 1 tokens.
         # The acceptance of a random-init model is ~0, so the table below uses an ASSUMED per-token
         # acceptance probability alpha (synthetic; the paper's acceptance table did not survive).
@@ -416,6 +444,8 @@ class ModelRoundWorkload:
                "context_vendor_bf16_gemv_GBps": None if t_bf16 is None else 2.0 * self.values / (t_bf16 * 1e-3) / 1e9,
                "context_own_bf16_gemv_pass_ms": t_own,
                "context_own_bf16_gemv_GBps": None if t_own is None else 2.0 * self.values / (t_own * 1e-3) / 1e9,
+               "context_own_bf16_decode_step_ms": t_dense_step,
+               "context_own_bf16_decode_tokens_per_s": None if t_dense_step is None else 1e3 / t_dense_step,
                "tokens_per_s_at_assumed_acceptance": synth_tps,
                "tokens_per_s_forced_acceptance_schedule": {f"alpha={a}": self._forced_rounds(a)
                                                            for a in (0.6, 0.8, 1.0)},

@@ -306,3 +306,39 @@ def test_step_calls_replay_from_a_hip_graph():
                 assert torch.equal(got, ref), rep
             assert bool(torch.isfinite(scratch))
     torch.cuda.synchronize()
+
+
+def test_plain_bf16_baseline_step_matches_the_oracles_target_pass(env):
+    """cas_dense_decode_step (uncompressed weights, uncompressed cache: the BFloat16 baseline) run
+    token by token gives the logits of the oracle's target pass, which is exact bf16 decoding
+    (Sec. 4.1: the verification data restore the original model bit for bit)."""
+    torch, B, ctx = env
+    keep, t = 600, 4
+    weights = synth.model_weights(SHAPE, seed=1)
+    model, kv = gpu_model(torch, B, ctx, weights, keep, t, max_cols=8)
+    om = oracle_model(weights, keep, t)
+    dense = [{n: _dev(torch, lw[n]) for n in ("wqkv", "wo", "wgu", "wd")} for lw in weights["layers"]]
+    head = _dev(torch, weights["lm_head"])
+    kvd = SHAPE.n_kv_heads * SHAPE.head_dim
+    kc = torch.zeros((SHAPE.n_layers, MAX_POS, kvd), dtype=torch.int16, device="cuda")
+    vc = torch.zeros_like(kc)
+    tokens = synth.token_ids(70, SHAPE.vocab, seed=13)          # crosses a page of 64 positions
+    tol = _logit_tol(om, False)
+    worst = 0.0
+    for i, tok in enumerate(tokens):
+        tin = torch.tensor([int(tok)], dtype=torch.int32, device="cuda")
+        tout = torch.empty(1, dtype=torch.int32, device="cuda")
+        lg = torch.empty((1, SHAPE.vocab), dtype=torch.float32, device="cuda")
+        B.cas_dense_decode_step(ctx, model, dense, head, kc, vc, i, tin, tout, lg)
+        ref, new_kv = om.forward([int(tok)], draft=False)
+        om.append_kv(new_kv, 1)
+        got = lg.cpu().numpy().astype(np.float64)
+        worst = max(worst, _check_logits(got, ref, tol, f"dense step {i}"))
+        assert int(tout[0]) == int(np.argmax(got[0]))
+        if i in (0, 63, 69):   # the rows the step stored are the oracle's k, v of that position
+            for layer in range(SHAPE.n_layers):
+                k_ref = new_kv[layer][0][0].reshape(-1)
+                k_got = kc[layer, i].cpu().numpy().view(np.uint16)
+                d = np.abs(O.bf16_to_f64(k_got) - O.bf16_to_f64(k_ref))
+                assert d.max() <= 0.05 * np.abs(O.bf16_to_f64(k_ref)).max()
+    record_ratio("tiny_model_plain_bf16_baseline_logits", worst)
