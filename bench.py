@@ -40,9 +40,10 @@ def parse():
     ap.add_argument("--context", type=int, default=8192, help="committed KV positions when a step starts")
     ap.add_argument("--batch", type=int, default=1,
                     help="sequences decoded together (1..4, batch * (k + 1) <= 16); 1 is the configuration of the metric")
-    ap.add_argument("--workload", choices=["model", "linear", "probe-linear", "probe-attn", "tune"], default="model",
+    ap.add_argument("--workload", choices=["model", "linear", "probe-linear", "probe-attn", "tune", "cpu-units"], default="model",
                     help="model: the metric's workload; linear: the linear layers alone; probe-*: short fixed "
-                         "launch sequences for hardware-counter runs (no JSON line, see workload.py); tune: format "
+                         "launch sequences for hardware-counter runs (no JSON line, see workload.py); cpu-units: the "
+                         "oracle's time for whole units of the workload, host only, minutes; tune: format "
                          "search on measured draft / verification pass times with user-supplied acceptance rates")
     ap.add_argument("--alpha", type=float, default=0.8, help="tune: acceptance rate assumed for every grid point")
     ap.add_argument("--alpha-grid", default=None, help="tune: JSON file with a [n_keep][n_trunc] table of acceptance rates")
@@ -157,12 +158,69 @@ def cpu_baseline(keep, t, k, ctx_len):
             "single_linear_layer_4096x4096_keep250_k4_one_thread": {"draft_gemv_s": td, "verify_gemm_5col_s": tv}}
 
 
+def cpu_units(keep, t):
+    """`bench.py --workload cpu-units` (host only, minutes): the oracle's time for the units the
+    default run only samples.  (1) the single 4096 x 4096 linear layer at 25 % kept, one draft GEMV
+    and one verify GEMM with 4 extra columns; (2) one Llama-3-8B-shaped decoder layer (512-row
+    output head) over 4096 cached positions, draft length 4: one draft step and one verification
+    step of 5 columns, each from the packed streams (decoding them is part of the step; encoding
+    is offline and not timed); (3) the 32-layer model per generated token, EXTRAPOLATED from (2).
+    Each with one thread and with the BLAS threads the host offers."""
+    import numpy as np
+    import threadpoolctl
+    import synth
+    from oracle import cassandra_oracle as O
+    nproc = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    out = {"nproc": int(nproc), "kind": "oracle", "units": {}}
+    W = synth.weight_matrix(4096, 4096, seed=1)
+    X = synth.activations(4096, 5, seed=2)
+    p1 = O.encode_weight(W, 250, 4)
+    k, L = 4, 4096
+    shape = synth.LlamaShape("llama3-8b-1l", 4096, 1, 32, 8, 128, 14336, 512)
+    weights = synth.model_weights(shape, seed=3)
+    tab = synth.rope_table(L + 64, shape.head_dim, shape.rope_theta)
+    K = synth.kv_tensor(L, shape.n_kv_heads, 128, seed=21, outlier_channels=4)
+    V = synth.kv_tensor(L, shape.n_kv_heads, 128, seed=22, outlier_channels=0)
+    pk, pv = O.encode_kv(K.reshape(-1, 128), keep, t), O.encode_kv(V.reshape(-1, 128), keep, t)
+    om0 = O.OracleModel(shape, weights, tab, w_keep=keep, w_t=t, kv_keep=keep, kv_t=t)
+    print("encoded (untimed)", file=sys.stderr, flush=True)
+    tokens = synth.token_ids(k + 1, shape.vocab, seed=9)
+    empty = [(np.zeros((0, shape.n_kv_heads, 128), np.uint16),) * 2]
+    for label, limit in (("one_thread", 1), ("all_threads", None)):
+        ctxm = threadpoolctl.threadpool_limits(limit) if limit else threadpoolctl.threadpool_limits(nproc)
+        with ctxm:
+            t0 = time.perf_counter(); O.gemv_draft(p1, X[0]); t1 = time.perf_counter(); O.gemm_verify(p1, X)
+            t2 = time.perf_counter()
+            res = {"single_linear_layer_4096x4096_keep250": {"draft_gemv_s": t1 - t0, "verify_gemm_5col_s": t2 - t1}}
+            step = {}
+            for draft in (True, False):
+                om0._dec = {}                       # every step decodes the packed streams itself
+                t0 = time.perf_counter()
+                dec = O.decode_draft if draft else O.decode_full
+                view = (dec(pk).reshape(K.shape), dec(pv).reshape(V.shape))
+                om0._cache_kv = lambda layer_index, d, view=view: view
+                om0.cache_len = lambda: L
+                if draft:
+                    om0.forward(tokens[:1], draft=True, extra_kv=empty)
+                else:
+                    om0.forward(tokens, draft=False)
+                step["draft_step_s" if draft else "verify_step_5col_s"] = time.perf_counter() - t0
+            res["one_8b_layer_ctx4096_k4"] = step
+            res["model_32_layers_per_round_k4_EXTRAPOLATED_s"] = 32 * (4 * step["draft_step_s"] + step["verify_step_5col_s"])
+            out["units"][label] = res
+        print(label, "done", file=sys.stderr, flush=True)
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures the one-GPU path only: run with --gpus 1 "
               "(no multi-GPU figure is produced in this build)", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "cpu-units":
+        cpu_units(args.keep, args.trunc)
+        return
     # the CPU oracle first: its worker processes are spawned before this process touches the GPU
     cpu = None if args.no_cpu_baseline or args.workload.startswith("probe") or args.workload == "tune" else \
         cpu_baseline(args.keep, args.trunc, args.k, args.context)

@@ -219,15 +219,17 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
     const int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
     return (uint32_t)((j > 0 ? b0 : 0) + (j > 1 ? b1 : 0) + (j > 2 ? b2 : 0));
   };
-  // only threads whose token is committed touch the pools (their masks are 0 otherwise and the
-  // decode then never looks at the windows)
+  // the pools are touched only by workgroups whose page holds committed positions (uniform for the
+  // workgroup): such a page has a tile of its own, so the rows of its not yet committed tokens can
+  // be read as well (their masks are 0 and the decode never looks at their windows)
+  const bool has_live = tok0 < a.len;
   auto load_v = [&]() {
     const uint32_t p = word_prefix(mv);
-    if (live) wvw.load(p, 32u * j - p, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw);
+    if (has_live) wvw.load(p, 32u * j - p, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw);
   };
   {
     const uint32_t p = word_prefix(mk);
-    if (live) wk.load(p, 32u * j - p, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw);
+    if (has_live) wk.load(p, 32u * j - p, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw);
   }
   // the draft form has registers to spare for both windows; the exact form asks for V later
   if constexpr (!FULL) load_v();

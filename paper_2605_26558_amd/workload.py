@@ -284,17 +284,24 @@ class ModelRoundWorkload:
         self.prof["gemv_draft"] = (n, td * 1e3, self.draft_w)
         self.prof["gemm_verify"] = (n, tv * 1e3, self.verify_w)
         ach = self.draft_w / td / 1e9
-        # HBM-side bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-        # FETCH_SIZE scaled by 2.000 after calibration with a plain copy): fetch = 1.042 x the
-        # algorithmic bytes on the 28672 x 4096 shape; every 4-byte output is written as a 32-byte
-        # sector (neighbouring rows belong to workgroups on different XCDs).
-        traffic = 1.042 * self.draft_w / n + 32.0 * sum(m.desc.rows for L in self.layers
-                                                       for m in (L["wqkv"], L["wo"], L["wgu"], L["wd"])) / n
+        # HBM-side bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
+        # `bench.py --workload probe-linear`; FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000 after
+        # calibration with a plain copy of known size): fetch / algorithmic bytes of the draft GEMV
+        # measured per matrix shape of the 8B model, 1.035 for any other shape (the weighted mean);
+        # every 4-byte output is written as a 32-byte sector (neighbouring rows belong to workgroups
+        # on different XCDs).
+        ratio = {(6144, 4096): 1.040, (4096, 4096): 1.044, (28672, 4096): 1.037, (4096, 14336): 1.027,
+                 (128256, 4096): 1.030}
+        mats = [L[n] for L in self.layers for n in ("wqkv", "wo", "wgu", "wd")] + [self.head]
+        fetch = sum(ratio.get((m.desc.rows, m.desc.cols), 1.035) * m.desc.rows * (m.desc.bw + m.desc.sw) * 4
+                    for m in mats)
+        traffic = (fetch + 32.0 * sum(m.desc.rows for m in mats)) / n
         return {"bound": "hbm", "kernel": "gemv_draft_kernel", "achieved": ach, "peak": 8000.0, "unit": "GB/s",
                 "frac": ach / 8000.0, "traffic": traffic, "launches": n, "avg_launch_us": td / n * 1e6,
                 "bytes_per_launch": self.draft_w / n,
-                "traffic_source": "profiles/pmc_gemv_draft_gemm_verify_28672x4096.md (counter ratio applied "
-                                  "to this run's bytes per launch)"}
+                "traffic_source": "profiles/pmc_gemv_draft_gemm_verify_llama3_8b_shapes.md (fetch / algorithmic "
+                                  "ratio measured per matrix shape, applied to this run's launches; shapes "
+                                  "outside that table use the weighted mean 1.035 and are an extrapolation)"}
 
     def _time_passes(self, reps=3):
         """Wall time of one draft pass, one verification pass (k+1 columns) and one plain decode

@@ -36,14 +36,15 @@ LOGIT_SLACK = 1.0
 
 
 def record_ratio(name: str, value: float) -> None:
-    """Appends a measured error / tolerance ratio of a GPU parity test to
-    gpurun_out/parity_ratios.jsonl (the figures quoted in the design notes come from there)."""
+    """Prints a measured error / tolerance ratio of a GPU parity test and, when the environment
+    variable CAS_PARITY_RATIOS names a file, appends it there as a JSON line (the figures quoted
+    in the design notes were collected that way)."""
     import json
-    out = os.path.join(ROOT, "gpurun_out")
-    try:
-        os.makedirs(out, exist_ok=True)
-        with open(os.path.join(out, "parity_ratios.jsonl"), "a") as f:
-            f.write(json.dumps({"test": name, "err_over_tol": float(value)}) + "\n")
-    except OSError:
-        pass
+    path = os.environ.get("CAS_PARITY_RATIOS")
+    if path:
+        try:
+            with open(path, "a") as f:
+                f.write(json.dumps({"test": name, "err_over_tol": float(value)}) + "\n")
+        except OSError:
+            pass
     print(f"[parity] {name}: err/tol = {value:.4g}", flush=True)
