@@ -94,6 +94,60 @@ def test_attention_limits(env):
     assert _code(B, lambda: B.cas_kv_append(ctx, kv, 0, 0, z(129, 2, 128), z(129, 2, 128))) == B.CAS_ENOMEM
 
 
+def test_entry_points_added_later_reject_what_they_cannot_do(env):
+    """cas_attention_multi, cas_token_probs, cas_spec_round_sampling and cas_dense_decode_step:
+    argument errors come back as codes from the host-side checks; degenerate sizes work."""
+    torch, B, _ = env
+    lib = B._lib()
+    ctx = B.Context(workspace=torch.empty(8 << 20, dtype=torch.uint8, device="cuda"))
+    kv = B.KVCache(ctx, 1, 2, n_pages=4, max_seqs=2, max_pages_per_seq=2)
+    z = lambda *s: torch.zeros(s, dtype=torch.int16, device="cuda")
+    # the same sequence twice in one call; a sequence out of range
+    q, kn = [z(1, 2, 128), z(1, 2, 128)], [z(1, 2, 128), z(1, 2, 128)]
+    assert _code(B, lambda: B.cas_attention_multi(ctx, kv, 0, [0, 0], False, q, kn, kn)) == B.CAS_EINVAL
+    assert _code(B, lambda: B.cas_attention_multi(ctx, kv, 0, [0, 2], False, q, kn, kn)) == B.CAS_EINVAL
+    outs = B.cas_attention_multi(ctx, kv, 0, [0, 1], False, q, kn, kn)       # empty caches, one in-flight vector each
+    assert len(outs) == 2 and outs[0].shape == (1, 2, 128)
+    # probabilities: no rows is fine, a vocabulary of 0 is not
+    lg = torch.zeros((0, 8), dtype=torch.float32, device="cuda")
+    assert B.cas_token_probs(ctx, lg, torch.zeros(0, dtype=torch.int32, device="cuda")).numel() == 0
+    one = torch.zeros((1, 1), dtype=torch.float32, device="cuda")
+    assert float(B.cas_token_probs(ctx, one, torch.zeros(1, dtype=torch.int32, device="cuda"))[0]) == 1.0
+    assert lib.cas_token_probs(ctx.h, B._ptr(one), 0, 1, B._ptr(one), B._ptr(one)) == B.CAS_EINVAL
+    assert lib.cas_spec_round_sampling_scratch_floats(100, 3) == 7 * 100 + 6
+    assert lib.cas_spec_round_sampling_scratch_floats(0, 3) == 0
+    # the rounds and the plain bf16 step on a small model
+    shape = synth.TINY
+    weights = synth.model_weights(shape, seed=1)
+    dev = lambda a: _dev(torch, a)
+    layers = []
+    for lw in weights["layers"]:
+        L = {n: B.cas_encode_weight(ctx, dev(lw[n]), 600, 4) for n in ("wqkv", "wo", "wgu", "wd")}
+        L["g_attn"], L["g_ffn"] = dev(lw["g_attn"]), dev(lw["g_ffn"])
+        layers.append(L)
+    head = B.cas_encode_weight(ctx, dev(weights["lm_head"]), 600, 4)
+    rope = torch.from_numpy(synth.rope_table(64, shape.head_dim, shape.rope_theta)).cuda()
+    model = B.Model(ctx, shape, layers, head, dev(weights["embed"]), dev(weights["g_final"]), rope, 4)
+    kv = B.KVCache(ctx, shape.n_layers, shape.n_kv_heads, n_pages=1, max_seqs=1, max_pages_per_seq=1)
+    # a draft length that does not fit max_cols; k = 0 is a plain step that needs no scratch and no r
+    assert _code(B, lambda: B.cas_spec_round_sampling(ctx, model, kv, 0, 1, 4, [0.5] * 4)) == B.CAS_EINVAL
+    n, out, p, q = B.cas_spec_round_sampling(ctx, model, kv, 0, 1, 0, [])
+    assert n == 0 and len(out) == 1 and B.cas_kv_len(kv, 0) == 1
+    dense = [{n: dev(lw[n]) for n in ("wqkv", "wo", "wgu", "wd")} for lw in weights["layers"]]
+    kvd = shape.n_kv_heads * shape.head_dim
+    kc = torch.zeros((shape.n_layers, 64, kvd), dtype=torch.int16, device="cuda")
+    tin = torch.ones(1, dtype=torch.int32, device="cuda")
+    # a position past the model's table; a missing matrix
+    assert _code(B, lambda: B.cas_dense_decode_step(ctx, model, dense, dev(weights["lm_head"]), kc, kc.clone(), 64, tin)) == B.CAS_EINVAL
+    arr = (B.cas_dense_layer * shape.n_layers)()
+    assert lib.cas_dense_decode_step(ctx.h, model.h, arr, B._ptr(kc), B._ptr(kc), B._ptr(kc), 0, B._ptr(tin), None,
+                                     None) == B.CAS_EINVAL
+    # without a workspace for the attention partials the step says so
+    ctx0 = B.Context()
+    model0 = B.Model(ctx0, shape, layers, head, dev(weights["embed"]), dev(weights["g_final"]), rope, 4)
+    assert _code(B, lambda: B.cas_dense_decode_step(ctx0, model0, dense, dev(weights["lm_head"]), kc, kc.clone(), 0, tin)) == B.CAS_ENOMEM
+
+
 def test_library_from_a_plain_c_program():
     """tests/c/abi_gpu_roundtrip.c: encode, exact and draft reconstruction, draft GEMV and
     verification GEMM through the C ABI with device memory from the HIP runtime, no Python in the
