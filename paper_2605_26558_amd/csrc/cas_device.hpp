@@ -121,22 +121,25 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// Raw windows of the packed streams at one 32-column bitmap word: the words that hold the
-// word's kept fields (spec), their dropped bits (lo) and its pruned values, before alignment.
-// Loading and decoding are separate so the loads of the next word can be in flight while the
-// current one is decoded.
+// Raw windows of the packed streams at one 32-column bitmap word, before alignment: the words
+// that hold the word's kept fields (spec) and their dropped bits (lo) in KeptWindows, those of
+// its pruned values in PrunedWindows.  Loading and decoding are separate so the loads of the
+// next word can be in flight while the current one is decoded.
+//
+// decode() hands each (column position, bf16 word) to `write`.  A lane that runs out of bits
+// keeps calling write with position -1 and a don't-care value: the caller maps -1 to a dump
+// slot.  All 64 lanes of the wave must call it together.
 template <int T, bool FULL>
-struct WordWindows {
+struct KeptWindows {
   static constexpr int FW = 16 - T;
   static constexpr int LW = T > 0 ? T : 1;
   uint32_t ds[FW + 1];
   uint32_t dl[LW + 1];
-  uint32_t dp[17];
-  uint32_t shs, shl, shp;
+  uint32_t shs, shl;
 
-  // p / u: kept / pruned values of the row before this word
-  __device__ __forceinline__ void load(uint32_t p, uint32_t u, const uint32_t* __restrict__ sp_row,
-                                       const uint32_t* __restrict__ lo_row, const uint32_t* __restrict__ pr_row) {
+  // p: kept values of the row before this word
+  __device__ __forceinline__ void load(uint32_t p, const uint32_t* __restrict__ sp_row,
+                                       const uint32_t* __restrict__ lo_row) {
     {
       uint32_t bit = p * FW;
       shs = bit & 31u;
@@ -151,30 +154,17 @@ struct WordWindows {
 #pragma unroll
       for (int q = 0; q <= T; ++q) dl[q] = src[q];
     }
-    if constexpr (FULL) {
-      shp = (u & 1u) << 4;
-      const uint32_t* src = pr_row + (u >> 1);
-#pragma unroll
-      for (int q = 0; q <= 16; ++q) dp[q] = src[q];
-    }
   }
 
-  // Hands each (column position, bf16 word) of the word to `write`.  m: kept mask, pm: pruned
-  // mask (0 when only the speculation data is read).  A lane that runs out of bits keeps
-  // calling write with position -1 and a don't-care value: the caller maps -1 to a dump slot.
-  // All 64 lanes of the wave must call this together.
+  // m: kept mask of the word
   template <class W>
-  __device__ __forceinline__ void decode(uint32_t m, uint32_t pm, W&& write) const {
-    uint32_t ws[FW], wl[LW], wp[16];
+  __device__ __forceinline__ void decode(uint32_t m, W&& write) const {
+    uint32_t ws[FW], wl[LW];
 #pragma unroll
     for (int q = 0; q < FW; ++q) ws[q] = __builtin_amdgcn_alignbit(ds[q + 1], ds[q], shs);
     if constexpr (FULL && T > 0) {
 #pragma unroll
       for (int q = 0; q < T; ++q) wl[q] = __builtin_amdgcn_alignbit(dl[q + 1], dl[q], shl);
-    }
-    if constexpr (FULL) {
-#pragma unroll
-      for (int q = 0; q < 16; ++q) wp[q] = __builtin_amdgcn_alignbit(dp[q + 1], dp[q], shp);
     }
     auto kept = [&](auto E) {
       constexpr int e = decltype(E)::value;
@@ -198,25 +188,63 @@ struct WordWindows {
       static_for<0, 8>(kept);
       kept_tail(kept_tail, std::integral_constant<int, 8>{});
     }
-    if constexpr (FULL) {
-      auto pruned = [&](auto E) {
-        constexpr int e = decltype(E)::value;
-        int pos = lowest_bit(pm);
-        pm &= pm - 1u;
-        write(pos, (uint16_t)(wp[e >> 1] >> ((e & 1) * 16)));
-      };
-      auto pruned_tail = [&](auto self, auto E) -> void {
-        constexpr int e = decltype(E)::value;
-        if constexpr (e < 32) {
-          if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
-            pruned(std::integral_constant<int, e>{});
-            pruned(std::integral_constant<int, e + 1>{});
-            self(self, std::integral_constant<int, e + 2>{});
-          }
+  }
+};
+
+struct PrunedWindows {
+  uint32_t dp[17];
+  uint32_t shp;
+
+  // u: pruned values of the row before this word
+  __device__ __forceinline__ void load(uint32_t u, const uint32_t* __restrict__ pr_row) {
+    shp = (u & 1u) << 4;
+    const uint32_t* src = pr_row + (u >> 1);
+#pragma unroll
+    for (int q = 0; q <= 16; ++q) dp[q] = src[q];
+  }
+
+  // pm: mask of the word's unselected columns
+  template <class W>
+  __device__ __forceinline__ void decode(uint32_t pm, W&& write) const {
+    uint32_t wp[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) wp[q] = __builtin_amdgcn_alignbit(dp[q + 1], dp[q], shp);
+    auto pruned = [&](auto E) {
+      constexpr int e = decltype(E)::value;
+      int pos = lowest_bit(pm);
+      pm &= pm - 1u;
+      write(pos, (uint16_t)(wp[e >> 1] >> ((e & 1) * 16)));
+    };
+    auto pruned_tail = [&](auto self, auto E) -> void {
+      constexpr int e = decltype(E)::value;
+      if constexpr (e < 32) {
+        if (__builtin_amdgcn_ballot_w64(pm != 0u)) {
+          pruned(std::integral_constant<int, e>{});
+          pruned(std::integral_constant<int, e + 1>{});
+          self(self, std::integral_constant<int, e + 2>{});
         }
-      };
-      pruned_tail(pruned_tail, std::integral_constant<int, 0>{});
-    }
+      }
+    };
+    pruned_tail(pruned_tail, std::integral_constant<int, 0>{});
+  }
+};
+
+// Both together (FULL) or the speculation data alone: pm is 0 and unused without FULL.
+template <int T, bool FULL>
+struct WordWindows {
+  KeptWindows<T, FULL> k;
+  PrunedWindows pr;
+
+  __device__ __forceinline__ void load(uint32_t p, uint32_t u, const uint32_t* __restrict__ sp_row,
+                                       const uint32_t* __restrict__ lo_row, const uint32_t* __restrict__ pr_row) {
+    k.load(p, sp_row, lo_row);
+    if constexpr (FULL) pr.load(u, pr_row);
+  }
+
+  template <class W>
+  __device__ __forceinline__ void decode(uint32_t m, uint32_t pm, W&& write) const {
+    k.decode(m, write);
+    if constexpr (FULL) pr.decode(pm, write);
   }
 };
 

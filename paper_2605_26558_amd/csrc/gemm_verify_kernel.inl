@@ -131,8 +131,9 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
         u4[i] = nvalid > 0 ? (uint32_t)(word0 + 4 * i) * 32u - p : 0u;
       }
     }
-    WordWindows<T, true> win[2];
-    win[0].load(p4[0], u4[0], sp_row, lo_row, pr_row);
+    KeptWindows<T, true> kw;
+    PrunedWindows pw;
+    kw.load(p4[0], sp_row, lo_row);
     // ---- this wave's X columns of the next XST steps (bf16, zero beyond the last column)
     auto stage_x = [&](int s) {
       const int col0 = slab * kSlabCols + part * (WPP * 32) + s * XQ;
@@ -154,9 +155,15 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
       constexpr int i = decltype(I)::value;
       // the MFMA reads of the previous staging ended with the fence that closes a step
       if constexpr (i % XST == 0) stage_x(i / XST);
-      if constexpr (i + 1 < WPL) win[(i + 1) & 1].load(p4[i + 1], u4[i + 1], sp_row, lo_row, pr_row);
+      // Half-step pipeline: the pruned values of this step are fetched while its kept values
+      // are placed, the kept fields of the next step while the pruned values are placed.  One
+      // raw window set of each kind is live at a time (116 registers instead of 156 with two
+      // whole sets); measured 4 % faster than loading a whole step ahead.
       // pos == -1 (lane out of bits) lands in the dump slot in front of the group
-      win[i & 1].decode(m4[i], pm4[i], [&](int pos, uint16_t v) { trow[pos] = v; });
+      pw.load(u4[i], pr_row);
+      kw.decode(m4[i], [&](int pos, uint16_t v) { trow[pos] = v; });
+      if constexpr (i + 1 < WPL) kw.load(p4[i + 1], sp_row, lo_row);
+      pw.decode(pm4[i], [&](int pos, uint16_t v) { trow[pos] = v; });
       // ---- tile x X: tile column 32*g + c is slab column (part*WPP + 4*i + g)*32 + c
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
