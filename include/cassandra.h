@@ -199,6 +199,17 @@ int cas_unary_decode(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, 
 int cas_gemv_draft_unary(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, const uint16_t* d_x,
                          float* d_y);
 
+/* Verification GEMM Y = W X with the speculation data in the unary form (Sec. 4.2 lossless
+ * configuration under Sec. 4.1 target inference): W is the exact bf16 matrix, rebuilt from
+ * d_uspec + d_verif.  Blocks of rows are first re-coded into the raw spec stream in the
+ * workspace, then multiplied by the kernel of cas_gemm_verify, so every output has exactly the
+ * bits cas_gemm_verify gives on the raw form.  d_X: bf16 [ncols][cols]; d_Y: float [ncols][rows];
+ * 1 <= ncols <= 32.  Workspace: at least 16 rows of the raw stream (16 * sw * 4 + 256 bytes); more
+ * means fewer launches.  CAS_ENOMEM if it holds less, CAS_ENOTSUP if K bytes of exponents do
+ * not fit the LDS. */
+int cas_gemm_verify_unary(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, const void* d_verif,
+                          const uint16_t* d_X, int ncols, float* d_Y);
+
 /* ---- speculation data with shared exponents (Sec. 4.2 "Exponent Compression", the MX
  *      approach: the lossy, smaller configuration; decoder of Sec. 5.1, leading-zero count
  *      and shift against the shared exponent) ---- */
@@ -405,6 +416,18 @@ int cas_model_act_bytes(const cas_model_cfg* cfg, size_t* bytes);
 int cas_model_create(const cas_model_cfg* cfg, const cas_model_weights* weights, void* d_act,
                      size_t act_bytes, cas_model** out);
 int cas_model_destroy(cas_model* model);
+
+/* Switches one linear layer of the model to the unary form of its speculation data (Sec. 4.2
+ * lossless configuration): from then on draft passes read d_uspec through the kernel of
+ * cas_gemv_draft_unary (norm, residual add and SwiGLU run as separate launches with the same
+ * roundings) and verification passes through cas_gemm_verify_unary, whose results equal those
+ * of the raw form bit for bit; the tensor's raw d_spec is no longer read and may be freed.
+ * layer: 0 .. n_layers-1, or -1 for the output head (which is then ignored); which: 0 wqkv,
+ * 1 wo, 2 wgu, 3 wd.  udesc / d_uspec: from cas_unary_plan / cas_unary_encode on that tensor
+ * (the descriptor is copied, the buffer stays caller-owned); udesc = NULL switches back.
+ * CAS_EINVAL if the descriptor does not belong to the tensor.  The context's workspace must
+ * hold 16 rows of the largest raw spec stream plus 256 bytes for the verification passes. */
+int cas_model_use_unary(cas_model* model, int layer, int which, const cas_udesc* udesc, const void* d_uspec);
 
 /* One draft pass (Sec. 4.1 draft inference): speculation data only for every linear layer and
  * for the cache.  d_token_in: the token at in-flight slot `slot` (position len + slot);

@@ -156,6 +156,9 @@ _SIGNATURES = {
     "cas_unary_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p]),
     "cas_unary_decode": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
     "cas_gemv_draft_unary": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p]),
+    "cas_model_use_unary": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(cas_udesc), C.c_void_p]),
+    "cas_gemm_verify_unary": (C.c_int, [C.c_void_p, C.POINTER(cas_udesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                      C.c_void_p]),
     "cas_gemv_bf16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "cas_mx_plan": (C.c_int, [C.POINTER(cas_wdesc), C.POINTER(cas_mxdesc)]),
     "cas_mx_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -355,6 +358,18 @@ def cas_gemv_draft_unary(ctx: Context, uw: UnaryWeight, x, out=None):
         out = torch.empty(d.rows, dtype=torch.float32, device=x.device)
     ctx._check(_lib().cas_gemv_draft_unary(ctx.h, C.byref(uw.desc), _ptr(uw.uspec), _ptr(x), _ptr(out)),
                "cas_gemv_draft_unary")
+    return out
+
+
+def cas_gemm_verify_unary(ctx: Context, uw: UnaryWeight, X, out=None):
+    """X: bf16 bits [ncols, cols] -> float32 [ncols, rows], W exact, read from the unary form."""
+    torch = ctx._torch
+    d = uw.desc.base
+    assert X.dim() == 2 and X.shape[1] == d.cols and X.is_contiguous() and X.element_size() == 2
+    if out is None:
+        out = torch.empty((X.shape[0], d.rows), dtype=torch.float32, device=X.device)
+    ctx._check(_lib().cas_gemm_verify_unary(ctx.h, C.byref(uw.desc), _ptr(uw.uspec), _ptr(uw.verif), _ptr(X),
+                                            X.shape[0], _ptr(out)), "cas_gemm_verify_unary")
     return out
 
 
@@ -618,6 +633,16 @@ class Model:
         if rc != CAS_OK:
             raise CasError(rc, "cas_model_create")
         self.h = h
+
+    def use_unary(self, layer: int, which: int, uw=None):
+        """Switch a linear layer (layer -1: the output head; which: 0 wqkv, 1 wo, 2 wgu, 3 wd) to the
+        unary form `uw` of its speculation data (UnaryWeight), or back to the raw form (None)."""
+        rc = _lib().cas_model_use_unary(self.h, layer, which, C.byref(uw.desc) if uw is not None else None,
+                                        _ptr(uw.uspec) if uw is not None else None)
+        if rc != CAS_OK:
+            raise CasError(rc, "cas_model_use_unary")
+        self._unary = getattr(self, "_unary", {})
+        self._unary[(layer, which if layer >= 0 else 0)] = uw   # keeps the buffer alive
 
     def close(self):
         if getattr(self, "h", None):

@@ -78,6 +78,10 @@ int launch_gemv_draft_fused(cas_ctx*, const cas_wdesc&, const void* spec, const 
 int launch_gemm_verify(cas_ctx*, const cas_wdesc&, const void* spec, const void* verif, const uint16_t* X, int ncols, float* Y);
 int launch_gemm_verify_fused(cas_ctx*, const cas_wdesc&, const void* spec, const void* verif, const uint16_t* X,
                              int ncols, float* Y, int epi, uint16_t* out16);
+// unary.hip: rows [row0, row0 + nrows) of the raw spec stream (sw words per row) rebuilt from the unary form
+int launch_unary_expand(cas_ctx*, const cas_udesc&, const void* uspec, int64_t row0, int nrows, uint32_t* out);
+int launch_gemm_verify_unary_fused(cas_ctx*, const cas_udesc&, const void* uspec, const void* verif, const uint16_t* X,
+                                   int ncols, float* Y, int epi, uint16_t* out16);
 int launch_kv_append(cas_ctx*, cas_kv*, int layer, int seq, const uint16_t* K, const uint16_t* V, int n_tok, int pos0);
 // the same for n_layers consecutive layers in one launch; the vectors of layer layer0 + i start
 // i * layer_stride values after K / V

@@ -23,6 +23,24 @@ int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const
   return launch_gemm_verify_fused(ctx, d, spec, verif, X, ncols, Y, 0, nullptr);
 }
 
+// Picks the form of the kernel for a matrix.  The choice depends on the shape of the WHOLE matrix
+// (a.yld rows), never on the number of columns or on the block of rows a launch covers: it fixes
+// the order in which a row's partial sums are added, and a column must get the same bits in
+// every call.
+static int launch_verify_args(cas_ctx* ctx, const VerifyArgs& a, int t) {
+  // One row group per workgroup.  Many row groups: four waves, each taking a quarter of every
+  // slab (measured faster than 8-wave workgroups: fewer lanes wait at the slab barriers).  Few
+  // row groups: eight waves so that every CU still gets several, sixteen when the rows are long
+  // (each wave then has one decode step per slab and the serial chain per workgroup halves).
+  // More than 8 columns: X is staged per decode step (see gemm_verify_wide.hip); up to 8 the
+  // per-slab staging measured 5 % faster on the largest matrices.
+  if (a.ncols > 8) return launch_gemm_verify_wide(ctx, a, t);
+  const int groups = (a.yld + 15) / 16;
+  if (groups < kFewGroups && a.cols >= 4 * kSlabCols) return launch_gq<1, 16, 1, 1>(ctx, a, t);
+  if (groups < kFewGroups) return launch_gq<1, 8, 2, 1>(ctx, a, t);
+  return launch_gq<1, 4, 4, 1>(ctx, a, t);
+}
+
 int launch_gemm_verify_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const void* verif,
                              const uint16_t* X, int ncols, float* Y, int epi, uint16_t* out16) {
   if (d.rows <= 0) return CAS_OK;
@@ -35,19 +53,46 @@ int launch_gemm_verify_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec,
   a.spec = (const uint32_t*)((const char*)spec + d.off_spec);
   a.lo = (const uint32_t*)((const char*)verif + d.off_lo);
   a.pruned = (const uint32_t*)((const char*)verif + d.off_pruned);
-  a.X = X; a.Y = Y;
+  a.X = X; a.Y = Y; a.yld = (int)d.rows;
   ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + d.sw + d.lw + d.pw));
-  // One row group per workgroup.  Many row groups: four waves, each taking a quarter of every
-  // slab (measured faster than 8-wave workgroups: fewer lanes wait at the slab barriers).  Few
-  // row groups: eight waves so that every CU still gets several, sixteen when the rows are long
-  // (each wave then has one decode step per slab and the serial chain per workgroup halves).
-  // More than 8 columns: X is staged per decode step (see gemm_verify_wide.hip); up to 8 the
-  // per-slab staging measured 5 % faster on the largest matrices.
-  if (ncols > 8) return launch_gemm_verify_wide(ctx, a, d.t);
-  const int groups = (int)((d.rows + 15) / 16);
-  if (groups < kFewGroups && d.cols >= 4 * kSlabCols) return launch_gq<1, 16, 1, 1>(ctx, a, d.t);
-  if (groups < kFewGroups) return launch_gq<1, 8, 2, 1>(ctx, a, d.t);
-  return launch_gq<1, 4, 4, 1>(ctx, a, d.t);
+  return launch_verify_args(ctx, a, d.t);
+}
+
+// The same product with the speculation data in the unary form (Sec. 4.2, the lossless
+// configuration): blocks of rows are re-coded into the raw spec stream in the workspace and the
+// kernel above runs on each block, so every output has the bits the raw form gives.
+int launch_gemm_verify_unary_fused(cas_ctx* ctx, const cas_udesc& u, const void* uspec, const void* verif,
+                                   const uint16_t* X, int ncols, float* Y, int epi, uint16_t* out16) {
+  const cas_wdesc& d = u.base;
+  if (d.rows <= 0) return CAS_OK;
+  if (epi == 2 && (d.rows & 1)) return CAS_EINVAL;
+  const size_t row_bytes = (size_t)d.sw * 4;
+  // a block of rows: a multiple of 16 (whole row groups), as many as the workspace holds
+  // (the kernel's windows read a little past the last field of a row: 256 bytes of slack behind the block)
+  int64_t blk = row_bytes ? (ctx->ws_bytes > 256 ? (int64_t)((ctx->ws_bytes - 256) / row_bytes) : 0) : d.rows;
+  blk = std::min<int64_t>(blk, d.rows);
+  if (blk < d.rows) blk = blk / 16 * 16;
+  if (blk < 1 || (d.sw > 0 && !ctx->d_ws)) return CAS_ENOMEM;
+  ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + u.smw + d.lw + d.pw) + 4.0 * (double)u.ue_words);
+  for (int64_t r0 = 0; r0 < d.rows; r0 += blk) {
+    const int nr = (int)std::min<int64_t>(blk, d.rows - r0);
+    int rc = launch_unary_expand(ctx, u, uspec, r0, nr, (uint32_t*)ctx->d_ws);
+    if (rc != CAS_OK) return rc;
+    VerifyArgs a;
+    a.epi = epi;
+    a.rows = nr; a.cols = (int)d.cols; a.bw = d.bw; a.sw = d.sw; a.lw = d.lw; a.pw = d.pw;
+    a.ncols = ncols;
+    a.bitmap = (const uint32_t*)((const char*)uspec + u.off_bitmap) + (size_t)r0 * d.bw;
+    a.spec = (const uint32_t*)ctx->d_ws;
+    a.lo = (const uint32_t*)((const char*)verif + d.off_lo) + (size_t)r0 * d.lw;
+    a.pruned = (const uint32_t*)((const char*)verif + d.off_pruned) + (size_t)r0 * d.pw;
+    a.X = X; a.yld = (int)d.rows;
+    a.Y = Y ? Y + r0 : nullptr;
+    a.out16 = out16 ? out16 + (epi == 2 ? r0 / 2 : r0) : nullptr;
+    rc = launch_verify_args(ctx, a, d.t);
+    if (rc != CAS_OK) return rc;
+  }
+  return CAS_OK;
 }
 
 }  // namespace cas

@@ -17,9 +17,10 @@ struct VerifyArgs {
   const uint32_t* lo;
   const uint32_t* pruned;
   const uint16_t* X;  // [ncols][cols]
-  float* Y;           // [ncols][rows] (epilogue 0)
+  float* Y;           // [ncols][yld] (epilogue 0)
+  int yld;            // output rows per column in Y / out16 (>= rows: the launch may cover a block of rows)
   int epi;            // 0: Y = W X;  1: h = bf16(h + bf16(W X));  2: act[i] = swiglu(rows 2i, 2i+1)
-  uint16_t* out16;    // h [ncols][rows] (epilogue 1) or act [ncols][rows/2] (epilogue 2)
+  uint16_t* out16;    // h [ncols][yld] (epilogue 1) or act [ncols][yld/2] (epilogue 2)
 };
 
 constexpr int kSlabCols = 2048;
@@ -199,14 +200,14 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         int orow = row0 + 4 * mq + e;
-        if (orow < a.rows) a.Y[(size_t)col * a.rows + orow] = s[e];
+        if (orow < a.rows) a.Y[(size_t)col * a.yld + orow] = s[e];
       }
     } else if (a.epi == 1) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         int orow = row0 + 4 * mq + e;
         if (orow < a.rows) {
-          uint16_t* hp = a.out16 + (size_t)col * a.rows + orow;
+          uint16_t* hp = a.out16 + (size_t)col * a.yld + orow;
           *hp = f32_to_bf16(bf16_to_f32(*hp) + round_bf16(s[e]));
         }
       }
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
         int orow = row0 + 4 * mq + e;
         if (orow + 1 < a.rows) {
           const float g = round_bf16(s[e]), u = round_bf16(s[e + 1]);
-          a.out16[(size_t)col * (a.rows >> 1) + (orow >> 1)] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
+          a.out16[(size_t)col * (a.yld >> 1) + (orow >> 1)] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
         }
       }
     }

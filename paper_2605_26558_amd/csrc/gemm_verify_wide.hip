@@ -11,7 +11,7 @@ namespace cas {
 // the same bits in every call.
 template <int NB>
 static int launch_nb(cas_ctx* ctx, const VerifyArgs& a, int t) {
-  const int groups = (a.rows + 15) / 16;
+  const int groups = (a.yld + 15) / 16;  // of the whole matrix, also when the launch covers a block of its rows
   if (groups < kFewGroups && a.cols >= 4 * kSlabCols) return launch_gq<1, 16, 1, NB>(ctx, a, t);
   if (groups < kFewGroups) return launch_gq<1, 8, 1, NB>(ctx, a, t);
   return launch_gq<1, 4, 1, NB>(ctx, a, t);
@@ -27,8 +27,8 @@ int launch_gemm_verify_wide(cas_ctx* ctx, const VerifyArgs& a, int t) {
   lo.ncols = 16;
   hi.ncols = a.ncols - 16;
   hi.X = a.X + (size_t)16 * a.cols;
-  if (a.Y) hi.Y = a.Y + (size_t)16 * a.rows;
-  if (a.out16) hi.out16 = a.out16 + (size_t)16 * (a.epi == 2 ? a.rows >> 1 : a.rows);
+  if (a.Y) hi.Y = a.Y + (size_t)16 * a.yld;
+  if (a.out16) hi.out16 = a.out16 + (size_t)16 * (a.epi == 2 ? a.yld >> 1 : a.yld);
   rc = launch_nb<1>(ctx, lo, t);
   if (rc != CAS_OK) return rc;
   return launch_nb<1>(ctx, hi, t);

@@ -4,6 +4,7 @@
 // from one operation to the next is rounded to bf16; inside an operation arithmetic is fp32.
 #include <algorithm>
 #include <new>
+#include <vector>
 #include "cas_device.hpp"
 #include "cas_internal.hpp"
 
@@ -20,6 +21,14 @@ struct cas_model {
   int32_t *tok, *tgt;  // token chain of a round: pending + drafts, and the target's tokens
   float* amax_v;       // per-slice argmax candidates
   int32_t* amax_i;
+  // Linear layers switched to the unary form of their speculation data (cas_model_use_unary):
+  // entry 4 * layer + {0 wqkv, 1 wo, 2 wgu, 3 wd}, the output head last.
+  struct UnaryRef {
+    bool on = false;
+    cas_udesc u;
+    const void* d_uspec = nullptr;
+  };
+  std::vector<UnaryRef> unary;
 };
 
 namespace cas {
@@ -230,16 +239,48 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, 
   if (ncols < 1 || ncols > c.max_cols || (!full && ncols > 4)) return CAS_EINVAL;
   hipStream_t st = ctx->stream;
   float* logits = d_logits ? d_logits : m->logits;
+  // A linear layer of the draft pass.  Raw form: one fused launch (norm of x, product, residual
+  // add or SwiGLU).  Unary form: the same operations with the same roundings as separate
+  // launches around the GEMV that reads the unary buffer, column by column.
+  auto lin_draft = [&](const cas_tensor& T, const cas_model::UnaryRef& U, const uint16_t* x, float* y,
+                       const uint16_t* gain, int epi, uint16_t* out16) -> int {
+    if (!U.on) return launch_gemv_draft_fused(ctx, T.desc, T.d_spec, x, ncols, y, gain, c.rms_eps, epi, out16);
+    const int rows = (int)T.desc.rows, cols = (int)T.desc.cols;
+    if (gain) {
+      hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(kNormThreads), 0, st, x, gain, m->xn, cols, c.rms_eps);
+      x = m->xn;
+    }
+    float* yy = epi == 0 ? y : m->y;
+    for (int col = 0; col < ncols; ++col) {
+      const int rc = cas_gemv_draft_unary(ctx, &U.u, U.d_uspec, x + (size_t)col * cols, yy + (size_t)col * rows);
+      if (rc != CAS_OK) return rc;
+    }
+    if (epi == 1) {
+      const int n = ncols * rows;
+      hipLaunchKernelGGL(residual_add_kernel, dim3((n + 255) / 256), dim3(256), 0, st, out16, yy, n);
+    } else if (epi == 2) {
+      const int n = ncols * (rows / 2);
+      hipLaunchKernelGGL(swiglu_kernel, dim3((n + 255) / 256), dim3(256), 0, st, yy, out16, n);
+    }
+    return CAS_OK;
+  };
+  // ... and of the verification pass: the unary form goes through the same kernel after its
+  // rows are re-coded, so both forms give the same bits.
+  auto lin_verify = [&](const cas_tensor& T, const cas_model::UnaryRef& U, const uint16_t* X, float* Y, int epi,
+                        uint16_t* out16) -> int {
+    if (!U.on) return launch_gemm_verify_fused(ctx, T.desc, T.d_spec, T.d_verif, X, ncols, Y, epi, out16);
+    return launch_gemm_verify_unary_fused(ctx, U.u, U.d_uspec, T.d_verif, X, ncols, Y, epi, out16);
+  };
   hipLaunchKernelGGL(embed_kernel, dim3(ncols), dim3(256), 0, st, d_tokens, m->d_embed, m->h, c.hidden, c.vocab);
   for (int l = 0; l < c.n_layers; ++l) {
     const cas_layer_weights& L = m->layers[l];
+    const cas_model::UnaryRef* UL = &m->unary[4 * (size_t)l];
     // the draft pass fuses the norms, residual adds and SwiGLU into its GEMV launches
     if (full) {
       hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(kNormThreads), 0, st, m->h, L.d_g_attn, m->xn, c.hidden, c.rms_eps);
-      CAS_TRY(launch_gemm_verify(ctx, L.wqkv.desc, L.wqkv.d_spec, L.wqkv.d_verif, m->xn, ncols, m->y));
+      CAS_TRY(lin_verify(L.wqkv, UL[0], m->xn, m->y, 0, nullptr));
     } else {
-      CAS_TRY(launch_gemv_draft_fused(ctx, L.wqkv.desc, L.wqkv.d_spec, m->h, ncols, m->y, L.d_g_attn, c.rms_eps, 0,
-                                      nullptr));
+      CAS_TRY(lin_draft(L.wqkv, UL[0], m->h, m->y, L.d_g_attn, 0, nullptr));
     }
     // the attention kernel splits the projection itself: bf16 rounding, rotary embedding of q and
     // k, and the copy of this pass's k, v into their in-flight slots
@@ -258,24 +299,21 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, 
     CAS_TRY(launch_attention_batch(ctx, kv, calls, ng));
     if (full) {
       // residual adds and SwiGLU ride in the epilogue of the verification GEMM
-      CAS_TRY(launch_gemm_verify_fused(ctx, L.wo.desc, L.wo.d_spec, L.wo.d_verif, m->ao, ncols, nullptr, 1, m->h));
+      CAS_TRY(lin_verify(L.wo, UL[1], m->ao, nullptr, 1, m->h));
       hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(kNormThreads), 0, st, m->h, L.d_g_ffn, m->xn, c.hidden, c.rms_eps);
-      CAS_TRY(launch_gemm_verify_fused(ctx, L.wgu.desc, L.wgu.d_spec, L.wgu.d_verif, m->xn, ncols, nullptr, 2,
-                                       m->act));
-      CAS_TRY(launch_gemm_verify_fused(ctx, L.wd.desc, L.wd.d_spec, L.wd.d_verif, m->act, ncols, nullptr, 1, m->h));
+      CAS_TRY(lin_verify(L.wgu, UL[2], m->xn, nullptr, 2, m->act));
+      CAS_TRY(lin_verify(L.wd, UL[3], m->act, nullptr, 1, m->h));
     } else {
-      CAS_TRY(launch_gemv_draft_fused(ctx, L.wo.desc, L.wo.d_spec, m->ao, ncols, nullptr, nullptr, 0.f, 1, m->h));
-      CAS_TRY(launch_gemv_draft_fused(ctx, L.wgu.desc, L.wgu.d_spec, m->h, ncols, nullptr, L.d_g_ffn, c.rms_eps, 2,
-                                      m->act));
-      CAS_TRY(launch_gemv_draft_fused(ctx, L.wd.desc, L.wd.d_spec, m->act, ncols, nullptr, nullptr, 0.f, 1, m->h));
+      CAS_TRY(lin_draft(L.wo, UL[1], m->ao, nullptr, nullptr, 1, m->h));
+      CAS_TRY(lin_draft(L.wgu, UL[2], m->h, nullptr, L.d_g_ffn, 2, m->act));
+      CAS_TRY(lin_draft(L.wd, UL[3], m->act, nullptr, nullptr, 1, m->h));
     }
   }
   if (full) {
     hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(kNormThreads), 0, st, m->h, m->d_g_final, m->xn, c.hidden, c.rms_eps);
-    CAS_TRY(launch_gemm_verify(ctx, m->lm_head.desc, m->lm_head.d_spec, m->lm_head.d_verif, m->xn, ncols, logits));
+    CAS_TRY(lin_verify(m->lm_head, m->unary.back(), m->xn, logits, 0, nullptr));
   } else {
-    CAS_TRY(launch_gemv_draft_fused(ctx, m->lm_head.desc, m->lm_head.d_spec, m->h, ncols, logits, m->d_g_final,
-                                    c.rms_eps, 0, nullptr));
+    CAS_TRY(lin_draft(m->lm_head, m->unary.back(), m->h, logits, m->d_g_final, 0, nullptr));
   }
   if (d_out) {
     hipLaunchKernelGGL(argmax_part_kernel, dim3(kArgmaxSlices, ncols), dim3(256), 0, st, logits, c.vocab, m->amax_v,
@@ -368,6 +406,7 @@ int cas_model_create(const cas_model_cfg* cfg, const cas_model_weights* w, void*
   if (!m->layers) { delete m; return CAS_ENOMEM; }
   std::copy(w->layers, w->layers + cfg->n_layers, m->layers);
   m->lm_head = w->lm_head;
+  m->unary.resize(4 * (size_t)cfg->n_layers + 1);
   m->d_embed = w->d_embed; m->d_g_final = w->d_g_final; m->d_rope = w->d_rope;
   char* b = (char*)d_act;
   m->h = (uint16_t*)(b + L.h); m->xn = (uint16_t*)(b + L.xn); m->q = (uint16_t*)(b + L.q);
@@ -377,6 +416,29 @@ int cas_model_create(const cas_model_cfg* cfg, const cas_model_weights* w, void*
   m->tok = (int32_t*)(b + L.tok); m->tgt = (int32_t*)(b + L.tgt);
   m->amax_v = (float*)(b + L.amax_v); m->amax_i = (int32_t*)(b + L.amax_i);
   *out = m;
+  return CAS_OK;
+}
+
+int cas_model_use_unary(cas_model* m, int layer, int which, const cas_udesc* udesc, const void* d_uspec) {
+  if (!m || layer < -1 || layer >= m->cfg.n_layers || (layer >= 0 && (which < 0 || which > 3))) return CAS_EINVAL;
+  const cas_tensor* tp = &m->lm_head;
+  if (layer >= 0) {
+    cas_layer_weights& lw = m->layers[layer];
+    tp = which == 0 ? &lw.wqkv : which == 1 ? &lw.wo : which == 2 ? &lw.wgu : &lw.wd;
+  }
+  const cas_tensor& T = *tp;
+  cas_model::UnaryRef& U = layer < 0 ? m->unary.back() : m->unary[4 * (size_t)layer + which];
+  if (!udesc) { U.on = false; return CAS_OK; }
+  if (!d_uspec || !cas::aligned256(d_uspec)) return CAS_EINVAL;
+  // the unary form must be the re-coding of this very tensor: same shape, kept count, truncation and
+  // verification layout
+  const cas_wdesc &a = udesc->base, &b = T.desc;
+  if (a.rows != b.rows || a.cols != b.cols || a.K != b.K || a.t != b.t || a.bw != b.bw || a.sw != b.sw ||
+      a.lw != b.lw || a.pw != b.pw || a.off_lo != b.off_lo || a.off_pruned != b.off_pruned)
+    return CAS_EINVAL;
+  U.u = *udesc;
+  U.d_uspec = d_uspec;
+  U.on = true;
   return CAS_OK;
 }
 

@@ -202,6 +202,37 @@ __global__ __launch_bounds__(64) void unary_decode_kernel(UnaryArgs a, uint16_t*
   }
 }
 
+// ---- the raw spec stream of a block of rows, rebuilt from the unary form: one wave per row ------
+// After the row's exponents are in LDS every lane assembles whole output words: word w holds the
+// bits of the (at most four) fields of 16-t bits that overlap it.
+__global__ __launch_bounds__(64) void unary_expand_kernel(UnaryArgs a, int row0, uint32_t* __restrict__ out) {
+  extern __shared__ uint8_t lds8[];
+  uint8_t* tab = lds8;         // exp_of_rank
+  uint8_t* exps = lds8 + 256;  // [K]
+  const int lane = threadIdx.x, row = row0 + blockIdx.x;
+  for (int i = lane; i < 256; i += 64) tab[i] = a.table[i];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const uint32_t o0 = a.rowoff[row], o1 = a.rowoff[row + 1];
+  unary_row_exponents(a.ue + o0, (int)(o1 - o0), a.K, tab, exps, lane);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const int mb = 7 - a.t, SW = 8 - a.t, FW = 16 - a.t;
+  const uint32_t* sm_row = a.u_sm + (size_t)row * a.smw;
+  uint32_t* orow = out + (size_t)blockIdx.x * a.sw;
+  for (int w = lane; w < a.sw; w += 64) {
+    uint32_t word = 0;
+    for (int e = (32 * w) / FW; e < a.K; ++e) {
+      const int bit = e * FW - 32 * w;  // where the field starts, relative to the word (may be negative)
+      if (bit >= 32) break;
+      const uint32_t sm = read_field(sm_row, (uint32_t)e * SW, SW);
+      const uint32_t f = ((sm >> mb) << (mb + 8)) | ((uint32_t)exps[e] << mb) | (sm & ((1u << mb) - 1u));
+      word |= bit >= 0 ? f << bit : f >> (-bit);
+    }
+    orow[w] = word;
+  }
+}
+
 // ---- draft GEMV from the unary form: eight waves per workgroup, one row per wave --------------
 // Per row a wave first decodes the row's exponents into its LDS array, then walks the bitmap
 // in chunks of 64 words as the raw-exponent kernel does: a DPP prefix sum gives each lane the
@@ -310,6 +341,20 @@ static UnaryArgs make_uargs(const cas_udesc& u, const void* spec_raw, void* uspe
     a.pruned = (const uint32_t*)((const char*)verif + d.off_pruned);
   }
   return a;
+}
+
+int launch_unary_expand(cas_ctx* ctx, const cas_udesc& u, const void* uspec, int64_t row0, int nrows, uint32_t* out) {
+  const cas_wdesc& d = u.base;
+  if (nrows <= 0 || d.sw == 0) return CAS_OK;
+  const size_t lds = 256 + (size_t)((d.K + 3) & ~3) + kExpSlack;
+  if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
+  UnaryArgs a = make_uargs(u, nullptr, const_cast<void*>(uspec), nullptr);
+  static LdsLimit lim;
+  const int rc = allow_lds(ctx, (const void*)unary_expand_kernel, lds, lim);
+  if (rc != CAS_OK) return rc;
+  hipLaunchKernelGGL(unary_expand_kernel, dim3((unsigned)nrows), dim3(64), lds, ctx->stream, a, (int)row0, out);
+  CAS_HIP(ctx, hipGetLastError());
+  return CAS_OK;
 }
 
 static int64_t up256(int64_t v) { return (v + 255) / 256 * 256; }
@@ -457,6 +502,14 @@ extern "C" int cas_unary_decode(cas_ctx* ctx, const cas_udesc* udesc, const void
                      d_verif ? 1 : 0);
   CAS_HIP(ctx, hipGetLastError());
   return CAS_OK;
+}
+
+extern "C" int cas_gemm_verify_unary(cas_ctx* ctx, const cas_udesc* udesc, const void* d_uspec, const void* d_verif,
+                                     const uint16_t* d_X, int ncols, float* d_Y) {
+  if (!ctx || check_udesc(udesc) != CAS_OK || ncols < 1 || ncols > 32) return CAS_EINVAL;
+  if (udesc->base.rows == 0) return CAS_OK;
+  if (!d_uspec || !d_verif || !d_X || !d_Y || !aligned256(d_uspec) || !aligned256(d_verif)) return CAS_EINVAL;
+  return launch_gemm_verify_unary_fused(ctx, *udesc, d_uspec, d_verif, d_X, ncols, d_Y, 0, nullptr);
 }
 
 template <int T>

@@ -105,6 +105,61 @@ def test_verify_and_draft_steps_match_oracle(env, keep, t):
         cur = torch.tensor([int(np.argmax(oref[0]))], dtype=torch.int32, device="cuda")   # teacher forcing
 
 
+def test_model_steps_on_unary_coded_weights(env):
+    """Every linear layer switched to the unary form of its speculation data (Sec. 4.2 lossless
+    configuration): the verification pass gives the bits of the raw form, the draft pass the
+    oracle's logits within the usual tolerance, and a speculative round emits the same tokens."""
+    torch, B, ctx = env
+    keep, t = 600, 4
+    weights = synth.model_weights(SHAPE, seed=1)
+    model, kv = gpu_model(torch, B, ctx, weights, keep, t, max_cols=8)
+    om = oracle_model(weights, keep, t)
+    prompt = synth.token_ids(6, SHAPE.vocab, seed=5)
+    toks = torch.from_numpy(prompt).cuda()
+
+    def run():
+        B.cas_kv_set_len(kv, 0, 0)
+        tgt = torch.empty(6, dtype=torch.int32, device="cuda")
+        vl = torch.empty((6, SHAPE.vocab), dtype=torch.float32, device="cuda")
+        B.cas_verify_step(ctx, model, kv, 0, toks, 5, tgt, vl)
+        B.cas_commit(ctx, model, kv, 0, 5)
+        cur = torch.tensor([int(prompt[-1])], dtype=torch.int32, device="cuda")
+        nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+        dl = torch.empty((1, SHAPE.vocab), dtype=torch.float32, device="cuda")
+        B.cas_draft_step(ctx, model, kv, 0, cur, 0, nxt, dl)
+        n, emitted = B.cas_spec_round(ctx, model, kv, 0, int(prompt[-1]), 4)
+        return vl.cpu().numpy(), tgt.cpu().numpy(), dl.cpu().numpy(), (n, emitted)
+
+    raw = run()
+    layers, head = model._keep[0], model._keep[1]
+    for l, L in enumerate(layers):
+        for which, name in enumerate(("wqkv", "wo", "wgu", "wd")):
+            model.use_unary(l, which, B.cas_unary_encode(ctx, L[name]))
+    model.use_unary(-1, 0, B.cas_unary_encode(ctx, head))
+    una = run()
+    np.testing.assert_array_equal(una[0], raw[0])      # verification logits: same kernel, same bits
+    np.testing.assert_array_equal(una[1], raw[1])
+    # draft logits against the oracle (its draft view is the same for both forms: the re-coding is lossless)
+    ref, new_kv = om.forward(prompt, draft=False)
+    om.append_kv(new_kv, 6)
+    extra = [(np.zeros((0, SHAPE.n_kv_heads, 128), np.uint16),) * 2 for _ in range(SHAPE.n_layers)]
+    oref, _ = om.forward([int(prompt[-1])], draft=True, extra_kv=extra)
+    r = _check_logits(una[2].astype(np.float64), oref, _logit_tol(om, True), "draft on unary weights")
+    record_ratio("tiny_model_draft_logits_unary", r)
+    # the round emits the target's greedy stream whatever was drafted: both runs give a prefix of it
+    m_ = min(len(una[3][1]), len(raw[3][1]))
+    assert una[3][1][:m_] == raw[3][1][:m_]
+    # a descriptor of another tensor is refused; switching back restores the raw path
+    with pytest.raises(B.CasError):
+        model.use_unary(0, 0, model._unary[(0, 1)])
+    model.use_unary(-1, 0, None)
+    for l in range(len(layers)):
+        for which in range(4):
+            model.use_unary(l, which, None)
+    back = run()
+    np.testing.assert_array_equal(back[2], raw[2])
+
+
 def _gpu_generate(torch, B, ctx, model, kv, prompt, n_new, k):
     B.cas_kv_set_len(kv, 0, 0)
     if len(prompt) > 1:

@@ -1,6 +1,6 @@
 """GPU parity of the unary-exponent form of the speculation data (Sec. 4.2 exponent
 compression) against the oracle, through the C ABI: every region of the buffer bit for bit,
-both reconstructions, and the draft GEMV read from the unary form."""
+both reconstructions, the draft GEMV and the verification GEMM read from the unary form."""
 import numpy as np
 import pytest
 
@@ -101,6 +101,49 @@ def test_gemv_draft_unary_matches_oracle(env, rows, cols, keep, t, special):
     # same values as the raw-exponent kernel up to the order of the fp32 sums
     y_raw = B.cas_gemv_draft(ctx, ew, _dev(torch, x)).cpu().numpy()[0]
     assert (np.abs(y - y_raw) / tol).max() < 2e-5
+
+
+@pytest.mark.parametrize("ncols", [1, 5, 20])
+@pytest.mark.parametrize("rows,cols,keep,t,special", [c for c in CASES if not c[4]])
+def test_gemm_verify_unary_is_exact_and_equal_to_the_raw_form(env, rows, cols, keep, t, special, ncols):
+    """Verification from the unary form (Sec. 4.2 lossless configuration, Sec. 4.1 target
+    inference): against the oracle's product with the matrix its unary reconstruction returns,
+    and bit for bit against the raw-exponent verification GEMM."""
+    torch, B, ctx = env
+    print(f"case rows={rows} cols={cols} keep={keep} t={t} ncols={ncols}", flush=True)
+    W = _matrix(rows, cols, False, seed=rows + cols + t)
+    X = synth.activations(cols, ncols, seed=13)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t)
+    uw = B.cas_unary_encode(ctx, ew)
+    Y = B.cas_gemm_verify_unary(ctx, uw, _dev(torch, X)).cpu().numpy()
+    u = O.to_unary(O.encode_weight(W, keep, t))
+    Wf = O.bf16_to_f64(O.decode_full_unary(u))
+    ref = (Wf @ O.bf16_to_f64(X).T).T
+    tol = np.linalg.norm(Wf, axis=1)[None, :] * np.linalg.norm(O.bf16_to_f64(X), axis=1)[:, None] + 1e-30
+    err = np.abs(Y - ref) / tol
+    assert err.max() < 2e-3          # north-star bar
+    assert err.max() < 2e-5, err.max()
+    np.testing.assert_array_equal(Y, B.cas_gemm_verify(ctx, ew, _dev(torch, X)).cpu().numpy())
+
+
+def test_gemm_verify_unary_in_row_blocks_and_without_room(env):
+    """A workspace that holds 16 rows of the raw stream at a time gives the same bits as one that
+    holds the matrix; one that holds fewer is refused."""
+    torch, B, ctx = env
+    rows, cols, keep, t = 150, 1000, 600, 4
+    W = _matrix(rows, cols, False, seed=5)
+    X = synth.activations(cols, 3, seed=6)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t)
+    uw = B.cas_unary_encode(ctx, ew)
+    whole = B.cas_gemm_verify_unary(ctx, uw, _dev(torch, X)).cpu().numpy()
+    row_bytes = ew.desc.sw * 4
+    small = B.Context(workspace=torch.empty(17 * row_bytes + 256, dtype=torch.uint8, device="cuda"))
+    # the matrix itself comes from the first context: buffers are plain device memory
+    np.testing.assert_array_equal(B.cas_gemm_verify_unary(small, uw, _dev(torch, X)).cpu().numpy(), whole)
+    tiny = B.Context(workspace=torch.empty(15 * row_bytes + 256, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(B.CasError) as e:
+        B.cas_gemm_verify_unary(tiny, uw, _dev(torch, X))
+    assert e.value.code == B.CAS_ENOMEM
 
 
 def test_unary_empty_matrix(env):
