@@ -258,6 +258,16 @@ int cas_mx_decode(cas_ctx* ctx, const cas_mxdesc* mx, const void* d_mxspec, cons
 int cas_gemv_draft_mx(cas_ctx* ctx, const cas_mxdesc* mx, const void* d_mxspec, const uint16_t* d_x,
                       float* d_y);
 
+/* Verification GEMM Y = W' X on the shared-exponent form, W' being the CONVERTED matrix (what
+ * cas_mx_decode returns with d_mxverif): the target model of a deployment that uses this
+ * format (Sec. 4.2: the conversion is lossy against the original weights, speculation against
+ * the converted model stays lossless).  Blocks of rows are written as raw spec and lo streams
+ * into the workspace and multiplied by the kernel of cas_gemm_verify.  d_X: bf16 [ncols][cols];
+ * d_Y: float [ncols][rows]; 1 <= ncols <= 32.  Workspace: at least 16 * (sw + lw) * 4 + 1024
+ * bytes; CAS_ENOMEM if less, CAS_ENOTSUP if one row of both streams does not fit the LDS. */
+int cas_gemm_verify_mx(cas_ctx* ctx, const cas_mxdesc* mx, const void* d_mxspec, const void* d_mxverif,
+                       const uint16_t* d_X, int ncols, float* d_Y);
+
 /* ---- compressed, paged KV cache (Sec. 4.2 per-token pruning, Sec. 5.1 online encoder) ---- */
 
 /*
@@ -428,6 +438,16 @@ int cas_model_destroy(cas_model* model);
  * CAS_EINVAL if the descriptor does not belong to the tensor.  The context's workspace must
  * hold 16 rows of the largest raw spec stream plus 256 bytes for the verification passes. */
 int cas_model_use_unary(cas_model* model, int layer, int which, const cas_udesc* udesc, const void* d_uspec);
+
+/* Switches one linear layer to the shared-exponent form (Sec. 4.2, the MX approach).  The
+ * layer's weight is from then on the CONVERTED matrix: draft passes read d_mxspec through the
+ * kernel of cas_gemv_draft_mx (with the fused norm / residual / SwiGLU of the raw form),
+ * verification passes go through cas_gemm_verify_mx, and a speculative round emits exactly what
+ * plain decoding with the converted weights emits.  Arguments as for cas_model_use_unary;
+ * mx = NULL switches back; one form at a time per tensor (the last call wins).  Workspace as
+ * for cas_gemm_verify_mx. */
+int cas_model_use_mx(cas_model* model, int layer, int which, const cas_mxdesc* mx, const void* d_mxspec,
+                     const void* d_mxverif);
 
 /* One draft pass (Sec. 4.1 draft inference): speculation data only for every linear layer and
  * for the cache.  d_token_in: the token at in-flight slot `slot` (position len + slot);

@@ -634,7 +634,12 @@ class OracleModel:
     """
 
     def __init__(self, shape, weights, rope_tab, w_keep=600, w_t=4, kv_keep=600, kv_t=4,
-                 act_norms=None):
+                 act_norms=None, exp_mode="raw"):
+        """exp_mode "raw": exponents stored as they are (also stands for the unary form, which is
+        a lossless re-coding of the same data).  "mx": every linear layer in the shared-exponent
+        form of Sec. 4.2; the target model is then the converted one."""
+        assert exp_mode in ("raw", "mx")
+        self.exp_mode = exp_mode
         self.s = shape
         self.rope_tab = rope_tab
         self.kv_keep, self.kv_t = kv_keep, kv_t
@@ -658,7 +663,11 @@ class OracleModel:
         key = (layer, name, draft)
         if key not in self._dec:
             p = self.lm_head if layer is None else self.layers[layer][name]
-            self._dec[key] = bf16_to_f64(decode_draft(p) if draft else decode_full(p))
+            if self.exp_mode == "mx":
+                mxp = to_mx(p)
+                self._dec[key] = bf16_to_f64(decode_draft_mx(mxp) if draft else decode_full_mx(mxp))
+            else:
+                self._dec[key] = bf16_to_f64(decode_draft(p) if draft else decode_full(p))
         return self._dec[key]
 
     def cache_len(self):

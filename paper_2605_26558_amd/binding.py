@@ -164,6 +164,9 @@ _SIGNATURES = {
     "cas_mx_encode": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "cas_mx_decode": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
     "cas_gemv_draft_mx": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p]),
+    "cas_gemm_verify_mx": (C.c_int, [C.c_void_p, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                   C.c_void_p]),
+    "cas_model_use_mx": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(cas_mxdesc), C.c_void_p, C.c_void_p]),
 }
 
 
@@ -430,6 +433,18 @@ def cas_gemv_draft_mx(ctx: Context, mw: MxWeight, x, out=None):
     return out
 
 
+def cas_gemm_verify_mx(ctx: Context, mw: MxWeight, X, out=None):
+    """X: bf16 bits [ncols, cols] -> float32 [ncols, rows]; the weight is the converted matrix."""
+    torch = ctx._torch
+    d = mw.desc.base
+    assert X.dim() == 2 and X.shape[1] == d.cols and X.is_contiguous() and X.element_size() == 2
+    if out is None:
+        out = torch.empty((X.shape[0], d.rows), dtype=torch.float32, device=X.device)
+    ctx._check(_lib().cas_gemm_verify_mx(ctx.h, C.byref(mw.desc), _ptr(mw.spec), _ptr(mw.verif), _ptr(X), X.shape[0],
+                                         _ptr(out)), "cas_gemm_verify_mx")
+    return out
+
+
 def cas_decode_weight(ctx: Context, ew: EncodedWeight, full: bool):
     torch = ctx._torch
     out = torch.empty((ew.desc.rows, ew.desc.cols), dtype=torch.int16, device=ew.spec.device)
@@ -643,6 +658,17 @@ class Model:
             raise CasError(rc, "cas_model_use_unary")
         self._unary = getattr(self, "_unary", {})
         self._unary[(layer, which if layer >= 0 else 0)] = uw   # keeps the buffer alive
+
+    def use_mx(self, layer: int, which: int, mw=None):
+        """Switch a linear layer to the shared-exponent form `mw` (MxWeight): its weight becomes the
+        converted matrix.  None switches back to the raw form."""
+        rc = _lib().cas_model_use_mx(self.h, layer, which, C.byref(mw.desc) if mw is not None else None,
+                                     _ptr(mw.spec) if mw is not None else None,
+                                     _ptr(mw.verif) if mw is not None else None)
+        if rc != CAS_OK:
+            raise CasError(rc, "cas_model_use_mx")
+        self._mx = getattr(self, "_mx", {})
+        self._mx[(layer, which if layer >= 0 else 0)] = mw   # keeps the buffers alive
 
     def close(self):
         if getattr(self, "h", None):

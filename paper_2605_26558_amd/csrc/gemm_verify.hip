@@ -95,4 +95,42 @@ int launch_gemm_verify_unary_fused(cas_ctx* ctx, const cas_udesc& u, const void*
   return CAS_OK;
 }
 
+// ... and in the shared-exponent form (Sec. 4.2, the MX approach): W is the CONVERTED matrix.  Blocks
+// of rows are written as raw spec and lo streams of that matrix into the workspace; bitmap and
+// pruned values are read in place.
+int launch_gemm_verify_mx_fused(cas_ctx* ctx, const cas_mxdesc& x, const void* mxspec, const void* mxverif,
+                                const uint16_t* X, int ncols, float* Y, int epi, uint16_t* out16) {
+  const cas_wdesc& d = x.base;
+  if (d.rows <= 0) return CAS_OK;
+  if (epi == 2 && (d.rows & 1)) return CAS_EINVAL;
+  const size_t row_bytes = (size_t)(d.sw + d.lw) * 4;
+  int64_t blk = row_bytes ? (ctx->ws_bytes > 1024 ? (int64_t)((ctx->ws_bytes - 1024) / row_bytes) : 0) : d.rows;
+  blk = std::min<int64_t>(blk, d.rows);
+  if (blk < d.rows) blk = blk / 16 * 16;
+  if (blk < 1 || (row_bytes > 0 && !ctx->d_ws)) return CAS_ENOMEM;
+  uint32_t* ws_spec = (uint32_t*)ctx->d_ws;
+  // behind the spec block and its slack, on a 256-byte boundary
+  uint32_t* ws_lo = (uint32_t*)((char*)ctx->d_ws + ((size_t)blk * d.sw * 4 + 256 + 255) / 256 * 256);
+  ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + x.fw + d.lw + d.pw) + (double)d.rows * x.ew);
+  for (int64_t r0 = 0; r0 < d.rows; r0 += blk) {
+    const int nr = (int)std::min<int64_t>(blk, d.rows - r0);
+    int rc = launch_mx_expand(ctx, x, mxspec, mxverif, r0, nr, ws_spec, ws_lo);
+    if (rc != CAS_OK) return rc;
+    VerifyArgs a;
+    a.epi = epi;
+    a.rows = nr; a.cols = (int)d.cols; a.bw = d.bw; a.sw = d.sw; a.lw = d.lw; a.pw = d.pw;
+    a.ncols = ncols;
+    a.bitmap = (const uint32_t*)((const char*)mxspec + x.off_bitmap) + (size_t)r0 * d.bw;
+    a.spec = ws_spec;
+    a.lo = ws_lo;
+    a.pruned = (const uint32_t*)((const char*)mxverif + x.off_pruned) + (size_t)r0 * d.pw;
+    a.X = X; a.yld = (int)d.rows;
+    a.Y = Y ? Y + r0 : nullptr;
+    a.out16 = out16 ? out16 + (epi == 2 ? r0 / 2 : r0) : nullptr;
+    rc = launch_verify_args(ctx, a, d.t);
+    if (rc != CAS_OK) return rc;
+  }
+  return CAS_OK;
+}
+
 }  // namespace cas

@@ -23,10 +23,15 @@ struct cas_model {
   int32_t* amax_i;
   // Linear layers switched to the unary form of their speculation data (cas_model_use_unary):
   // entry 4 * layer + {0 wqkv, 1 wo, 2 wgu, 3 wd}, the output head last.
+  // or to the shared-exponent form of the tensor (cas_model_use_mx): then the converted matrix is the weight
   struct UnaryRef {
-    bool on = false;
+    bool on = false;   // unary form
     cas_udesc u;
     const void* d_uspec = nullptr;
+    bool mx_on = false;  // shared-exponent form
+    cas_mxdesc mx;
+    const void* d_mxspec = nullptr;
+    const void* d_mxverif = nullptr;
   };
   std::vector<UnaryRef> unary;
 };
@@ -244,8 +249,17 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, 
   // launches around the GEMV that reads the unary buffer, column by column.
   auto lin_draft = [&](const cas_tensor& T, const cas_model::UnaryRef& U, const uint16_t* x, float* y,
                        const uint16_t* gain, int epi, uint16_t* out16) -> int {
-    if (!U.on) return launch_gemv_draft_fused(ctx, T.desc, T.d_spec, x, ncols, y, gain, c.rms_eps, epi, out16);
     const int rows = (int)T.desc.rows, cols = (int)T.desc.cols;
+    if (U.mx_on) {  // the kernel of the raw form with the shared-exponent field decode, one column per launch
+      for (int col = 0; col < ncols; ++col) {
+        const int rc = launch_gemv_draft_mx_fused(ctx, U.mx, U.d_mxspec, x + (size_t)col * cols,
+                                                  y ? y + (size_t)col * rows : nullptr, gain, c.rms_eps, epi,
+                                                  out16 ? out16 + (size_t)col * (epi == 2 ? rows / 2 : rows) : nullptr);
+        if (rc != CAS_OK) return rc;
+      }
+      return CAS_OK;
+    }
+    if (!U.on) return launch_gemv_draft_fused(ctx, T.desc, T.d_spec, x, ncols, y, gain, c.rms_eps, epi, out16);
     if (gain) {
       hipLaunchKernelGGL(rmsnorm_kernel, dim3(ncols), dim3(kNormThreads), 0, st, x, gain, m->xn, cols, c.rms_eps);
       x = m->xn;
@@ -268,6 +282,7 @@ static int forward(cas_ctx* ctx, cas_model* m, cas_kv* kv, const ColGroup* grp, 
   // rows are re-coded, so both forms give the same bits.
   auto lin_verify = [&](const cas_tensor& T, const cas_model::UnaryRef& U, const uint16_t* X, float* Y, int epi,
                         uint16_t* out16) -> int {
+    if (U.mx_on) return launch_gemm_verify_mx_fused(ctx, U.mx, U.d_mxspec, U.d_mxverif, X, ncols, Y, epi, out16);
     if (!U.on) return launch_gemm_verify_fused(ctx, T.desc, T.d_spec, T.d_verif, X, ncols, Y, epi, out16);
     return launch_gemm_verify_unary_fused(ctx, U.u, U.d_uspec, T.d_verif, X, ncols, Y, epi, out16);
   };
@@ -419,26 +434,54 @@ int cas_model_create(const cas_model_cfg* cfg, const cas_model_weights* w, void*
   return CAS_OK;
 }
 
-int cas_model_use_unary(cas_model* m, int layer, int which, const cas_udesc* udesc, const void* d_uspec) {
-  if (!m || layer < -1 || layer >= m->cfg.n_layers || (layer >= 0 && (which < 0 || which > 3))) return CAS_EINVAL;
-  const cas_tensor* tp = &m->lm_head;
+// the tensor (layer, which) of the model and its alternative-form record; false if there is none
+static bool model_tensor(cas_model* m, int layer, int which, const cas_tensor** T, cas_model::UnaryRef** U) {
+  if (!m || layer < -1 || layer >= m->cfg.n_layers || (layer >= 0 && (which < 0 || which > 3))) return false;
+  *T = &m->lm_head;
   if (layer >= 0) {
     cas_layer_weights& lw = m->layers[layer];
-    tp = which == 0 ? &lw.wqkv : which == 1 ? &lw.wo : which == 2 ? &lw.wgu : &lw.wd;
+    *T = which == 0 ? &lw.wqkv : which == 1 ? &lw.wo : which == 2 ? &lw.wgu : &lw.wd;
   }
-  const cas_tensor& T = *tp;
-  cas_model::UnaryRef& U = layer < 0 ? m->unary.back() : m->unary[4 * (size_t)layer + which];
-  if (!udesc) { U.on = false; return CAS_OK; }
+  *U = layer < 0 ? &m->unary.back() : &m->unary[4 * (size_t)layer + which];
+  return true;
+}
+
+// another form must be the re-coding of this very tensor: same shape, kept count, truncation, stream widths
+static bool same_matrix(const cas_wdesc& a, const cas_wdesc& b) {
+  return a.rows == b.rows && a.cols == b.cols && a.K == b.K && a.t == b.t && a.bw == b.bw && a.sw == b.sw &&
+         a.lw == b.lw && a.pw == b.pw;
+}
+
+int cas_model_use_unary(cas_model* m, int layer, int which, const cas_udesc* udesc, const void* d_uspec) {
+  const cas_tensor* T;
+  cas_model::UnaryRef* U;
+  if (!model_tensor(m, layer, which, &T, &U)) return CAS_EINVAL;
+  if (!udesc) { U->on = false; return CAS_OK; }
   if (!d_uspec || !cas::aligned256(d_uspec)) return CAS_EINVAL;
-  // the unary form must be the re-coding of this very tensor: same shape, kept count, truncation and
-  // verification layout
-  const cas_wdesc &a = udesc->base, &b = T.desc;
-  if (a.rows != b.rows || a.cols != b.cols || a.K != b.K || a.t != b.t || a.bw != b.bw || a.sw != b.sw ||
-      a.lw != b.lw || a.pw != b.pw || a.off_lo != b.off_lo || a.off_pruned != b.off_pruned)
+  // ... and the verification data stays the tensor's own
+  if (!same_matrix(udesc->base, T->desc) || udesc->base.off_lo != T->desc.off_lo ||
+      udesc->base.off_pruned != T->desc.off_pruned)
     return CAS_EINVAL;
-  U.u = *udesc;
-  U.d_uspec = d_uspec;
-  U.on = true;
+  U->u = *udesc;
+  U->d_uspec = d_uspec;
+  U->on = true;
+  U->mx_on = false;
+  return CAS_OK;
+}
+
+int cas_model_use_mx(cas_model* m, int layer, int which, const cas_mxdesc* mx, const void* d_mxspec,
+                     const void* d_mxverif) {
+  const cas_tensor* T;
+  cas_model::UnaryRef* U;
+  if (!model_tensor(m, layer, which, &T, &U)) return CAS_EINVAL;
+  if (!mx) { U->mx_on = false; return CAS_OK; }
+  if (!d_mxspec || !d_mxverif || !cas::aligned256(d_mxspec) || !cas::aligned256(d_mxverif)) return CAS_EINVAL;
+  if (!cas::mxdesc_ok(mx) || !same_matrix(mx->base, T->desc)) return CAS_EINVAL;
+  U->mx = *mx;
+  U->d_mxspec = d_mxspec;
+  U->d_mxverif = d_mxverif;
+  U->mx_on = true;
+  U->on = false;
   return CAS_OK;
 }
 

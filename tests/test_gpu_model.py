@@ -160,6 +160,45 @@ def test_model_steps_on_unary_coded_weights(env):
     np.testing.assert_array_equal(back[2], raw[2])
 
 
+def test_model_steps_on_shared_exponent_weights(env):
+    """Every linear layer in the shared-exponent form (Sec. 4.2, the MX approach): the target is
+    the converted model.  Verification and draft logits against the oracle run in that mode."""
+    torch, B, ctx = env
+    keep, t = 600, 4
+    weights = synth.model_weights(SHAPE, seed=1)
+    model, kv = gpu_model(torch, B, ctx, weights, keep, t, max_cols=8)
+    layers, head = model._keep[0], model._keep[1]
+    for l, L in enumerate(layers):
+        for which, name in enumerate(("wqkv", "wo", "wgu", "wd")):
+            model.use_mx(l, which, B.cas_mx_encode(ctx, L[name]))
+    model.use_mx(-1, 0, B.cas_mx_encode(ctx, head))
+    tab = synth.rope_table(MAX_POS, SHAPE.head_dim, SHAPE.rope_theta)
+    om = O.OracleModel(SHAPE, weights, tab, w_keep=keep, w_t=t, kv_keep=keep, kv_t=t, exp_mode="mx")
+    prompt = synth.token_ids(6, SHAPE.vocab, seed=5)
+    toks = torch.from_numpy(prompt).cuda()
+    tgt = torch.empty(6, dtype=torch.int32, device="cuda")
+    vl = torch.empty((6, SHAPE.vocab), dtype=torch.float32, device="cuda")
+    B.cas_verify_step(ctx, model, kv, 0, toks, 5, tgt, vl)
+    ref, new_kv = om.forward(prompt, draft=False)
+    r = _check_logits(vl.cpu().numpy().astype(np.float64), ref, _logit_tol(om, False), "verify, shared exponents")
+    record_ratio("tiny_model_verify_logits_mx", r)
+    B.cas_commit(ctx, model, kv, 0, 5)
+    om.append_kv(new_kv, 6)
+    cur = torch.tensor([int(np.argmax(ref[5]))], dtype=torch.int32, device="cuda")
+    nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+    dl = torch.empty((1, SHAPE.vocab), dtype=torch.float32, device="cuda")
+    B.cas_draft_step(ctx, model, kv, 0, cur, 0, nxt, dl)
+    extra = [(np.zeros((0, SHAPE.n_kv_heads, 128), np.uint16),) * 2 for _ in range(SHAPE.n_layers)]
+    oref, _ = om.forward([int(cur.item())], draft=True, extra_kv=extra)
+    r = _check_logits(dl.cpu().numpy().astype(np.float64), oref, _logit_tol(om, True), "draft, shared exponents")
+    record_ratio("tiny_model_draft_logits_mx", r)
+    # speculation against the converted model is lossless: the stream of rounds equals plain decoding
+    gen_prompt = synth.token_ids(5, SHAPE.vocab, seed=9)
+    plain, _ = _gpu_generate(torch, B, ctx, model, kv, gen_prompt, 16, 0)
+    spec, stats = _gpu_generate(torch, B, ctx, model, kv, gen_prompt, 16, 4)
+    assert spec == plain, (spec, plain)
+
+
 def _gpu_generate(torch, B, ctx, model, kv, prompt, n_new, k):
     B.cas_kv_set_len(kv, 0, 0)
     if len(prompt) > 1:

@@ -1,6 +1,7 @@
 """GPU parity of the shared-exponent (MX) form of the speculation data (Sec. 4.2 exponent
 compression, first approach; Sec. 5.1 decoder #N) against the oracle, through the C ABI: every
-region of both buffers bit for bit, both reconstructions, and the draft GEMV."""
+region of both buffers bit for bit, both reconstructions, the draft GEMV and the verification
+GEMM on the converted matrix."""
 import numpy as np
 import pytest
 
@@ -14,7 +15,7 @@ pytestmark = pytest.mark.gpu
 def env():
     import torch
     from paper_2605_26558_amd import binding as B
-    return torch, B, B.Context()
+    return torch, B, B.Context(workspace=torch.empty(8 << 20, dtype=torch.uint8, device="cuda"))
 
 
 def _dev(torch, a):
@@ -115,6 +116,53 @@ def test_gemv_draft_mx_tiny_magnitudes(env):
     assert np.abs(ref).max() > 0
     tol = np.linalg.norm(O.bf16_to_f64(W), axis=1) * np.linalg.norm(O.bf16_to_f64(x[0]))
     assert (np.abs(y - ref) <= 2e-5 * tol + 2.0 ** -149).all()
+
+
+@pytest.mark.parametrize("ncols", [1, 5, 20])
+@pytest.mark.parametrize("rows,cols,keep,t,special", [c for c in CASES if not c[4]])
+def test_gemm_verify_mx_is_the_product_with_the_converted_matrix(env, rows, cols, keep, t, special, ncols):
+    """Verification on the shared-exponent form (Sec. 4.2 MX approach under Sec. 4.1 target
+    inference): Y = W' X with W' the oracle's converted matrix."""
+    torch, B, ctx = env
+    print(f"case rows={rows} cols={cols} keep={keep} t={t} ncols={ncols}", flush=True)
+    W = _matrix(rows, cols, False, seed=rows + cols + t)
+    X = synth.activations(cols, ncols, seed=13)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t)
+    mw = B.cas_mx_encode(ctx, ew)
+    Y = B.cas_gemm_verify_mx(ctx, mw, _dev(torch, X)).cpu().numpy()
+    Wc = O.decode_full_mx(O.to_mx(O.encode_weight(W, keep, t)))
+    Wf = O.bf16_to_f64(Wc)
+    ref = (Wf @ O.bf16_to_f64(X).T).T
+    tol = np.linalg.norm(Wf, axis=1)[None, :] * np.linalg.norm(O.bf16_to_f64(X), axis=1)[:, None] + 1e-30
+    err = np.abs(Y - ref) / tol
+    assert err.max() < 2e-3          # north-star bar
+    assert err.max() < 2e-5, err.max()
+    # a unit vector picks one column of the converted matrix: exact, every bit of the re-coding counts
+    if ncols == 5:
+        picks = sorted({0, cols - 1, cols // 2, min(33, cols - 1), min(31, cols - 1)})[:5]
+        U = np.zeros((len(picks), cols), dtype=np.uint16)
+        for i, j in enumerate(picks):
+            U[i, j] = 0x3F80
+        Yu = B.cas_gemm_verify_mx(ctx, mw, _dev(torch, U)).cpu().numpy()
+        for i, j in enumerate(picks):
+            np.testing.assert_array_equal(Yu[i], O.bf16_to_f64(Wc[:, j]).astype(np.float32))
+
+
+def test_gemm_verify_mx_in_row_blocks_and_without_room(env):
+    torch, B, ctx = env
+    rows, cols, keep, t = 150, 1000, 600, 4
+    W = _matrix(rows, cols, False, seed=5)
+    X = synth.activations(cols, 3, seed=6)
+    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t)
+    mw = B.cas_mx_encode(ctx, ew)
+    whole = B.cas_gemm_verify_mx(ctx, mw, _dev(torch, X)).cpu().numpy()
+    row_bytes = (ew.desc.sw + ew.desc.lw) * 4
+    small = B.Context(workspace=torch.empty(17 * row_bytes + 1024, dtype=torch.uint8, device="cuda"))
+    np.testing.assert_array_equal(B.cas_gemm_verify_mx(small, mw, _dev(torch, X)).cpu().numpy(), whole)
+    tiny = B.Context(workspace=torch.empty(15 * row_bytes + 1024, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(B.CasError) as e:
+        B.cas_gemm_verify_mx(tiny, mw, _dev(torch, X))
+    assert e.value.code == B.CAS_ENOMEM
 
 
 def test_mx_empty_matrix(env):

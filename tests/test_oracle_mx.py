@@ -153,3 +153,36 @@ def test_only_kept_values_set_the_shared_exponent():
     m = O.to_mx(O.pack(w, mask, 4))
     assert (m.sexp == 120).all()
     np.testing.assert_array_equal(O.decode_full_mx(m), w)
+
+
+def test_model_in_shared_exponent_mode_reduces_to_the_raw_mode_when_blocks_have_one_exponent():
+    """The shared-exponent mode of the oracle's model (Sec. 4.2, the MX approach: the converted
+    matrices are the weights) must give the raw mode's logits, draft and target, bit for bit when
+    no block loses anything: every 32-column block of every row holds a single exponent."""
+    shape = synth.TINY
+    weights = synth.model_weights(shape, seed=4)
+    rng = np.random.default_rng(8)
+
+    def one_exponent_per_block(w):
+        rows, cols = w.shape
+        nb = (cols + 31) // 32
+        exps = rng.integers(118, 123, (rows, nb)).repeat(32, axis=1)[:, :cols].astype(np.uint16)
+        return ((w & 0x807F) | (exps << 7)).astype(np.uint16)
+
+    for lw in weights["layers"]:
+        for name in ("wqkv", "wo", "wgu", "wd"):
+            lw[name] = one_exponent_per_block(lw[name])
+    weights["lm_head"] = one_exponent_per_block(weights["lm_head"])
+    tab = synth.rope_table(32, shape.head_dim, shape.rope_theta)
+    raw = O.OracleModel(shape, weights, tab, w_keep=600, w_t=4, exp_mode="raw")
+    mx = O.OracleModel(shape, weights, tab, w_keep=600, w_t=4, exp_mode="mx")
+    toks = synth.token_ids(3, shape.vocab, seed=2)
+    for draft in (False, True):
+        a, _ = raw.forward(toks, draft=draft)
+        b, _ = mx.forward(toks, draft=draft)
+        np.testing.assert_array_equal(a, b)
+    # ... and differs from it on ordinary weights (the mode is really switched on)
+    weights2 = synth.model_weights(shape, seed=4)
+    a, _ = O.OracleModel(shape, weights2, tab, exp_mode="raw").forward(toks, draft=False)
+    b, _ = O.OracleModel(shape, weights2, tab, exp_mode="mx").forward(toks, draft=False)
+    assert np.abs(a - b).max() > 0
