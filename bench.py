@@ -40,11 +40,12 @@ def parse():
     ap.add_argument("--context", type=int, default=8192, help="committed KV positions when a step starts")
     ap.add_argument("--batch", type=int, default=1,
                     help="sequences decoded together (1..4, batch * (k + 1) <= 16); 1 is the configuration of the metric")
-    ap.add_argument("--workload", choices=["model", "linear", "probe-linear", "probe-attn", "tune", "cpu-units"], default="model",
+    ap.add_argument("--workload", choices=["model", "linear", "probe-linear", "probe-attn", "tune", "exp-modes", "cpu-units"], default="model",
                     help="model: the metric's workload; linear: the linear layers alone; probe-*: short fixed "
                          "launch sequences for hardware-counter runs (no JSON line, see workload.py); cpu-units: the "
                          "oracle's time for whole units of the workload, host only, minutes; tune: format "
-                         "search on measured draft / verification pass times with user-supplied acceptance rates")
+                         "search on measured draft / verification pass times with user-supplied acceptance rates; "
+                         "exp-modes: pass times with raw, unary-coded and shared exponents on the same model")
     ap.add_argument("--alpha", type=float, default=0.8, help="tune: acceptance rate assumed for every grid point")
     ap.add_argument("--alpha-grid", default=None, help="tune: JSON file with a [n_keep][n_trunc] table of acceptance rates")
     ap.add_argument("--tune-keeps", default="700,600,500,400", help="tune: kept fractions in 1/1000 (Sec. 7.2.2 grid)")
@@ -222,7 +223,7 @@ def main():
         cpu_units(args.keep, args.trunc)
         return
     # the CPU oracle first: its worker processes are spawned before this process touches the GPU
-    cpu = None if args.no_cpu_baseline or args.workload.startswith("probe") or args.workload == "tune" else \
+    cpu = None if args.no_cpu_baseline or args.workload.startswith("probe") or args.workload in ("tune", "exp-modes") else \
         cpu_baseline(args.keep, args.trunc, args.k, args.context)
     import torch
     from paper_2605_26558_amd import binding as B
@@ -232,6 +233,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.workload.startswith("probe"):
         workload.run_probe(B, args)
+        return
+    if args.workload == "exp-modes":
+        workload.run_exp_modes(B, args, dev)
         return
     if args.workload == "tune":
         workload.run_tune(B, args, dev)

@@ -261,10 +261,9 @@ int cas_gemv_draft_mx(cas_ctx* ctx, const cas_mxdesc* mx, const void* d_mxspec, 
 /* Verification GEMM Y = W' X on the shared-exponent form, W' being the CONVERTED matrix (what
  * cas_mx_decode returns with d_mxverif): the target model of a deployment that uses this
  * format (Sec. 4.2: the conversion is lossy against the original weights, speculation against
- * the converted model stays lossless).  Blocks of rows are written as raw spec and lo streams
- * into the workspace and multiplied by the kernel of cas_gemm_verify.  d_X: bf16 [ncols][cols];
- * d_Y: float [ncols][rows]; 1 <= ncols <= 32.  Workspace: at least 16 * (sw + lw) * 4 + 1024
- * bytes; CAS_ENOMEM if less, CAS_ENOTSUP if one row of both streams does not fit the LDS. */
+ * the converted model stays lossless).  The kernel of cas_gemm_verify with the kept values
+ * rebuilt from sign, magnitude and block exponent inside the walk; a column gets the same bits
+ * whatever rides along.  d_X: bf16 [ncols][cols]; d_Y: float [ncols][rows]; 1 <= ncols <= 32. */
 int cas_gemm_verify_mx(cas_ctx* ctx, const cas_mxdesc* mx, const void* d_mxspec, const void* d_mxverif,
                        const uint16_t* d_X, int ncols, float* d_Y);
 
@@ -444,8 +443,7 @@ int cas_model_use_unary(cas_model* model, int layer, int which, const cas_udesc*
  * kernel of cas_gemv_draft_mx (with the fused norm / residual / SwiGLU of the raw form),
  * verification passes go through cas_gemm_verify_mx, and a speculative round emits exactly what
  * plain decoding with the converted weights emits.  Arguments as for cas_model_use_unary;
- * mx = NULL switches back; one form at a time per tensor (the last call wins).  Workspace as
- * for cas_gemm_verify_mx. */
+ * mx = NULL switches back; one form at a time per tensor (the last call wins). */
 int cas_model_use_mx(cas_model* model, int layer, int which, const cas_mxdesc* mx, const void* d_mxspec,
                      const void* d_mxverif);
 

@@ -129,9 +129,13 @@ __device__ __forceinline__ void static_for(F&& f) {
 // decode() hands each (column position, bf16 word) to `write`.  A lane that runs out of bits
 // keeps calling write with position -1 and a don't-care value: the caller maps -1 to a dump
 // slot.  All 64 lanes of the wave must call it together.
-template <int T, bool FULL>
+// MX: the kept fields are those of the shared-exponent form (Sec. 4.2, the MX approach): sign
+// above the 8-T leading magnitude bits in the spec-side stream, the T low magnitude bits in lo;
+// decode() then takes the block's exponent and writes the bf16 word of
+// (-1)^sign * magnitude * 2^(E - 134).
+template <int T, bool FULL, bool MX = false>
 struct KeptWindows {
-  static constexpr int FW = 16 - T;
+  static constexpr int FW = MX ? 9 - T : 16 - T;
   static constexpr int LW = T > 0 ? T : 1;
   uint32_t ds[FW + 1];
   uint32_t dl[LW + 1];
@@ -156,9 +160,20 @@ struct KeptWindows {
     }
   }
 
-  // m: kept mask of the word
+  // bf16 word of a shared-exponent value: the leading zeros of the magnitude come off the
+  // exponent; subnormal when it runs out (same arithmetic as the reconstruction in mx.hip)
+  static __device__ __forceinline__ uint32_t mx_bf16(uint32_t sign, int E, uint32_t mag) {
+    const int lz = __clz(mag) - 24;  // 8 for mag == 0
+    const int e = E - lz;
+    const uint32_t normal = ((uint32_t)e << 7) | ((mag << lz) & 0x7Fu);
+    const uint32_t sub = mag << (max(E, 1) - 1);
+    const uint32_t v = mag == 0u ? 0u : (e >= 1 ? normal : sub);
+    return (sign << 15) | v;
+  }
+
+  // m: kept mask of the word; shared_exp: the word's shared exponent (MX only)
   template <class W>
-  __device__ __forceinline__ void decode(uint32_t m, W&& write) const {
+  __device__ __forceinline__ void decode(uint32_t m, W&& write, int shared_exp = 0) const {
     uint32_t ws[FW], wl[LW];
 #pragma unroll
     for (int q = 0; q < FW; ++q) ws[q] = __builtin_amdgcn_alignbit(ds[q + 1], ds[q], shs);
@@ -170,8 +185,15 @@ struct KeptWindows {
       constexpr int e = decltype(E)::value;
       int pos = lowest_bit(m);
       m &= m - 1u;
-      uint32_t v = field_at<FW, e>(ws) << T;
-      if constexpr (FULL && T > 0) v |= field_at<T, e>(wl);
+      uint32_t v = field_at<FW, e>(ws);
+      if constexpr (MX) {
+        uint32_t mag = (v & ((1u << (8 - T)) - 1u)) << T;
+        if constexpr (FULL && T > 0) mag |= field_at<T, e>(wl);
+        v = mx_bf16(v >> (8 - T), shared_exp, mag);
+      } else {
+        v <<= T;
+        if constexpr (FULL && T > 0) v |= field_at<T, e>(wl);
+      }
       write(pos, (uint16_t)v);
     };
     auto kept_tail = [&](auto self, auto E) -> void {

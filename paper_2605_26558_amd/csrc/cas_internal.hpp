@@ -82,9 +82,7 @@ int launch_gemm_verify_fused(cas_ctx*, const cas_wdesc&, const void* spec, const
 int launch_unary_expand(cas_ctx*, const cas_udesc&, const void* uspec, int64_t row0, int nrows, uint32_t* out);
 int launch_gemm_verify_unary_fused(cas_ctx*, const cas_udesc&, const void* uspec, const void* verif, const uint16_t* X,
                                    int ncols, float* Y, int epi, uint16_t* out16);
-// mx.hip: rows [row0, row0 + nrows) of the converted matrix as raw spec (sw words per row) and lo (lw words per row) streams
-int launch_mx_expand(cas_ctx*, const cas_mxdesc&, const void* mxspec, const void* mxverif, int64_t row0, int nrows,
-                     uint32_t* out_spec, uint32_t* out_lo);
+// mx.hip / gemm_verify_mx.hip
 int launch_gemv_draft_mx_fused(cas_ctx*, const cas_mxdesc&, const void* mxspec, const uint16_t* x, float* y,
                                const uint16_t* gain, float eps, int epi, uint16_t* out16);
 int launch_gemm_verify_mx_fused(cas_ctx*, const cas_mxdesc&, const void* mxspec, const void* mxverif, const uint16_t* X,

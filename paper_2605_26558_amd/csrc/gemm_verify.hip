@@ -23,22 +23,9 @@ int launch_gemm_verify(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const
   return launch_gemm_verify_fused(ctx, d, spec, verif, X, ncols, Y, 0, nullptr);
 }
 
-// Picks the form of the kernel for a matrix.  The choice depends on the shape of the WHOLE matrix
-// (a.yld rows), never on the number of columns or on the block of rows a launch covers: it fixes
-// the order in which a row's partial sums are added, and a column must get the same bits in
-// every call.
 static int launch_verify_args(cas_ctx* ctx, const VerifyArgs& a, int t) {
-  // One row group per workgroup.  Many row groups: four waves, each taking a quarter of every
-  // slab (measured faster than 8-wave workgroups: fewer lanes wait at the slab barriers).  Few
-  // row groups: eight waves so that every CU still gets several, sixteen when the rows are long
-  // (each wave then has one decode step per slab and the serial chain per workgroup halves).
-  // More than 8 columns: X is staged per decode step (see gemm_verify_wide.hip); up to 8 the
-  // per-slab staging measured 5 % faster on the largest matrices.
   if (a.ncols > 8) return launch_gemm_verify_wide(ctx, a, t);
-  const int groups = (a.yld + 15) / 16;
-  if (groups < kFewGroups && a.cols >= 4 * kSlabCols) return launch_gq<1, 16, 1, 1>(ctx, a, t);
-  if (groups < kFewGroups) return launch_gq<1, 8, 2, 1>(ctx, a, t);
-  return launch_gq<1, 4, 4, 1>(ctx, a, t);
+  return verify_narrow<false>(ctx, a, t);
 }
 
 int launch_gemm_verify_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec, const void* verif,
@@ -54,6 +41,7 @@ int launch_gemm_verify_fused(cas_ctx* ctx, const cas_wdesc& d, const void* spec,
   a.lo = (const uint32_t*)((const char*)verif + d.off_lo);
   a.pruned = (const uint32_t*)((const char*)verif + d.off_pruned);
   a.X = X; a.Y = Y; a.yld = (int)d.rows;
+  a.sexp = nullptr; a.ew = 0;
   ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + d.sw + d.lw + d.pw));
   return launch_verify_args(ctx, a, d.t);
 }
@@ -87,44 +75,7 @@ int launch_gemm_verify_unary_fused(cas_ctx* ctx, const cas_udesc& u, const void*
     a.lo = (const uint32_t*)((const char*)verif + d.off_lo) + (size_t)r0 * d.lw;
     a.pruned = (const uint32_t*)((const char*)verif + d.off_pruned) + (size_t)r0 * d.pw;
     a.X = X; a.yld = (int)d.rows;
-    a.Y = Y ? Y + r0 : nullptr;
-    a.out16 = out16 ? out16 + (epi == 2 ? r0 / 2 : r0) : nullptr;
-    rc = launch_verify_args(ctx, a, d.t);
-    if (rc != CAS_OK) return rc;
-  }
-  return CAS_OK;
-}
-
-// ... and in the shared-exponent form (Sec. 4.2, the MX approach): W is the CONVERTED matrix.  Blocks
-// of rows are written as raw spec and lo streams of that matrix into the workspace; bitmap and
-// pruned values are read in place.
-int launch_gemm_verify_mx_fused(cas_ctx* ctx, const cas_mxdesc& x, const void* mxspec, const void* mxverif,
-                                const uint16_t* X, int ncols, float* Y, int epi, uint16_t* out16) {
-  const cas_wdesc& d = x.base;
-  if (d.rows <= 0) return CAS_OK;
-  if (epi == 2 && (d.rows & 1)) return CAS_EINVAL;
-  const size_t row_bytes = (size_t)(d.sw + d.lw) * 4;
-  int64_t blk = row_bytes ? (ctx->ws_bytes > 1024 ? (int64_t)((ctx->ws_bytes - 1024) / row_bytes) : 0) : d.rows;
-  blk = std::min<int64_t>(blk, d.rows);
-  if (blk < d.rows) blk = blk / 16 * 16;
-  if (blk < 1 || (row_bytes > 0 && !ctx->d_ws)) return CAS_ENOMEM;
-  uint32_t* ws_spec = (uint32_t*)ctx->d_ws;
-  // behind the spec block and its slack, on a 256-byte boundary
-  uint32_t* ws_lo = (uint32_t*)((char*)ctx->d_ws + ((size_t)blk * d.sw * 4 + 256 + 255) / 256 * 256);
-  ProfScope prof(ctx, PROF_GEMM_VERIFY, 4.0 * (double)d.rows * (d.bw + x.fw + d.lw + d.pw) + (double)d.rows * x.ew);
-  for (int64_t r0 = 0; r0 < d.rows; r0 += blk) {
-    const int nr = (int)std::min<int64_t>(blk, d.rows - r0);
-    int rc = launch_mx_expand(ctx, x, mxspec, mxverif, r0, nr, ws_spec, ws_lo);
-    if (rc != CAS_OK) return rc;
-    VerifyArgs a;
-    a.epi = epi;
-    a.rows = nr; a.cols = (int)d.cols; a.bw = d.bw; a.sw = d.sw; a.lw = d.lw; a.pw = d.pw;
-    a.ncols = ncols;
-    a.bitmap = (const uint32_t*)((const char*)mxspec + x.off_bitmap) + (size_t)r0 * d.bw;
-    a.spec = ws_spec;
-    a.lo = ws_lo;
-    a.pruned = (const uint32_t*)((const char*)mxverif + x.off_pruned) + (size_t)r0 * d.pw;
-    a.X = X; a.yld = (int)d.rows;
+    a.sexp = nullptr; a.ew = 0;
     a.Y = Y ? Y + r0 : nullptr;
     a.out16 = out16 ? out16 + (epi == 2 ? r0 / 2 : r0) : nullptr;
     rc = launch_verify_args(ctx, a, d.t);

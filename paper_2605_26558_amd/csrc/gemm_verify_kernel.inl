@@ -19,11 +19,15 @@ struct VerifyArgs {
   const uint16_t* X;  // [ncols][cols]
   float* Y;           // [ncols][yld] (epilogue 0)
   int yld;            // output rows per column in Y / out16 (>= rows: the launch may cover a block of rows)
+  const uint8_t* sexp;  // shared-exponent form only: one exponent per bitmap word, ew bytes per row
+  int ew;
   int epi;            // 0: Y = W X;  1: h = bf16(h + bf16(W X));  2: act[i] = swiglu(rows 2i, 2i+1)
   uint16_t* out16;    // h [ncols][yld] (epilogue 1) or act [ncols][yld/2] (epilogue 2)
 };
 
 constexpr int kSlabCols = 2048;
+// row groups below which a matrix gets more waves per row group (just over one group per CU)
+constexpr int kFewGroups = 300;
 constexpr int kGroupPitch = 36;         // 4 dump slots + 32 columns
 constexpr int kTilePitch = 148;         // 4 groups + 4 pad, keeps 8-byte alignment, spreads banks
 
@@ -35,7 +39,7 @@ constexpr int kTilePitch = 148;         // 4 groups + 4 pad, keeps 8-byte alignm
 // words, so one step reads one contiguous run of each stream per row and every cache line is
 // fetched by one step only (lines are not kept in L1 between steps: 12 waves x 16 rows x 3
 // streams are far more than it holds).
-template <int T, int G, int Q, int XST, int NB>
+template <int T, int G, int Q, int XST, int NB, bool MX = false>
 __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
   constexpr int NW = G * Q;          // waves per workgroup
   constexpr int NT = 64 * NW;        // threads
@@ -132,7 +136,14 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
         u4[i] = nvalid > 0 ? (uint32_t)(word0 + 4 * i) * 32u - p : 0u;
       }
     }
-    KeptWindows<T, true> kw;
+    // shared-exponent form: the exponent of each of the lane's words (sp_row is then the field stream)
+    int E4[WPL];
+    if constexpr (MX) {
+#pragma unroll
+      for (int i = 0; i < WPL; ++i)
+        E4[i] = word0 + 4 * i < a.bw ? (int)a.sexp[(size_t)row * a.ew + word0 + 4 * i] : 0;
+    }
+    KeptWindows<T, true, MX> kw;
     PrunedWindows pw;
     kw.load(p4[0], sp_row, lo_row);
     // ---- this wave's X columns of the next XST steps (bf16, zero beyond the last column)
@@ -162,7 +173,7 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
       // whole sets); measured 4 % faster than loading a whole step ahead.
       // pos == -1 (lane out of bits) lands in the dump slot in front of the group
       pw.load(u4[i], pr_row);
-      kw.decode(m4[i], [&](int pos, uint16_t v) { trow[pos] = v; });
+      kw.decode(m4[i], [&](int pos, uint16_t v) { trow[pos] = v; }, MX ? E4[i] : 0);
       if constexpr (i + 1 < WPL) kw.load(p4[i + 1], sp_row, lo_row);
       pw.decode(pm4[i], [&](int pos, uint16_t v) { trow[pos] = v; });
       // ---- tile x X: tile column 32*g + c is slab column (part*WPP + 4*i + g)*32 + c
@@ -224,7 +235,7 @@ __global__ __launch_bounds__(64 * G * Q) void gemm_verify_kernel(VerifyArgs a) {
   }
 }
 
-template <int G, int Q, int XST, int NB>
+template <int G, int Q, int XST, int NB, bool MX = false>
 static int launch_gq(cas_ctx* ctx, const VerifyArgs& a, int t) {
   constexpr int NW = G * Q;
   size_t lds = sizeof(uint16_t) * (NW * 16 * kTilePitch + (size_t)NW * a.ncols * (XST * 128 + 8));
@@ -235,9 +246,9 @@ static int launch_gq(cas_ctx* ctx, const VerifyArgs& a, int t) {
 #define CAS_LAUNCH(TV)                                                                                        \
   case TV: {                                                                                                  \
     static LdsLimit lim;                                                                                      \
-    const int rc = allow_lds(ctx, (const void*)gemm_verify_kernel<TV, G, Q, XST, NB>, lds, lim);              \
+    const int rc = allow_lds(ctx, (const void*)gemm_verify_kernel<TV, G, Q, XST, NB, MX>, lds, lim);              \
     if (rc != CAS_OK) return rc;                                                                              \
-    hipLaunchKernelGGL((gemm_verify_kernel<TV, G, Q, XST, NB>), dim3(grid), dim3(64 * NW), lds, ctx->stream, a); \
+    hipLaunchKernelGGL((gemm_verify_kernel<TV, G, Q, XST, NB, MX>), dim3(grid), dim3(64 * NW), lds, ctx->stream, a); \
   } break;
   switch (t) {
     CAS_LAUNCH(0) CAS_LAUNCH(1) CAS_LAUNCH(2) CAS_LAUNCH(3) CAS_LAUNCH(4) CAS_LAUNCH(5) CAS_LAUNCH(6) CAS_LAUNCH(7)
@@ -248,10 +259,54 @@ static int launch_gq(cas_ctx* ctx, const VerifyArgs& a, int t) {
   return CAS_OK;
 }
 
-// row groups below which a matrix gets more waves per row group (just over one group per CU)
-constexpr int kFewGroups = 300;
+// ---- which form of the kernel a matrix gets ----------------------------------------------------
+// The choice depends on the shape of the WHOLE matrix (a.yld rows), never on the number of columns
+// or on the block of rows a launch covers: it fixes the order in which a row's partial sums are
+// added, and a column must get the same bits in every call.
 
-// the forms for 9 to 32 columns (gemm_verify_wide.hip)
+// Up to 8 columns.  One row group per workgroup.  Many row groups: four waves, each taking a
+// quarter of every slab (measured faster than 8-wave workgroups: fewer lanes wait at the slab
+// barriers).  Few row groups: eight waves so that every CU still gets several, sixteen when the
+// rows are long (each wave then has one decode step per slab and the serial chain per workgroup
+// halves).  X is staged per slab: measured 5 % faster on the largest matrices than per step.
+template <bool MX>
+static int verify_narrow(cas_ctx* ctx, const VerifyArgs& a, int t) {
+  const int groups = (a.yld + 15) / 16;
+  if (groups < kFewGroups && a.cols >= 4 * kSlabCols) return launch_gq<1, 16, 1, 1, MX>(ctx, a, t);
+  if (groups < kFewGroups) return launch_gq<1, 8, 2, 1, MX>(ctx, a, t);
+  return launch_gq<1, 4, 4, 1, MX>(ctx, a, t);
+}
+
+// 9 to 32 columns (several sequences per pass, or long drafts): X staged one decode step at a
+// time, so that the LDS of a workgroup stays small enough for three of them per CU, and a second
+// block of 16 output columns above 16.
+template <int NB, bool MX>
+static int verify_wide_nb(cas_ctx* ctx, const VerifyArgs& a, int t) {
+  const int groups = (a.yld + 15) / 16;
+  if (groups < kFewGroups && a.cols >= 4 * kSlabCols) return launch_gq<1, 16, 1, NB, MX>(ctx, a, t);
+  if (groups < kFewGroups) return launch_gq<1, 8, 1, NB, MX>(ctx, a, t);
+  return launch_gq<1, 4, 1, NB, MX>(ctx, a, t);
+}
+
+template <bool MX>
+static int verify_wide(cas_ctx* ctx, const VerifyArgs& a, int t) {
+  if (a.ncols <= 16) return verify_wide_nb<1, MX>(ctx, a, t);
+  int rc = verify_wide_nb<2, MX>(ctx, a, t);
+  if (rc != CAS_ENOTSUP) return rc;
+  // sixteen waves per row group with more than 20 columns exceed the LDS: two launches of one
+  // column block each (the weights of such a matrix are read twice)
+  VerifyArgs lo = a, hi = a;
+  lo.ncols = 16;
+  hi.ncols = a.ncols - 16;
+  hi.X = a.X + (size_t)16 * a.cols;
+  if (a.Y) hi.Y = a.Y + (size_t)16 * a.yld;
+  if (a.out16) hi.out16 = a.out16 + (size_t)16 * (a.epi == 2 ? a.yld >> 1 : a.yld);
+  rc = verify_wide_nb<1, MX>(ctx, lo, t);
+  if (rc != CAS_OK) return rc;
+  return verify_wide_nb<1, MX>(ctx, hi, t);
+}
+
+// gemm_verify_wide.hip: verify_wide<false> (its own translation unit: the build compiles the files side by side)
 int launch_gemm_verify_wide(cas_ctx* ctx, const VerifyArgs& a, int t);
 
 }  // namespace cas

@@ -124,47 +124,6 @@ __global__ __launch_bounds__(256) void mx_decode_kernel(MxArgs a, uint16_t* __re
   }
 }
 
-// ---- raw spec and lo streams of the CONVERTED matrix for a block of rows: one wave per row ----
-// The verification GEMM reads the raw layout, so a kept value of the shared-exponent form (sign,
-// block exponent, all eight magnitude bits) is first written as the bf16 word it stands for and
-// then split as the raw form splits it: leading 16-t bits into the spec stream, t low bits into lo.
-// Fields are OR-ed into a zeroed row in LDS and copied out.
-__global__ __launch_bounds__(64) void mx_expand_kernel(MxArgs a, int row0, uint32_t* __restrict__ out_spec,
-                                                       uint32_t* __restrict__ out_lo) {
-  extern __shared__ uint32_t rowbuf[];  // [sw] spec words, then [lw] lo words
-  const int lane = threadIdx.x, row = row0 + blockIdx.x;
-  uint32_t* sbuf = rowbuf;
-  uint32_t* lbuf = rowbuf + a.sw;
-  for (int i = lane; i < a.sw + a.lw; i += 64) rowbuf[i] = 0u;
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  const int FB = 9 - a.t, HB = 8 - a.t, HW = 16 - a.t;
-  const uint32_t* f_row = a.m_field + (size_t)row * a.fw;
-  const uint32_t* l_row = a.m_lo + (size_t)row * a.lw;
-  int base = 0;
-  for (int w0 = 0; w0 < a.bw; w0 += 64) {
-    const int w = w0 + lane;
-    uint32_t m = w < a.bw ? a.m_bitmap[(size_t)row * a.bw + w] : 0u;
-    const int E = w < a.bw ? a.m_sexp[(size_t)row * a.ew + w] : 0;
-    const int cnt = __popc(m);
-    const int incl = wave_incl_scan(cnt);
-    int e = base + incl - cnt;
-    base += __builtin_amdgcn_readlane(incl, 63);
-    for (int j = 0; j < cnt; ++j, ++e) {
-      const uint32_t f = read_field(f_row, (uint32_t)e * FB, FB);
-      uint32_t mag = (f & ((1u << HB) - 1u)) << a.t;
-      if (a.t > 0) mag |= read_field(l_row, (uint32_t)e * a.t, a.t);
-      const uint32_t word = mx_word(f >> HB, E, mag);
-      or_field(sbuf, (uint32_t)e, HW, word >> a.t);
-      if (a.t > 0) or_field(lbuf, (uint32_t)e, a.t, word & ((1u << a.t) - 1u));
-    }
-  }
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  for (int i = lane; i < a.sw; i += 64) out_spec[(size_t)blockIdx.x * a.sw + i] = sbuf[i];
-  for (int i = lane; i < a.lw; i += 64) out_lo[(size_t)blockIdx.x * a.lw + i] = lbuf[i];
-}
-
 static int64_t up256(int64_t v) { return (v + 255) / 256 * 256; }
 constexpr int64_t kMxSlack = 256;
 
@@ -224,21 +183,6 @@ static MxArgs make_args(const cas_mxdesc& x, const void* spec, const void* verif
 
 static int row_grid(cas_ctx* ctx, int64_t rows) {
   return (int)std::max<int64_t>(1, std::min<int64_t>((rows + 3) / 4, (int64_t)ctx->num_cu * 8));
-}
-
-int launch_mx_expand(cas_ctx* ctx, const cas_mxdesc& x, const void* mxspec, const void* mxverif, int64_t row0,
-                     int nrows, uint32_t* out_spec, uint32_t* out_lo) {
-  const cas_wdesc& d = x.base;
-  if (nrows <= 0 || d.sw + d.lw == 0) return CAS_OK;
-  const size_t lds = (size_t)(d.sw + d.lw) * 4;
-  if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
-  MxArgs a = make_args(x, nullptr, nullptr, const_cast<void*>(mxspec), mxverif);
-  static LdsLimit lim;
-  const int rc = allow_lds(ctx, (const void*)mx_expand_kernel, lds, lim);
-  if (rc != CAS_OK) return rc;
-  hipLaunchKernelGGL(mx_expand_kernel, dim3((unsigned)nrows), dim3(64), lds, ctx->stream, a, (int)row0, out_spec, out_lo);
-  CAS_HIP(ctx, hipGetLastError());
-  return CAS_OK;
 }
 
 // Draft GEMV on the shared-exponent form with the epilogues of the raw form (one column).

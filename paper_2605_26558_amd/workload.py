@@ -610,6 +610,57 @@ def run_tune(B, args, dev):
                       "eq2_J": j, "best_by_eq2_bits": {"keep_permille": keeps[bj[0]], "trunc_bits": truncs[bj[1]]}}))
 
 
+def run_exp_modes(B, args, dev):
+    """`bench.py --workload exp-modes`: pass times of the whole model with the speculation data of
+    every linear layer in the raw, the unary-coded and the shared-exponent form (Sec. 4.2), on the
+    same weights, cache and context.  Context figures, one JSON object; the metric's workload is
+    the raw form."""
+    import json
+    import torch
+    wl = ModelRoundWorkload(B, args, dev)
+    ctx, model = wl.ctx, wl.model
+    names = ("wqkv", "wo", "wgu", "wd")
+    mats = [(l, w, L[n]) for l, L in enumerate(wl.layers) for w, n in enumerate(names)] + [(-1, 0, wl.head)]
+    kv_d, kv_v = wl.draft_kv, wl.verify_kv
+
+    def report(draft_bytes, verify_bytes):
+        td, tv, tp = wl._time_passes(reps=3)
+        return {"draft_pass_ms": td, "verify_pass_ms": tv, "plain_step_ms": tp,
+                "draft_pass_bytes": draft_bytes + kv_d, "verify_pass_bytes": verify_bytes + kv_v,
+                "draft_pass_GBps": (draft_bytes + kv_d) / td / 1e6, "verify_pass_GBps": (verify_bytes + kv_v) / tv / 1e6,
+                "bits_per_value_draft": 8.0 * draft_bytes / wl.values, "bits_per_value_verify": 8.0 * verify_bytes / wl.values}
+
+    out = {"workload": wl.config["workload"], "k": wl.k, "context": wl.ctx_len,
+           "keep_permille": args.keep, "trunc_bits": args.trunc}
+    out["raw"] = report(wl.draft_w, wl.verify_w)
+    # unary-coded exponents: lossless, verification gives the raw form's bits
+    d_b = v_b = 0
+    for l, w, m in mats:
+        uw = B.cas_unary_encode(ctx, m)
+        model.use_unary(l, w, uw)
+        u, d = uw.desc, uw.desc.base
+        b = d.rows * (d.bw + u.smw) * 4 + u.ue_words * 4 + (d.rows + 1) * 4 + 512
+        d_b += b
+        v_b += b + d.rows * (d.lw + d.pw) * 4
+    torch.cuda.synchronize()
+    out["unary"] = report(d_b, v_b)
+    for l, w, m in mats:
+        model.use_unary(l, w, None)
+    model._unary = {}
+    # shared exponents: the converted matrices are the weights
+    d_b = v_b = 0
+    for l, w, m in mats:
+        mw = B.cas_mx_encode(ctx, m)
+        model.use_mx(l, w, mw)
+        x, d = mw.desc, mw.desc.base
+        b = d.rows * (d.bw * 4 + x.ew + x.fw * 4)
+        d_b += b
+        v_b += b + d.rows * (d.lw + d.pw) * 4
+    torch.cuda.synchronize()
+    out["mx"] = report(d_b, v_b)
+    print(json.dumps(out))
+
+
 def build(B, args, dev):
     if args.workload == "linear":
         return LinearRoundWorkload(B, args, dev)

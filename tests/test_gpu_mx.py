@@ -148,21 +148,18 @@ def test_gemm_verify_mx_is_the_product_with_the_converted_matrix(env, rows, cols
             np.testing.assert_array_equal(Yu[i], O.bf16_to_f64(Wc[:, j]).astype(np.float32))
 
 
-def test_gemm_verify_mx_in_row_blocks_and_without_room(env):
+def test_gemm_verify_mx_gives_a_column_the_same_bits_in_any_company(env):
     torch, B, ctx = env
     rows, cols, keep, t = 150, 1000, 600, 4
     W = _matrix(rows, cols, False, seed=5)
-    X = synth.activations(cols, 3, seed=6)
-    ew = B.cas_encode_weight(ctx, _dev(torch, W), keep, t)
-    mw = B.cas_mx_encode(ctx, ew)
-    whole = B.cas_gemm_verify_mx(ctx, mw, _dev(torch, X)).cpu().numpy()
-    row_bytes = (ew.desc.sw + ew.desc.lw) * 4
-    small = B.Context(workspace=torch.empty(17 * row_bytes + 1024, dtype=torch.uint8, device="cuda"))
-    np.testing.assert_array_equal(B.cas_gemm_verify_mx(small, mw, _dev(torch, X)).cpu().numpy(), whole)
-    tiny = B.Context(workspace=torch.empty(15 * row_bytes + 1024, dtype=torch.uint8, device="cuda"))
-    with pytest.raises(B.CasError) as e:
-        B.cas_gemm_verify_mx(tiny, mw, _dev(torch, X))
-    assert e.value.code == B.CAS_ENOMEM
+    X = synth.activations(cols, 20, seed=6)
+    mw = B.cas_mx_encode(ctx, B.cas_encode_weight(ctx, _dev(torch, W), keep, t))
+    Y20 = B.cas_gemm_verify_mx(ctx, mw, _dev(torch, X)).cpu().numpy()
+    Y5 = B.cas_gemm_verify_mx(ctx, mw, _dev(torch, X[:5])).cpu().numpy()
+    np.testing.assert_array_equal(Y20[:5], Y5)
+    for c in (0, 7, 19):
+        y1 = B.cas_gemm_verify_mx(ctx, mw, _dev(torch, X[c:c + 1])).cpu().numpy()
+        np.testing.assert_array_equal(y1[0], Y20[c])
 
 
 def test_mx_empty_matrix(env):
