@@ -471,8 +471,8 @@ def run_probe(B, args):
     algorithmic bytes of every launch that follows so that counter readings can be compared.
 
     probe-linear: draft GEMV (1 column) and verify GEMM (k+1 columns) on four distinct matrices of
-    each 8B layer shape and one output head, then the unary-coded and shared-exponent draft GEMVs on
-    the 28672 x 4096 matrices.  probe-attn: draft (1 column) and verification (k+1 columns) attention
+    each 8B layer shape and one output head, then the unary-coded and shared-exponent draft GEMVs and
+    verification GEMMs on the 28672 x 4096 matrices.  probe-attn: draft (1 column) and verification (k+1 columns) attention
     of one layer over a compressed cache of `--context` positions, six distinct layers."""
     import torch
     ctx = B.Context(workspace=torch.empty(256 << 20, dtype=torch.uint8, device="cuda"))
@@ -513,9 +513,19 @@ def run_probe(B, args):
                 for _ in range(3):
                     for xm in xmats:
                         B.cas_gemv_draft_mx(ctx, xm, x1, yu)
+                for _ in range(3):
+                    for xm in xmats:
+                        B.cas_gemm_verify_mx(ctx, xm, x, y[:, :rows])
+                for _ in range(3):
+                    for u in umats:
+                        B.cas_gemm_verify_unary(ctx, u, x, y[:, :rows])
                 u, xd = umats[0].desc, xmats[0].desc
                 print("gemv_draft_unary_algorithmic_bytes", rows * (d.bw + u.smw) * 4 + (u.ue_words + rows + 1) * 4)
-                print("gemv_draft_mx_algorithmic_bytes", rows * (d.bw * 4 + d.bw + xd.fw * 4), flush=True)
+                print("gemv_draft_mx_algorithmic_bytes", rows * (d.bw * 4 + d.bw + xd.fw * 4))
+                print("gemm_verify_mx_algorithmic_bytes", rows * (d.bw * 4 + d.bw + (xd.fw + d.lw + d.pw) * 4))
+                print("gemm_verify_unary_algorithmic_bytes (unary_expand_kernel, then gemm_verify_kernel on the "
+                      "re-coded block)", rows * (d.bw + u.smw + d.lw + d.pw) * 4 + (u.ue_words + rows + 1) * 4,
+                      flush=True)
                 del umats, xmats
             del mats
     else:
