@@ -48,9 +48,13 @@ typedef struct cas_ctx cas_ctx;
 typedef struct {
   int32_t keep_permille; /* kept fraction in 1/1000 (600 = 40 % pruned); K = (keep*G+500)/1000 */
   int32_t trunc_bits;    /* t in 0..7: low mantissa bits moved to the verification data */
-  int32_t exp_mode;      /* 0 = exponent stored raw (8 bits); other values: CAS_ENOTSUP (the unary form
-                            is produced from a raw encoding by cas_unary_plan / cas_unary_encode) */
+  int32_t exp_mode;      /* CAS_EXP_RAW: exponent stored as it is (8 bits).  CAS_EXP_SHARED: one exponent
+                            per 32 values (Sec. 4.2, the MX approach), accepted by the KV cache
+                            (cas_kv_desc_init); cas_encode_weight takes CAS_EXP_RAW only, the other forms
+                            of a matrix are re-codings of its raw encoding (cas_unary_*, cas_mx_*).
+                            Anything else: CAS_ENOTSUP. */
 } cas_fmt;
+enum { CAS_EXP_RAW = 0, CAS_EXP_SHARED = 2 };
 
 /*
  * Layout of one encoded matrix: `rows` selection groups (output rows of a linear layer, or
@@ -279,6 +283,14 @@ int cas_gemm_verify_mx(cas_ctx* ctx, const cas_mxdesc* mx, const void* d_mxspec,
  * Tile index = ((layer * n_pages + page) * 2 + (0 for K, 1 for V)) * n_kv_heads + head; tiles
  * are tile_spec_bytes / tile_verif_bytes apart.  The selection group is one vector of one
  * token and one kv head; K and V are selected separately; ties go to the lower channel.
+ *
+ * fmt.exp_mode = CAS_EXP_SHARED stores the kept values in the shared-exponent form described at
+ * cas_mxdesc, a block being the 32 channels of one bitmap word of one vector: what the cache
+ * then holds (and what verification reads back) is the CONVERTED vector, the draft pass reads
+ * sign + leading magnitude bits.  Its speculation pool tile is [page_tokens][4] bitmap words,
+ * [page_tokens] words with the four block exponents of a vector (block j in byte j), then
+ * [page_tokens][sw] words of K fields of 9-t bits; the verification pool tile is unchanged in
+ * shape (lo = the t low magnitude bits).
  */
 typedef struct {
   int32_t n_layers, n_kv_heads, head_dim /* must be 128 */, page_tokens /* must be 64 */;

@@ -634,12 +634,16 @@ class OracleModel:
     """
 
     def __init__(self, shape, weights, rope_tab, w_keep=600, w_t=4, kv_keep=600, kv_t=4,
-                 act_norms=None, exp_mode="raw"):
+                 act_norms=None, exp_mode="raw", kv_exp_mode="raw"):
         """exp_mode "raw": exponents stored as they are (also stands for the unary form, which is
         a lossless re-coding of the same data).  "mx": every linear layer in the shared-exponent
-        form of Sec. 4.2; the target model is then the converted one."""
-        assert exp_mode in ("raw", "mx")
-        self.exp_mode = exp_mode
+        form of Sec. 4.2; the target model is then the converted one.  kv_exp_mode: the same
+        choice for the cache (Sec. 5.1 encoder: the speculation group of a new vector goes
+        through the exponent compression before it is stored); with "mx" a cached vector is read
+        back as its converted form by the target pass and as sign + leading magnitude bits by
+        the draft pass, a block being the 32 channels of one bitmap word."""
+        assert exp_mode in ("raw", "mx") and kv_exp_mode in ("raw", "mx")
+        self.exp_mode, self.kv_exp_mode = exp_mode, kv_exp_mode
         self.s = shape
         self.rope_tab = rope_tab
         self.kv_keep, self.kv_t = kv_keep, kv_t
@@ -675,7 +679,10 @@ class OracleModel:
 
     def _cache_kv(self, layer, draft: bool):
         st = self.cache[layer]
-        dec = decode_draft if draft else decode_full
+        if self.kv_exp_mode == "mx":
+            dec = decode_draft_mx if draft else decode_full_mx
+        else:
+            dec = decode_draft if draft else decode_full
         if not st.k:
             z = np.zeros((0, self.s.n_kv_heads, self.s.head_dim), dtype=np.uint16)
             return z, z.copy()
@@ -733,8 +740,11 @@ class OracleModel:
         (Sec. 5.1 encoder: online formatting of the KV cache)."""
         for li, (nk, nv) in enumerate(new_kv):
             for c in range(n_cols):
-                self.cache[li].k.append(encode_kv(nk[c], self.kv_keep, self.kv_t))
-                self.cache[li].v.append(encode_kv(nv[c], self.kv_keep, self.kv_t))
+                pk, pv = encode_kv(nk[c], self.kv_keep, self.kv_t), encode_kv(nv[c], self.kv_keep, self.kv_t)
+                if self.kv_exp_mode == "mx":
+                    pk, pv = to_mx(pk), to_mx(pv)
+                self.cache[li].k.append(pk)
+                self.cache[li].v.append(pv)
 
     def truncate(self, n: int):
         for st in self.cache:

@@ -10,6 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcassandra_hip.so")
 
 CAS_OK, CAS_EINVAL, CAS_ENOTSUP, CAS_ENOMEM, CAS_EHIP = 0, -1, -2, -3, -4
+CAS_EXP_RAW, CAS_EXP_SHARED = 0, 2   # cas_fmt.exp_mode
 
 
 class CasError(RuntimeError):
@@ -509,12 +510,12 @@ class KVCache:
     """Pools, page table and the cas_kv handle of a compressed paged cache."""
 
     def __init__(self, ctx: Context, n_layers, n_kv_heads, n_pages, max_seqs, max_pages_per_seq,
-                 keep_permille=600, trunc_bits=4, head_dim=128, page_tokens=64, page_table=None):
+                 keep_permille=600, trunc_bits=4, head_dim=128, page_tokens=64, page_table=None, exp_mode=0):
         torch = ctx._torch
         d = cas_kv_desc()
         d.n_layers, d.n_kv_heads, d.head_dim, d.page_tokens = n_layers, n_kv_heads, head_dim, page_tokens
         d.n_pages, d.max_seqs, d.max_pages_per_seq = n_pages, max_seqs, max_pages_per_seq
-        d.fmt = cas_fmt(keep_permille, trunc_bits, 0)
+        d.fmt = cas_fmt(keep_permille, trunc_bits, exp_mode)   # CAS_EXP_RAW or CAS_EXP_SHARED
         rc = _lib().cas_kv_desc_init(C.byref(d))
         if rc != CAS_OK:
             raise CasError(rc, "cas_kv_desc_init")

@@ -27,9 +27,18 @@
 namespace cas {
 
 // the draft form (speculation data only) is compiled in attention_draft.hip
-extern template int launch_mt<1, false>(cas_ctx*, const AttnBatch&, dim3);
-extern template int launch_mt<2, false>(cas_ctx*, const AttnBatch&, dim3);
-extern template int launch_mt<3, false>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<1, false, false>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<2, false, false>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<3, false, false>(cas_ctx*, const AttnBatch&, dim3);
+// the forms over a cache with shared exponents: attention_mx.hip, attention_mx_draft.hip
+extern template int launch_mt<1, true, true>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<2, true, true>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<3, true, true>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<4, true, true>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<5, true, true>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<1, false, true>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<2, false, true>(cas_ctx*, const AttnBatch&, dim3);
+extern template int launch_mt<3, false, true>(cas_ctx*, const AttnBatch&, dim3);
 
 // Combine the splits: o = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, rounded to bf16.
 // One workgroup per (query row, kv head, half of the channels): the split weights are computed
@@ -154,7 +163,7 @@ static int launch_attention_group(cas_ctx* ctx, cas_kv* kv, const AttnCall* call
     max_r = std::max(max_r, R);
     max_split = std::max(max_split, q.nsplit);
     // committed positions: bitmap + spec (+ lo + pruned) of K and V; in-flight ones: plain bf16
-    const double per_tok = 4.0 * (4 + g.sw + (c.full ? g.lw + g.pw : 0));
+    const double per_tok = 4.0 * (4 + g.mx + g.sw + (c.full ? g.lw + g.pw : 0));
     bytes += 2.0 * g.n_kv_heads * (per_tok * q.len + 256.0 * q.n_new);
   }
   const int MT = (max_r + 15) / 16;
@@ -162,7 +171,18 @@ static int launch_attention_group(cas_ctx* ctx, cas_kv* kv, const AttnCall* call
   int rc;
   {
     ProfScope scope(prof ? ctx : nullptr, c0.full ? PROF_ATTN_VERIFY : PROF_ATTN_DRAFT, bytes);
-    if (c0.full) {
+    if (g.mx) {
+      if (c0.full) {
+        rc = MT == 1   ? launch_mt<1, true, true>(ctx, b, grid)
+             : MT == 2 ? launch_mt<2, true, true>(ctx, b, grid)
+             : MT == 3 ? launch_mt<3, true, true>(ctx, b, grid)
+             : MT == 4 ? launch_mt<4, true, true>(ctx, b, grid)
+                       : launch_mt<5, true, true>(ctx, b, grid);
+      } else {
+        rc = MT == 1 ? launch_mt<1, false, true>(ctx, b, grid) : MT == 2 ? launch_mt<2, false, true>(ctx, b, grid)
+                                                                          : launch_mt<3, false, true>(ctx, b, grid);
+      }
+    } else if (c0.full) {
       rc = MT == 1   ? launch_mt<1, true>(ctx, b, grid)
            : MT == 2 ? launch_mt<2, true>(ctx, b, grid)
            : MT == 3 ? launch_mt<3, true>(ctx, b, grid)

@@ -3,7 +3,7 @@
 #include "attention_kernel.inl"
 
 namespace cas {
-template int launch_mt<1, false>(cas_ctx*, const AttnBatch&, dim3);
-template int launch_mt<2, false>(cas_ctx*, const AttnBatch&, dim3);
-template int launch_mt<3, false>(cas_ctx*, const AttnBatch&, dim3);
+template int launch_mt<1, false, false>(cas_ctx*, const AttnBatch&, dim3);
+template int launch_mt<2, false, false>(cas_ctx*, const AttnBatch&, dim3);
+template int launch_mt<3, false, false>(cas_ctx*, const AttnBatch&, dim3);
 }  // namespace cas

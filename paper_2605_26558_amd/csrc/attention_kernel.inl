@@ -96,7 +96,8 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v + row_rot<0x128>(v);
 }
 
-template <int MT, bool FULL, int T>
+// MX: the cache is in the shared-exponent form (one exponent per 32-channel block of a vector)
+template <int MT, bool FULL, int T, bool MX = false>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
   const AttnArgs a = attn_args_of(batch, blockIdx.z);
   if ((int)blockIdx.x >= a.nsplit) return;  // a shorter sequence of the launch: uniform for the workgroup
@@ -197,6 +198,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
   const uint32_t* vvf = a.verif_pool + tv * g.tile_verif_words;
   const uint32_t mk = live ? ks[r * 4 + j] : 0u;
   const uint32_t mv = live ? vs[r * 4 + j] : 0u;
+  int ek = 0, ev = 0;  // shared-exponent form: exponent of this thread's block (byte j of the token's word)
+  if constexpr (MX) {
+    if (live) {
+      ek = (int)((ks[kPT * 4 + r] >> (8 * j)) & 0xFFu);
+      ev = (int)((vs[kPT * 4 + r] >> (8 * j)) & 0xFFu);
+    }
+  }
   // ---- 2. queries to LDS: row rr = column * grp + member; rows past R are 0
   if (a.qkv) {
 #pragma unroll
@@ -213,7 +221,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
       *reinterpret_cast<uint4*>(Qs + rr * kQP + d) = qraw[it];
     }
   }
-  WordWindows<T, FULL> wk, wvw;
+  WordWindows<T, FULL, MX> wk, wvw;
   auto word_prefix = [&](uint32_t m) -> uint32_t {  // kept values of the token before word j
     const int cnt = __popc(m);
     const int b0 = quad_dpp<0x00>(cnt), b1 = quad_dpp<0x55>(cnt), b2 = quad_dpp<0xAA>(cnt);
@@ -225,11 +233,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
   const bool has_live = tok0 < a.len;
   auto load_v = [&]() {
     const uint32_t p = word_prefix(mv);
-    if (has_live) wvw.load(p, 32u * j - p, vs + kPT * 4 + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw);
+    if (has_live) wvw.load(p, 32u * j - p, vs + g.spec_off + r * g.sw, vvf + r * g.lw, vvf + kPT * g.lw + r * g.pw);
   };
   {
     const uint32_t p = word_prefix(mk);
-    if (has_live) wk.load(p, 32u * j - p, ks + kPT * 4 + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw);
+    if (has_live) wk.load(p, 32u * j - p, ks + g.spec_off + r * g.sw, kvf + r * g.lw, kvf + kPT * g.lw + r * g.pw);
   }
   // the draft form has registers to spare for both windows; the exact form asks for V later
   if constexpr (!FULL) load_v();
@@ -274,7 +282,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
           *reinterpret_cast<uint64_t*>(krow + 4 * q) = *reinterpret_cast<const uint64_t*>(src + 4 * q);
       }
     }
-    wk.decode(mk, (FULL && live) ? ~mk : 0u, [&](int bp, uint16_t v) { krow[bp] = v; });
+    wk.decode(mk, (FULL && live) ? ~mk : 0u, [&](int bp, uint16_t v) { krow[bp] = v; }, ek);
   }
   if constexpr (FULL) load_v();
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -342,7 +350,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
         for (int q = 0; q < 4; ++q) Vt[(33 * q + 1 + dq) * kVP + tr] = fv[cb][q];
       }
     }
-    wvw.decode(mv, (FULL && live) ? ~mv : 0u, [&](int bp, uint16_t v) { vcol[bp * kVP] = v; });
+    wvw.decode(mv, (FULL && live) ? ~mv : 0u, [&](int bp, uint16_t v) { vcol[bp * kVP] = v; }, ev);
   }
   __syncthreads();
   // ---- 7. O = P V ; wave w owns channels 32w .. 32w+31; partial result of this page
@@ -376,15 +384,15 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnBatch batch) {
   }
 }
 
-template <int MT, bool FULL>
+template <int MT, bool FULL, bool MX = false>
 int launch_mt(cas_ctx* ctx, const AttnBatch& a, dim3 grid) {
   constexpr size_t lds = attn_lds_bytes<MT>();
 #define CAS_LAUNCH(TV)                                                                                     \
   case TV: {                                                                                               \
     static LdsLimit lim;                                                                                   \
-    const int rc = allow_lds(ctx, (const void*)attn_partial_kernel<MT, FULL, TV>, lds, lim);               \
+    const int rc = allow_lds(ctx, (const void*)attn_partial_kernel<MT, FULL, TV, MX>, lds, lim);               \
     if (rc != CAS_OK) return rc;                                                                           \
-    hipLaunchKernelGGL((attn_partial_kernel<MT, FULL, TV>), grid, dim3(256), lds, ctx->stream, a);         \
+    hipLaunchKernelGGL((attn_partial_kernel<MT, FULL, TV, MX>), grid, dim3(256), lds, ctx->stream, a);         \
   } break;
   switch (a.common.g.t) {
     CAS_LAUNCH(0) CAS_LAUNCH(1) CAS_LAUNCH(2) CAS_LAUNCH(3) CAS_LAUNCH(4) CAS_LAUNCH(5) CAS_LAUNCH(6) CAS_LAUNCH(7)

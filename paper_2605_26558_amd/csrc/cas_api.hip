@@ -166,15 +166,16 @@ int cas_kv_desc_init(cas_kv_desc* d) {
     return CAS_EINVAL;
   if (d->fmt.trunc_bits < 0 || d->fmt.trunc_bits > 7 || d->fmt.keep_permille < 0 || d->fmt.keep_permille > 1000)
     return CAS_EINVAL;
-  if (d->fmt.exp_mode != 0) return CAS_ENOTSUP;
+  if (d->fmt.exp_mode != CAS_EXP_RAW && d->fmt.exp_mode != CAS_EXP_SHARED) return CAS_ENOTSUP;
+  const bool mx = d->fmt.exp_mode == CAS_EXP_SHARED;
   const int t = d->fmt.trunc_bits;
   int64_t K = ((int64_t)d->fmt.keep_permille * d->head_dim + 500) / 1000;
   K = std::max<int64_t>(0, std::min<int64_t>(d->head_dim, K));
   d->K = (int32_t)K;
-  d->sw = (int32_t)words(K * (16 - t));
+  d->sw = (int32_t)words(K * (mx ? 9 - t : 16 - t));
   d->lw = (int32_t)words(K * t);
   d->pw = (int32_t)words((d->head_dim - K) * 16);
-  d->tile_spec_bytes = up256((int64_t)d->page_tokens * (4 + d->sw) * 4);
+  d->tile_spec_bytes = up256((int64_t)d->page_tokens * (4 + (mx ? 1 : 0) + d->sw) * 4);
   d->tile_verif_bytes = up256((int64_t)d->page_tokens * (d->lw + d->pw) * 4);
   const int64_t tiles = (int64_t)d->n_layers * d->n_pages * 2 * d->n_kv_heads;
   d->spec_pool_bytes = tiles * d->tile_spec_bytes + kSlack;
@@ -197,6 +198,8 @@ int cas_kv_create(const cas_kv_desc* desc, void* d_spec_pool, void* d_verif_pool
   g.n_layers = chk.n_layers; g.n_kv_heads = chk.n_kv_heads; g.page_tokens = chk.page_tokens;
   g.n_pages = chk.n_pages; g.max_pages_per_seq = chk.max_pages_per_seq;
   g.K = chk.K; g.t = chk.fmt.trunc_bits; g.sw = chk.sw; g.lw = chk.lw; g.pw = chk.pw;
+  g.mx = chk.fmt.exp_mode == CAS_EXP_SHARED ? 1 : 0;
+  g.spec_off = chk.page_tokens * (g.mx ? 5 : 4);
   g.tile_spec_words = (int)(chk.tile_spec_bytes / 4);
   g.tile_verif_words = (int)(chk.tile_verif_bytes / 4);
   kv->d_spec = d_spec_pool; kv->d_verif = d_verif_pool; kv->d_page_table = d_page_table;

@@ -121,6 +121,23 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// ---- shared-exponent form (Sec. 4.2, the MX approach): value = (-1)^sign * magnitude * 2^(E - 134) ----
+// exponent field with 0 read as 1, and the significand with its hidden bit written out
+__device__ __forceinline__ int eff_exponent(uint32_t word) { return max((int)((word >> 7) & 0xFFu), 1); }
+__device__ __forceinline__ uint32_t significand(uint32_t word) {
+  return (word & 0x7Fu) | (((word >> 7) & 0xFFu) ? 0x80u : 0u);
+}
+
+// bf16 word of (-1)^sign * mag * 2^(E - 134): shift out the leading zeros of the magnitude and
+// take their count off the exponent; subnormal when the exponent runs out
+__device__ __forceinline__ uint32_t mx_word(uint32_t sign, int E, uint32_t mag) {
+  if (mag == 0u) return sign << 15;
+  const int lz = __clz(mag) - 24;
+  const int e = E - lz;
+  if (e >= 1) return (sign << 15) | ((uint32_t)e << 7) | ((mag << lz) & 0x7Fu);
+  return (sign << 15) | (mag << (max(E, 1) - 1));
+}
+
 // Raw windows of the packed streams at one 32-column bitmap word, before alignment: the words
 // that hold the word's kept fields (spec) and their dropped bits (lo) in KeptWindows, those of
 // its pruned values in PrunedWindows.  Loading and decoding are separate so the loads of the
@@ -160,17 +177,6 @@ struct KeptWindows {
     }
   }
 
-  // bf16 word of a shared-exponent value: the leading zeros of the magnitude come off the
-  // exponent; subnormal when it runs out (same arithmetic as the reconstruction in mx.hip)
-  static __device__ __forceinline__ uint32_t mx_bf16(uint32_t sign, int E, uint32_t mag) {
-    const int lz = __clz(mag) - 24;  // 8 for mag == 0
-    const int e = E - lz;
-    const uint32_t normal = ((uint32_t)e << 7) | ((mag << lz) & 0x7Fu);
-    const uint32_t sub = mag << (max(E, 1) - 1);
-    const uint32_t v = mag == 0u ? 0u : (e >= 1 ? normal : sub);
-    return (sign << 15) | v;
-  }
-
   // m: kept mask of the word; shared_exp: the word's shared exponent (MX only)
   template <class W>
   __device__ __forceinline__ void decode(uint32_t m, W&& write, int shared_exp = 0) const {
@@ -189,7 +195,7 @@ struct KeptWindows {
       if constexpr (MX) {
         uint32_t mag = (v & ((1u << (8 - T)) - 1u)) << T;
         if constexpr (FULL && T > 0) mag |= field_at<T, e>(wl);
-        v = mx_bf16(v >> (8 - T), shared_exp, mag);
+        v = mx_word(v >> (8 - T), shared_exp, mag);
       } else {
         v <<= T;
         if constexpr (FULL && T > 0) v |= field_at<T, e>(wl);
@@ -252,9 +258,9 @@ struct PrunedWindows {
 };
 
 // Both together (FULL) or the speculation data alone: pm is 0 and unused without FULL.
-template <int T, bool FULL>
+template <int T, bool FULL, bool MX = false>
 struct WordWindows {
-  KeptWindows<T, FULL> k;
+  KeptWindows<T, FULL, MX> k;
   PrunedWindows pr;
 
   __device__ __forceinline__ void load(uint32_t p, uint32_t u, const uint32_t* __restrict__ sp_row,
@@ -264,8 +270,8 @@ struct WordWindows {
   }
 
   template <class W>
-  __device__ __forceinline__ void decode(uint32_t m, uint32_t pm, W&& write) const {
-    k.decode(m, write);
+  __device__ __forceinline__ void decode(uint32_t m, uint32_t pm, W&& write, int shared_exp = 0) const {
+    k.decode(m, write, shared_exp);
     if constexpr (FULL) pr.decode(pm, write);
   }
 };

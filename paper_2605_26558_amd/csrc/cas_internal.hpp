@@ -39,6 +39,10 @@ struct KvGeom {
   int n_layers, n_kv_heads, page_tokens, n_pages, max_pages_per_seq;
   int K, t, sw, lw, pw;
   int tile_spec_words, tile_verif_words;
+  // Shared-exponent form of the cache (mx != 0): a tile's speculation part is bitmap [64][4] |
+  // one word per token with the exponents of its four 32-channel blocks | fields of 9-t bits
+  // (sw words per token); spec_off = words in front of the field stream (256 raw, 320 shared).
+  int mx, spec_off;
 };
 }  // namespace cas
 

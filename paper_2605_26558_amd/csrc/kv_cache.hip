@@ -47,23 +47,42 @@ __global__ __launch_bounds__(64) void kv_append_kernel(KvGeom g, uint32_t* spec_
   uint32_t* st_spec = stage;
   uint32_t* st_lo = stage + g.sw;
   uint32_t* st_pr = st_lo + g.lw;
-  const int fw = 16 - g.t;
+  const int fw = g.mx ? 9 - g.t : 16 - g.t;
   const uint32_t lomask = (1u << g.t) - 1u;
+  // shared-exponent form: the exponent of a 32-channel block is the largest among its kept values
+  // (0 for a block without any); lanes 0..31 / 32..63 hold blocks 0 / 1 in v0 and blocks 2 / 3 in v1
+  int E0 = 0, E1 = 0;
+  if (g.mx) {
+    E0 = k0 ? eff_exponent(v0) : 0;
+    E1 = k1 ? eff_exponent(v1) : 0;
+#pragma unroll
+    for (int d = 1; d < 32; d <<= 1) {
+      E0 = max(E0, __shfl_xor(E0, d));
+      E1 = max(E1, __shfl_xor(E1, d));
+    }
+  }
   auto put = [&](uint32_t* s, uint32_t bit, uint32_t v, int width) {
     uint32_t w = bit >> 5, sh = bit & 31;
     atomicOr(&s[w], v << sh);
     if (sh + width > 32) atomicOr(&s[w + 1], v >> (32 - sh));
   };
-  auto emit = [&](bool kept, uint32_t v, uint32_t rank, uint32_t col) {
+  auto emit = [&](bool kept, uint32_t v, uint32_t rank, uint32_t col, int E) {
     if (kept) {
-      put(st_spec, rank * fw, v >> g.t, fw);
-      if (g.t) put(st_lo, rank * g.t, v & lomask, g.t);
+      if (g.mx) {  // sign + magnitude: the significand shifted down to the block's exponent
+        const int sh = E - eff_exponent(v);
+        const uint32_t mag = sh < 8 ? significand(v) >> sh : 0u;
+        put(st_spec, rank * fw, ((v >> 15) << (8 - g.t)) | (mag >> g.t), fw);
+        if (g.t) put(st_lo, rank * g.t, mag & lomask, g.t);
+      } else {
+        put(st_spec, rank * fw, v >> g.t, fw);
+        if (g.t) put(st_lo, rank * g.t, v & lomask, g.t);
+      }
     } else {
       put(st_pr, (col - rank) * 16, v, 16);
     }
   };
-  emit(k0, v0, r0, (uint32_t)lane);
-  emit(k1, v1, r1, (uint32_t)lane + 64u);
+  emit(k0, v0, r0, (uint32_t)lane, E0);
+  emit(k1, v1, r1, (uint32_t)lane + 64u, E1);
   __syncthreads();
 
   const int pos = pos0 + tok;
@@ -77,7 +96,11 @@ __global__ __launch_bounds__(64) void kv_append_kernel(KvGeom g, uint32_t* spec_
     uint64_t m = lane < 2 ? m01 : m23;
     ts[row * 4 + lane] = (uint32_t)(m >> ((lane & 1) * 32));
   }
-  uint32_t* dspec = ts + g.page_tokens * 4 + row * g.sw;
+  if (g.mx) {  // the four block exponents of the vector, block j in byte j
+    const int e01 = __shfl(E0, 0) | (__shfl(E0, 32) << 8), e23 = __shfl(E1, 0) | (__shfl(E1, 32) << 8);
+    if (lane == 0) ts[g.page_tokens * 4 + row] = (uint32_t)(e01 | (e23 << 16));
+  }
+  uint32_t* dspec = ts + g.spec_off + row * g.sw;
   uint32_t* dlo = tv + row * g.lw;
   uint32_t* dpr = tv + g.page_tokens * g.lw + row * g.pw;
   for (int i = lane; i < g.sw; i += 64) dspec[i] = st_spec[i];
@@ -107,11 +130,17 @@ __global__ __launch_bounds__(128) void kv_read_kernel(KvGeom g, const uint32_t* 
   for (int i = 0; i < j; ++i) p += __popc(bm[i]);
   const uint32_t m = bm[j];
   p += __popc(m & ((1u << c) - 1u));
-  const int fw = 16 - g.t;
+  const int fw = g.mx ? 9 - g.t : 16 - g.t;
   uint32_t v;
   if ((m >> c) & 1u) {
-    v = read_field(ts + g.page_tokens * 4 + row * g.sw, p * fw, fw) << g.t;
-    if (full && g.t) v |= read_field(tv + row * g.lw, p * g.t, g.t);
+    v = read_field(ts + g.spec_off + row * g.sw, p * fw, fw);
+    const uint32_t lo = (full && g.t) ? read_field(tv + row * g.lw, p * g.t, g.t) : 0u;
+    if (g.mx) {
+      const int E = (int)((ts[g.page_tokens * 4 + row] >> (8 * j)) & 0xFFu);
+      v = mx_word(v >> (8 - g.t), E, ((v & ((1u << (8 - g.t)) - 1u)) << g.t) | lo);
+    } else {
+      v = (v << g.t) | lo;
+    }
   } else {
     v = full ? read_field(tv + g.page_tokens * g.lw + row * g.pw, ((uint32_t)col - p) * 16, 16) : 0u;
   }

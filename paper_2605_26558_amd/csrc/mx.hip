@@ -27,22 +27,6 @@ __device__ __forceinline__ void or_field(uint32_t* row, uint32_t index, int widt
   if (sh + width > 32) atomicOr(&row[(bit >> 5) + 1], v >> (32u - sh));
 }
 
-// exponent field with 0 read as 1, and the significand with its hidden bit written out
-__device__ __forceinline__ int eff_exponent(uint32_t word) { return max((int)((word >> 7) & 0xFFu), 1); }
-__device__ __forceinline__ uint32_t significand(uint32_t word) {
-  return (word & 0x7Fu) | (((word >> 7) & 0xFFu) ? 0x80u : 0u);
-}
-
-// bf16 word of (-1)^sign * mag * 2^(E - 134): shift out the leading zeros of the magnitude and
-// take their count off the exponent; subnormal when the exponent runs out
-__device__ __forceinline__ uint32_t mx_word(uint32_t sign, int E, uint32_t mag) {
-  if (mag == 0u) return sign << 15;
-  const int lz = __clz(mag) - 24;
-  const int e = E - lz;
-  if (e >= 1) return (sign << 15) | ((uint32_t)e << 7) | ((mag << lz) & 0x7Fu);
-  return (sign << 15) | (mag << (max(E, 1) - 1));
-}
-
 // ---- re-coding: one wave per row, one bitmap word (= one block) per lane ---------------------
 // field and lo regions are zero before this kernel; bits are OR-ed in.
 __global__ __launch_bounds__(256) void mx_encode_kernel(MxArgs a) {

@@ -225,3 +225,91 @@ def test_attention_head_layouts_and_cache_formats(env, nq, nkv, ncols, full, kee
     # the last column alone gets the bits it gets in company
     o1 = _host(B.cas_attention(ctx, kv, 0, 0, full, _dev(torch, Q[ncols - 1:]), _dev(torch, Kn), _dev(torch, Vn)))
     np.testing.assert_array_equal(o1[0], out[ncols - 1])
+
+
+# ---- the cache in the shared-exponent form (Sec. 4.2, the MX approach; Sec. 5.1 encoder) ----------
+
+@pytest.mark.parametrize("keep,t", [(600, 4), (1000, 4), (250, 0), (0, 4), (500, 7)])
+def test_kv_append_shared_exponents_is_bit_exact(env, keep, t):
+    """Online formatting with shared exponents: every region of a tile against the oracle's
+    re-coding of the same vectors, and both read-backs (converted vector / draft view)."""
+    torch, B, ctx = env
+    print(f"case keep={keep} t={t}", flush=True)
+    heads, layers, ntok = 2, 2, 75
+    perm = torch.tensor([[3, 0, 2, 1]], dtype=torch.int32)
+    kv = B.KVCache(ctx, layers, heads, n_pages=4, max_seqs=1, max_pages_per_seq=4, keep_permille=keep,
+                   trunc_bits=t, page_table=perm, exp_mode=B.CAS_EXP_SHARED)
+    Kh = synth.kv_tensor(ntok, heads, 128, seed=1)
+    Vh = synth.kv_tensor(ntok, heads, 128, seed=2, outlier_channels=0)
+    Kh[5, 0, :] = Kh[5, 0, 0]
+    specials = np.array([0x0000, 0x8000, 0x0001, 0x807F, 0x7F7F, 0x7F80, 0xFF80, 0x7FC0, 0xFFFF, 0x0080],
+                        dtype=np.uint16)
+    Kh[7, 1, 30:40] = specials                                       # spans two blocks
+    Vh[8, 0, :] = 0x0003                                             # a vector of subnormals
+    for layer in range(layers):
+        B.cas_kv_append(ctx, kv, layer, 0, _dev(torch, Kh[:70]), _dev(torch, Vh[:70]))
+    B.cas_kv_set_len(kv, 0, 70)
+    for layer in range(layers):
+        B.cas_kv_append(ctx, kv, layer, 0, _dev(torch, Kh[70:]), _dev(torch, Vh[70:]))
+    B.cas_kv_set_len(kv, 0, ntok)
+    mk = O.to_mx(O.encode_kv(Kh.reshape(-1, 128), keep, t))
+    mv = O.to_mx(O.encode_kv(Vh.reshape(-1, 128), keep, t))
+    for layer in range(layers):
+        Kf, Vf = B.cas_kv_read(ctx, kv, layer, 0, 0, ntok, full=True)
+        np.testing.assert_array_equal(_host(Kf).reshape(-1, 128), O.decode_full_mx(mk))
+        np.testing.assert_array_equal(_host(Vf).reshape(-1, 128), O.decode_full_mx(mv))
+        Kd, Vd = B.cas_kv_read(ctx, kv, layer, 0, 0, ntok, full=False)
+        np.testing.assert_array_equal(_host(Kd).reshape(-1, 128), O.decode_draft_mx(mk))
+        np.testing.assert_array_equal(_host(Vd).reshape(-1, 128), O.decode_draft_mx(mv))
+    d = kv.desc
+    spec = kv.spec_pool.cpu().numpy()
+    verif = kv.verif_pool.cpu().numpy()
+    tile = ((1 * d.n_pages + 3) * 2 + 0) * heads + 1                  # layer 1, K, head 1, page slot 0 -> page 3
+    ts = spec[tile * d.tile_spec_bytes: (tile + 1) * d.tile_spec_bytes].view("<u4")
+    tv = verif[tile * d.tile_verif_bytes: (tile + 1) * d.tile_verif_bytes].view("<u4")
+    p = O.encode_kv(Kh[:64, 1, :], keep, t)
+    m = O.to_mx(p)
+    assert d.sw == m.field.shape[1] and d.lw == m.lo.shape[1]
+    np.testing.assert_array_equal(ts[: 64 * 4].reshape(64, 4), p.bitmap)
+    np.testing.assert_array_equal(ts[64 * 4: 64 * 5].view(np.uint8).reshape(64, 4), m.sexp)
+    np.testing.assert_array_equal(ts[64 * 5: 64 * (5 + d.sw)].reshape(64, d.sw), m.field)
+    np.testing.assert_array_equal(tv[: 64 * d.lw].reshape(64, d.lw), m.lo)
+    np.testing.assert_array_equal(tv[64 * d.lw: 64 * (d.lw + d.pw)].reshape(64, d.pw), p.pruned)
+
+
+@pytest.mark.parametrize("len_cache,ncols,n_new,full", [
+    (150, 1, 1, False), (150, 1, 3, False), (64, 1, 2, False), (1, 1, 1, False),
+    (150, 5, 5, True), (130, 7, 7, True), (200, 9, 9, True), (63, 1, 1, True),
+])
+def test_attention_over_a_shared_exponent_cache_matches_oracle(env, len_cache, ncols, n_new, full):
+    torch, B, ctx = env
+    print(f"case len={len_cache} ncols={ncols} n_new={n_new} full={full}", flush=True)
+    nq, nkv, layers = 8, 2, 2
+    kv = B.KVCache(ctx, layers, nkv, n_pages=8, max_seqs=2, max_pages_per_seq=4,
+                   page_table=torch.tensor([[5, 1, 7, 2], [0, 3, 4, 6]], dtype=torch.int32),
+                   exp_mode=B.CAS_EXP_SHARED)
+    seq, layer = 1, 1
+    Kh = synth.kv_tensor(len_cache, nkv, 128, seed=3)
+    Vh = synth.kv_tensor(len_cache, nkv, 128, seed=4, outlier_channels=0)
+    B.cas_kv_append(ctx, kv, layer, seq, _dev(torch, Kh), _dev(torch, Vh))
+    B.cas_kv_set_len(kv, seq, len_cache)
+    Q = synth.normal_bf16((ncols, nq, 128), 1.0, seed=5)
+    Kn = synth.kv_tensor(n_new, nkv, 128, seed=6)
+    Vn = synth.kv_tensor(n_new, nkv, 128, seed=7, outlier_channels=0)
+    out = _host(B.cas_attention(ctx, kv, layer, seq, full, _dev(torch, Q), _dev(torch, Kn), _dev(torch, Vn)))
+    mk = O.to_mx(O.encode_kv(Kh.reshape(-1, 128), 600, 4))
+    mv = O.to_mx(O.encode_kv(Vh.reshape(-1, 128), 600, 4))
+    dec = O.decode_full_mx if full else O.decode_draft_mx
+    Kc = dec(mk).reshape(len_cache, nkv, 128)
+    Vc = dec(mv).reshape(len_cache, nkv, 128)
+    ref = _ref_attention(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv)
+    reff = O.bf16_to_f64(ref)
+    err = np.abs(O.bf16_to_f64(out) - reff)
+    tol = _attn_tol(Q, Kc, Vc, Kn, Vn, ncols, nq, nkv, reff)
+    assert (err <= tol).all(), float((err / tol).max())
+    if full and ncols > 1:
+        for c in (0, ncols - 1):
+            vis = n_new - ncols + c + 1
+            o1 = _host(B.cas_attention(ctx, kv, layer, seq, True, _dev(torch, Q[c:c + 1]),
+                                       _dev(torch, Kn[:vis]), _dev(torch, Vn[:vis])))
+            np.testing.assert_array_equal(o1[0], out[c])

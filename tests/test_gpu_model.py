@@ -25,7 +25,7 @@ def _dev(torch, a):
     return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
 
 
-def gpu_model(torch, B, ctx, weights, keep, t, max_cols):
+def gpu_model(torch, B, ctx, weights, keep, t, max_cols, kv_exp_mode=0):
     layers = []
     for lw in weights["layers"]:
         L = {n: B.cas_encode_weight(ctx, _dev(torch, lw[n]), keep, t) for n in ("wqkv", "wo", "wgu", "wd")}
@@ -36,7 +36,7 @@ def gpu_model(torch, B, ctx, weights, keep, t, max_cols):
     model = B.Model(ctx, SHAPE, layers, head, _dev(torch, weights["embed"]), _dev(torch, weights["g_final"]), rope,
                     max_cols)
     kv = B.KVCache(ctx, SHAPE.n_layers, SHAPE.n_kv_heads, n_pages=2, max_seqs=1, max_pages_per_seq=2,
-                   keep_permille=keep, trunc_bits=t)
+                   keep_permille=keep, trunc_bits=t, exp_mode=kv_exp_mode)
     return model, kv
 
 
@@ -160,20 +160,23 @@ def test_model_steps_on_unary_coded_weights(env):
     np.testing.assert_array_equal(back[2], raw[2])
 
 
-def test_model_steps_on_shared_exponent_weights(env):
+@pytest.mark.parametrize("kv_mx", [False, True])
+def test_model_steps_on_shared_exponent_weights(env, kv_mx):
     """Every linear layer in the shared-exponent form (Sec. 4.2, the MX approach): the target is
-    the converted model.  Verification and draft logits against the oracle run in that mode."""
+    the converted model.  Verification and draft logits against the oracle run in that mode;
+    kv_mx: the cache in the shared-exponent form as well (the whole "Cassandra-2" configuration)."""
     torch, B, ctx = env
     keep, t = 600, 4
     weights = synth.model_weights(SHAPE, seed=1)
-    model, kv = gpu_model(torch, B, ctx, weights, keep, t, max_cols=8)
+    model, kv = gpu_model(torch, B, ctx, weights, keep, t, max_cols=8, kv_exp_mode=B.CAS_EXP_SHARED if kv_mx else 0)
     layers, head = model._keep[0], model._keep[1]
     for l, L in enumerate(layers):
         for which, name in enumerate(("wqkv", "wo", "wgu", "wd")):
             model.use_mx(l, which, B.cas_mx_encode(ctx, L[name]))
     model.use_mx(-1, 0, B.cas_mx_encode(ctx, head))
     tab = synth.rope_table(MAX_POS, SHAPE.head_dim, SHAPE.rope_theta)
-    om = O.OracleModel(SHAPE, weights, tab, w_keep=keep, w_t=t, kv_keep=keep, kv_t=t, exp_mode="mx")
+    om = O.OracleModel(SHAPE, weights, tab, w_keep=keep, w_t=t, kv_keep=keep, kv_t=t, exp_mode="mx",
+                       kv_exp_mode="mx" if kv_mx else "raw")
     prompt = synth.token_ids(6, SHAPE.vocab, seed=5)
     toks = torch.from_numpy(prompt).cuda()
     tgt = torch.empty(6, dtype=torch.int32, device="cuda")
@@ -181,7 +184,7 @@ def test_model_steps_on_shared_exponent_weights(env):
     B.cas_verify_step(ctx, model, kv, 0, toks, 5, tgt, vl)
     ref, new_kv = om.forward(prompt, draft=False)
     r = _check_logits(vl.cpu().numpy().astype(np.float64), ref, _logit_tol(om, False), "verify, shared exponents")
-    record_ratio("tiny_model_verify_logits_mx", r)
+    record_ratio("tiny_model_verify_logits_mx" + ("_kv" if kv_mx else ""), r)
     B.cas_commit(ctx, model, kv, 0, 5)
     om.append_kv(new_kv, 6)
     cur = torch.tensor([int(np.argmax(ref[5]))], dtype=torch.int32, device="cuda")
@@ -191,7 +194,7 @@ def test_model_steps_on_shared_exponent_weights(env):
     extra = [(np.zeros((0, SHAPE.n_kv_heads, 128), np.uint16),) * 2 for _ in range(SHAPE.n_layers)]
     oref, _ = om.forward([int(cur.item())], draft=True, extra_kv=extra)
     r = _check_logits(dl.cpu().numpy().astype(np.float64), oref, _logit_tol(om, True), "draft, shared exponents")
-    record_ratio("tiny_model_draft_logits_mx", r)
+    record_ratio("tiny_model_draft_logits_mx" + ("_kv" if kv_mx else ""), r)
     # speculation against the converted model is lossless: the stream of rounds equals plain decoding
     gen_prompt = synth.token_ids(5, SHAPE.vocab, seed=9)
     plain, _ = _gpu_generate(torch, B, ctx, model, kv, gen_prompt, 16, 0)

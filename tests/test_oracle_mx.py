@@ -186,3 +186,52 @@ def test_model_in_shared_exponent_mode_reduces_to_the_raw_mode_when_blocks_have_
     a, _ = O.OracleModel(shape, weights2, tab, exp_mode="raw").forward(toks, draft=False)
     b, _ = O.OracleModel(shape, weights2, tab, exp_mode="mx").forward(toks, draft=False)
     assert np.abs(a - b).max() > 0
+
+
+def test_cache_in_shared_exponent_mode_against_real_arithmetic_and_the_raw_mode():
+    """The oracle model's cache with kv_exp_mode="mx" (Sec. 5.1 encoder: exponent compression of
+    the speculation group before storing): what the target pass reads back is, for a kept
+    value, sign * floor(significand * 2^(e - E)) * 2^(E - 134) with E the largest exponent among
+    the kept values of its 32-channel block, restated here in real arithmetic; unselected
+    values come back as they went in; vectors whose blocks hold one exponent come back
+    unchanged, as in the raw mode."""
+    shape = synth.TINY
+    weights = synth.model_weights(shape, seed=4)
+    tab = synth.rope_table(32, shape.head_dim, shape.rope_theta)
+    keep, t = 600, 4
+    mx = O.OracleModel(shape, weights, tab, kv_keep=keep, kv_t=t, kv_exp_mode="mx")
+    raw = O.OracleModel(shape, weights, tab, kv_keep=keep, kv_t=t, kv_exp_mode="raw")
+    rng = np.random.default_rng(3)
+    ncols, H, D = 3, shape.n_kv_heads, shape.head_dim
+    wide = O.f64_to_bf16(rng.standard_normal((ncols, H, D)) * np.exp2(rng.integers(-6, 1, (ncols, H, D)).astype(float)))
+    exps = rng.integers(110, 130, (ncols, H, D // 32)).repeat(32, axis=2)
+    flat = ((rng.integers(0, 2, (ncols, H, D)) << 15) | (exps << 7) | rng.integers(0, 128, (ncols, H, D))).astype(np.uint16)
+    new_kv = [(wide, flat) for _ in range(shape.n_layers)]
+    mx.append_kv(new_kv, ncols)
+    raw.append_kv(new_kv, ncols)
+    K_mx, V_mx = mx._cache_kv(0, draft=False)
+    K_raw, V_raw = raw._cache_kv(0, draft=False)
+    np.testing.assert_array_equal(V_mx, flat)            # one exponent per block: nothing is lost
+    np.testing.assert_array_equal(V_raw, flat)
+    np.testing.assert_array_equal(K_raw, wide)           # the raw mode is lossless for any vector
+    # K with mixed exponents: every value against the conversion in real arithmetic
+    for c in range(ncols):
+        for h in range(H):
+            v = wide[c, h]
+            mask = O.unpack_mask(O.encode_kv(v[None, :], keep, t))[0]
+            e = np.maximum((v >> 7) & 0xFF, 1).astype(int)
+            sig = ((v & 0x7F) | np.where(((v >> 7) & 0xFF) != 0, 0x80, 0)).astype(int)
+            for b in range(D // 32):
+                sl = slice(32 * b, 32 * b + 32)
+                kept = mask[sl]
+                if not kept.any():
+                    continue
+                E = e[sl][kept].max()
+                want = np.where(v[sl] >> 15, -1.0, 1.0) * np.floor(sig[sl] * np.exp2((e[sl] - E).astype(float))) * 2.0 ** (E - 134)
+                got = O.bf16_to_f64(K_mx[c, h, sl])
+                np.testing.assert_array_equal(got[kept], want[kept])
+                np.testing.assert_array_equal(K_mx[c, h, sl][~kept], v[sl][~kept])
+    # the draft pass sees sign + leading magnitude bits of the kept values and zeros elsewhere
+    K_d, _ = mx._cache_kv(0, draft=True)
+    assert (np.abs(O.bf16_to_f64(K_d)) <= np.abs(O.bf16_to_f64(K_mx))).all()
+    assert (K_d[~np.stack([[O.unpack_mask(O.encode_kv(wide[c, h][None, :], keep, t))[0] for h in range(H)] for c in range(ncols)])] == 0).all()
