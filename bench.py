@@ -46,6 +46,9 @@ def parse():
                          "oracle's time for whole units of the workload, host only, minutes; tune: format "
                          "search on measured draft / verification pass times with user-supplied acceptance rates; "
                          "exp-modes: pass times with raw, unary-coded and shared exponents on the same model")
+    ap.add_argument("--kv-exp-mode", choices=["raw", "shared"], default="raw",
+                    help="exponents of the KV cache: raw (the metric's configuration) or shared per 32 channels "
+                         "(Sec. 4.2, the MX approach; context figures)")
     ap.add_argument("--alpha", type=float, default=0.8, help="tune: acceptance rate assumed for every grid point")
     ap.add_argument("--alpha-grid", default=None, help="tune: JSON file with a [n_keep][n_trunc] table of acceptance rates")
     ap.add_argument("--tune-keeps", default="700,600,500,400", help="tune: kept fractions in 1/1000 (Sec. 7.2.2 grid)")

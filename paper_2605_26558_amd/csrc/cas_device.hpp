@@ -131,11 +131,12 @@ __device__ __forceinline__ uint32_t significand(uint32_t word) {
 // bf16 word of (-1)^sign * mag * 2^(E - 134): shift out the leading zeros of the magnitude and
 // take their count off the exponent; subnormal when the exponent runs out
 __device__ __forceinline__ uint32_t mx_word(uint32_t sign, int E, uint32_t mag) {
-  if (mag == 0u) return sign << 15;
-  const int lz = __clz(mag) - 24;
+  const int lz = __clz(mag) - 24;  // 8 for mag == 0 (selected away below)
   const int e = E - lz;
-  if (e >= 1) return (sign << 15) | ((uint32_t)e << 7) | ((mag << lz) & 0x7Fu);
-  return (sign << 15) | (mag << (max(E, 1) - 1));
+  const uint32_t normal = ((uint32_t)e << 7) | ((mag << lz) & 0x7Fu);
+  const uint32_t sub = mag << (max(E, 1) - 1);
+  const uint32_t v = mag == 0u ? 0u : (e >= 1 ? normal : sub);  // selects, no branches: called per value in walks
+  return (sign << 15) | v;
 }
 
 // Raw windows of the packed streams at one 32-column bitmap word, before alignment: the words

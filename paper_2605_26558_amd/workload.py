@@ -162,8 +162,10 @@ class ModelRoundWorkload:
         self.model = B.Model(ctx, shape, layers, head, embed, self.g_final, rope,
                              max_cols=min(32, nb * (self.k + 1)), max_seqs=nb)
         pages = (max_pos + 63) // 64
+        kv_mx = getattr(args, "kv_exp_mode", "raw") == "shared"
         self.kv = B.KVCache(ctx, shape.n_layers, shape.n_kv_heads, n_pages=pages * nb, max_seqs=nb,
-                            max_pages_per_seq=pages, keep_permille=args.keep, trunc_bits=args.trunc)
+                            max_pages_per_seq=pages, keep_permille=args.keep, trunc_bits=args.trunc,
+                            exp_mode=B.CAS_EXP_SHARED if kv_mx else B.CAS_EXP_RAW)
         # synthetic cache contents
         chunk = 1024
         for layer in range(shape.n_layers):
@@ -186,8 +188,9 @@ class ModelRoundWorkload:
         self.draft_w = sum(m.desc.rows * (m.desc.bw + m.desc.sw) * 4 for m in mats)
         self.verify_w = sum(m.desc.rows * (m.desc.bw + m.desc.sw + m.desc.lw + m.desc.pw) * 4 for m in mats)
         d = self.kv.desc
-        per_tok_draft = 2 * shape.n_layers * shape.n_kv_heads * 4 * (4 + d.sw)
-        per_tok_full = 2 * shape.n_layers * shape.n_kv_heads * 4 * (4 + d.sw + d.lw + d.pw)
+        bmw = 5 if kv_mx else 4   # bitmap words (+ one word of block exponents) per cached vector
+        per_tok_draft = 2 * shape.n_layers * shape.n_kv_heads * 4 * (bmw + d.sw)
+        per_tok_full = 2 * shape.n_layers * shape.n_kv_heads * 4 * (bmw + d.sw + d.lw + d.pw)
         self.draft_kv = per_tok_draft * self.ctx_len
         self.verify_kv = per_tok_full * self.ctx_len
         self.values = sum(m.desc.rows * m.desc.cols for m in mats)
@@ -205,6 +208,7 @@ class ModelRoundWorkload:
                                    f"(synthetic K/V, 4 outlier key channels per head), draft length k={self.k}, "
                                    "greedy acceptance; weights + KV in Cassandra format",
                        "keep_permille": args.keep, "trunc_bits": args.trunc, "k": self.k, "context": self.ctx_len,
+                       "kv_exp_mode": "shared" if kv_mx else "raw",
                        "step": "one speculative round: k draft passes + verify(k+1) + accept + commit"}
 
     def step(self):
@@ -641,7 +645,8 @@ def run_exp_modes(B, args, dev):
                 "bits_per_value_draft": 8.0 * draft_bytes / wl.values, "bits_per_value_verify": 8.0 * verify_bytes / wl.values}
 
     out = {"workload": wl.config["workload"], "k": wl.k, "context": wl.ctx_len,
-           "keep_permille": args.keep, "trunc_bits": args.trunc}
+           "keep_permille": args.keep, "trunc_bits": args.trunc, "kv_exp_mode": wl.config["kv_exp_mode"],
+           "kv_bytes_draft_pass": kv_d, "kv_bytes_verify_pass": kv_v}
     out["raw"] = report(wl.draft_w, wl.verify_w)
     # unary-coded exponents: lossless, verification gives the raw form's bits
     d_b = v_b = 0
