@@ -321,22 +321,35 @@ def test_multi_sequence_passes_equal_single_sequence_passes(env):
             assert torch.equal(Ka, Kb) and torch.equal(Va, Vb)
 
 
-@pytest.mark.parametrize("max_cols,k,nseq", [(12, 3, 3), (8, 3, 3), (4, 3, 3), (20, 4, 4), (32, 7, 4)])
-def test_multi_sequence_round_equals_single_sequence_rounds(env, max_cols, k, nseq):
+@pytest.mark.parametrize("max_cols,k,nseq,form", [(12, 3, 3, "raw"), (8, 3, 3, "raw"), (4, 3, 3, "raw"),
+                                                  (20, 4, 4, "raw"), (32, 7, 4, "raw"),
+                                                  (12, 3, 3, "unary"), (20, 4, 4, "unary"),
+                                                  (12, 3, 3, "mx"), (20, 4, 4, "mx")])
+def test_multi_sequence_round_equals_single_sequence_rounds(env, max_cols, k, nseq, form):
     """cas_spec_round_multi emits, sequence by sequence, the stream cas_spec_round emits, also
     when the verification columns of the sequences need two or three passes, and when one pass
-    carries more than 16 columns (20 and 32: the second column block of the verify GEMM)."""
+    carries more than 16 columns (20 and 32: the second column block of the verify GEMM).
+    form: the exponents of every linear layer raw, unary-coded, or shared (then the cache has
+    shared exponents as well)."""
     torch, B, ctx = env
-    print(f"case max_cols={max_cols} k={k} nseq={nseq}", flush=True)
+    print(f"case max_cols={max_cols} k={k} nseq={nseq} form={form}", flush=True)
     keep, t = 600, 4
     weights = synth.model_weights(SHAPE, seed=2)
     model, _ = gpu_model(torch, B, ctx, weights, keep, t, max_cols=12)
     # same weights, room for three sequences
     layers, head, embed, g_final, rope = model._keep
     model = B.Model(ctx, SHAPE, layers, head, embed, g_final, rope, max_cols=max_cols, max_seqs=nseq)
+    if form != "raw":
+        recode = B.cas_unary_encode if form == "unary" else B.cas_mx_encode
+        use = model.use_unary if form == "unary" else model.use_mx
+        for l, L in enumerate(layers):
+            for which, name in enumerate(("wqkv", "wo", "wgu", "wd")):
+                use(l, which, recode(ctx, L[name]))
+        use(-1, 0, recode(ctx, head))
     def cache():
         return B.KVCache(ctx, SHAPE.n_layers, SHAPE.n_kv_heads, n_pages=2 * nseq, max_seqs=nseq, max_pages_per_seq=2,
-                         keep_permille=keep, trunc_bits=t)
+                         keep_permille=keep, trunc_bits=t,
+                         exp_mode=B.CAS_EXP_SHARED if form == "mx" else B.CAS_EXP_RAW)
     kv_a, kv_b = cache(), cache()
     prompts = [synth.token_ids(n, SHAPE.vocab, seed=40 + n) for n in (5, 20, 33, 11)[:nseq]]
     for kv in (kv_a, kv_b):
