@@ -129,3 +129,28 @@ def test_speed_model_and_measured_format_search_against_oracle():
         B.cas_speed_model(1.5, 4, 1.0, 2.0, 2.0)
     with pytest.raises(B.CasError):
         B.cas_speed_model(0.5, 4, 1.0, 0.0, 2.0)
+
+
+def test_kv_geometry_of_both_exponent_modes_in_closed_form():
+    """cas_kv_desc_init (host only): stream widths and tile sizes of the raw and the shared-exponent
+    cache against the sizes the layout description in the header gives, for several formats; a
+    mode the cache has no kernels for is refused as unsupported."""
+    from paper_2605_26558_amd import binding as B
+    lib = B._lib()
+    words = lambda bits: (bits + 31) // 32
+    up256 = lambda n: (n + 255) // 256 * 256
+    for keep, t in ((600, 4), (1000, 0), (250, 7), (0, 4)):
+        K = min(128, max(0, (keep * 128 + 500) // 1000))
+        for mode, fw_bits, extra in ((B.CAS_EXP_RAW, 16 - t, 0), (B.CAS_EXP_SHARED, 9 - t, 1)):
+            d = B.cas_kv_desc()
+            d.n_layers, d.n_kv_heads, d.head_dim, d.page_tokens = 3, 2, 128, 64
+            d.n_pages, d.max_seqs, d.max_pages_per_seq = 5, 1, 5
+            d.fmt = B.cas_fmt(keep, t, mode)
+            assert lib.cas_kv_desc_init(ctypes.byref(d)) == B.CAS_OK
+            assert (d.K, d.sw, d.lw, d.pw) == (K, words(K * fw_bits), words(K * t), words((128 - K) * 16))
+            assert d.tile_spec_bytes == up256(64 * (4 + extra + d.sw) * 4)
+            assert d.tile_verif_bytes == up256(64 * (d.lw + d.pw) * 4)
+            tiles = 3 * 5 * 2 * 2
+            assert d.spec_pool_bytes >= tiles * d.tile_spec_bytes and d.verif_pool_bytes >= tiles * d.tile_verif_bytes
+    d.fmt = B.cas_fmt(600, 4, 1)
+    assert lib.cas_kv_desc_init(ctypes.byref(d)) == B.CAS_ENOTSUP
