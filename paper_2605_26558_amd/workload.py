@@ -459,7 +459,7 @@ class ModelRoundWorkload:
                "context_own_bf16_decode_tokens_per_s": None if t_dense_step is None else 1e3 / t_dense_step,
                "tokens_per_s_at_assumed_acceptance": synth_tps,
                "tokens_per_s_forced_acceptance_schedule": {f"alpha={a}": self._forced_rounds(a)
-                                                           for a in (0.6, 0.8, 1.0)},
+                                                           for a in (0.0, 0.6, 0.8, 1.0)},
                "kernels": {}}
         for name, (n, ms, by) in self.prof.items():
             if n:
