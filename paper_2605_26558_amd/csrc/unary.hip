@@ -218,7 +218,16 @@ __global__ __launch_bounds__(64) void unary_expand_kernel(UnaryArgs a, int row0,
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   const int mb = 7 - a.t, SW = 8 - a.t, FW = 16 - a.t;
-  const uint32_t* sm_row = a.u_sm + (size_t)row * a.smw;
+  // the row's sign / mantissa fields come through LDS as well: a field is looked at by up to two
+  // output words, and its two words would otherwise be fetched from memory each time
+  uint32_t* sm_row = reinterpret_cast<uint32_t*>(lds8 + 256 + (((size_t)a.K + 3) & ~(size_t)3) + kExpSlack);
+  {
+    const uint32_t* src = a.u_sm + (size_t)row * a.smw;
+    for (int i = lane; i < a.smw; i += 64) sm_row[i] = src[i];
+    if (lane == 0) sm_row[a.smw] = 0u;  // read_field looks one word ahead
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
   uint32_t* orow = out + (size_t)blockIdx.x * a.sw;
   for (int w = lane; w < a.sw; w += 64) {
     uint32_t word = 0;
@@ -346,7 +355,7 @@ static UnaryArgs make_uargs(const cas_udesc& u, const void* spec_raw, void* uspe
 int launch_unary_expand(cas_ctx* ctx, const cas_udesc& u, const void* uspec, int64_t row0, int nrows, uint32_t* out) {
   const cas_wdesc& d = u.base;
   if (nrows <= 0 || d.sw == 0) return CAS_OK;
-  const size_t lds = 256 + (size_t)((d.K + 3) & ~3) + kExpSlack;
+  const size_t lds = 256 + (size_t)((d.K + 3) & ~3) + kExpSlack + ((size_t)u.smw + 1) * 4;  // codebook, exponents, sm fields
   if (lds > (size_t)ctx->lds_max) return CAS_ENOTSUP;
   UnaryArgs a = make_uargs(u, nullptr, const_cast<void*>(uspec), nullptr);
   static LdsLimit lim;
