@@ -148,6 +148,65 @@ def test_entry_points_added_later_reject_what_they_cannot_do(env):
     assert _code(B, lambda: B.cas_dense_decode_step(ctx0, model0, dense, dev(weights["lm_head"]), kc, kc.clone(), 0, tin)) == B.CAS_ENOMEM
 
 
+def test_exponent_form_entry_points_reject_what_they_cannot_do(env):
+    """cas_gemm_verify_unary, cas_gemm_verify_mx, cas_model_use_unary / _mx and the shared-exponent
+    cache: argument errors come back as codes from the host-side checks; degenerate sizes work."""
+    torch, B, _ = env
+    lib = B._lib()
+    ctx = B.Context(workspace=torch.empty(4 << 20, dtype=torch.uint8, device="cuda"))
+    dev = lambda a: _dev(torch, a)
+    W = synth.weight_matrix(32, 256, seed=3)
+    ew = B.cas_encode_weight(ctx, dev(W), 600, 4)
+    uw, mw = B.cas_unary_encode(ctx, ew), B.cas_mx_encode(ctx, ew)
+    X = dev(synth.activations(256, 2, seed=4))
+    Y = torch.empty((2, 32), dtype=torch.float32, device="cuda")
+
+    for fn, d, spec, verif in ((lib.cas_gemm_verify_unary, uw.desc, uw.uspec, uw.verif),
+                               (lib.cas_gemm_verify_mx, mw.desc, mw.spec, mw.verif)):
+        args = lambda **k: (ctx.h, C.byref(d), k.get("spec", B._ptr(spec)), k.get("verif", B._ptr(verif)),
+                            k.get("X", B._ptr(X)), k.get("ncols", 2), k.get("Y", B._ptr(Y)))
+        assert fn(*args()) == B.CAS_OK
+        assert fn(*args(ncols=0)) == B.CAS_EINVAL and fn(*args(ncols=33)) == B.CAS_EINVAL
+        assert fn(*args(spec=None)) == B.CAS_EINVAL and fn(*args(verif=None)) == B.CAS_EINVAL
+        assert fn(*args(X=None)) == B.CAS_EINVAL and fn(*args(Y=None)) == B.CAS_EINVAL
+        assert fn(*args(spec=spec.data_ptr() + 4)) == B.CAS_EINVAL          # not 256-byte aligned
+        assert fn(None, *args()[1:]) == B.CAS_EINVAL
+    # without a workspace the unary form has nowhere to put its re-coded rows; the shared-exponent form needs none
+    ctx0 = B.Context()
+    assert _code(B, lambda: B.cas_gemm_verify_unary(ctx0, uw, X)) == B.CAS_ENOMEM
+    np.testing.assert_array_equal(B.cas_gemm_verify_mx(ctx0, mw, X).cpu().numpy(),
+                                  B.cas_gemm_verify_mx(ctx, mw, X).cpu().numpy())
+    # an empty matrix
+    e = B.cas_encode_weight(ctx, torch.empty((0, 256), dtype=torch.int16, device="cuda"), 600, 4)
+    assert B.cas_gemm_verify_mx(ctx, B.cas_mx_encode(ctx, e), X).shape == (2, 0)
+    assert B.cas_gemm_verify_unary(ctx, B.cas_unary_encode(ctx, e), X).shape == (2, 0)
+    # the model: a layer or tensor that does not exist, a form of another matrix, a NULL buffer
+    shape = synth.TINY
+    weights = synth.model_weights(shape, seed=1)
+    layers = []
+    for lw in weights["layers"]:
+        L = {n: B.cas_encode_weight(ctx, dev(lw[n]), 600, 4) for n in ("wqkv", "wo", "wgu", "wd")}
+        L["g_attn"], L["g_ffn"] = dev(lw["g_attn"]), dev(lw["g_ffn"])
+        layers.append(L)
+    head = B.cas_encode_weight(ctx, dev(weights["lm_head"]), 600, 4)
+    rope = torch.from_numpy(synth.rope_table(64, shape.head_dim, shape.rope_theta)).cuda()
+    model = B.Model(ctx, shape, layers, head, dev(weights["embed"]), dev(weights["g_final"]), rope, 4)
+    uq, mq = B.cas_unary_encode(ctx, layers[0]["wqkv"]), B.cas_mx_encode(ctx, layers[0]["wqkv"])
+    assert _code(B, lambda: model.use_unary(shape.n_layers, 0, uq)) == B.CAS_EINVAL
+    assert _code(B, lambda: model.use_unary(0, 4, uq)) == B.CAS_EINVAL
+    assert _code(B, lambda: model.use_unary(0, 1, uq)) == B.CAS_EINVAL       # wqkv's form offered for wo
+    assert _code(B, lambda: model.use_mx(0, 3, mq)) == B.CAS_EINVAL          # ... and for wd
+    assert lib.cas_model_use_unary(model.h, 0, 0, C.byref(uq.desc), None) == B.CAS_EINVAL
+    assert lib.cas_model_use_mx(model.h, 0, 0, C.byref(mq.desc), B._ptr(mq.spec), None) == B.CAS_EINVAL
+    assert lib.cas_model_use_unary(None, 0, 0, None, None) == B.CAS_EINVAL
+    model.use_unary(0, 0, uq); model.use_mx(0, 0, mq); model.use_mx(0, 0, None)   # the last call wins; switching off works
+    # the cache: a mode without kernels
+    d = B.cas_kv_desc()
+    d.n_layers, d.n_kv_heads, d.head_dim, d.page_tokens, d.n_pages, d.max_seqs, d.max_pages_per_seq = 1, 1, 128, 64, 1, 1, 1
+    d.fmt = B.cas_fmt(600, 4, 1)
+    assert lib.cas_kv_desc_init(C.byref(d)) == B.CAS_ENOTSUP
+
+
 def test_library_from_a_plain_c_program():
     """tests/c/abi_gpu_roundtrip.c: encode, exact and draft reconstruction, draft GEMV and
     verification GEMM through the C ABI with device memory from the HIP runtime, no Python in the
